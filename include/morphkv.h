@@ -1,0 +1,109 @@
+/*
+ * libmorphkv -- MorphKV's per-decode-step hot path on one MI355X (gfx950).
+ *
+ * What the path computes (paper: Section 3.1 Eq.1, Eq.3-7, Algorithm 1,
+ * Section 3.3; Section 4 "Implementation" for the prompt-time selection):
+ * every decode step, grouped-query attention of the new token over a
+ * constant-size cache of C retained older tokens plus the R most recent ones;
+ * the group-summed attention weights of that token are recorded as the newest
+ * of R rows; the R rows are fused (sum, Eq.5, or max, Eq.6) into one score per
+ * older token; the top-C older tokens are kept (Eq.7) and K/V are compacted in
+ * fixed slots.  The same selection runs once over the whole prompt.
+ *
+ * Conventions
+ *  - unit = one (layer, sequence, KV head); u = (layer*batch + b)*n_kv_heads + h;
+ *    U = n_layers*batch*n_kv_heads independent caches (Section 3.3).
+ *  - every function returns 0 on success or a negative MORPHKV_E* code; nothing
+ *    throws or aborts.  morphkv_last_error() gives the text of the last failure
+ *    on the calling thread.
+ *  - ALL device buffers are caller-owned (sizes from morphkv_sizes); the handle
+ *    is host memory only.  The library allocates no device memory, enqueues all
+ *    work on the caller's stream, and never synchronises.
+ *  - the layouts inside `cache`, `scores_ring` and `scratch` are private; read
+ *    them through the export calls.
+ *  - one handle must not be used from two streams at once: calls on it are
+ *    ordered by the stream they are enqueued on.
+ */
+#ifndef MORPHKV_H
+#define MORPHKV_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MORPHKV_OK 0
+#define MORPHKV_EINVAL (-1) /* bad shape, flag, size or null pointer */
+#define MORPHKV_ESTATE (-2) /* decode before prefill */
+#define MORPHKV_EHIP (-3)   /* a HIP runtime call or kernel launch failed */
+
+#define MORPHKV_FUSION_SUM 0 /* Eq.5 */
+#define MORPHKV_FUSION_MAX 1 /* Eq.6 */
+#define MORPHKV_DTYPE_F32 0
+#define MORPHKV_DTYPE_BF16 1
+
+typedef struct morphkv_config {
+  int32_t n_layers, batch;
+  int32_t n_q_heads;      /* M  (Algorithm 1) */
+  int32_t n_kv_heads;     /* M' ; M % M' == 0; group size G = M/M' must be 1..8 */
+  int32_t head_dim;       /* d_h of Eq.1: 64 or 128 */
+  int32_t C;              /* older tokens retained (Eq.3), >= 1 */
+  int32_t R;              /* recent window (H1), 1..1024 */
+  int32_t fusion;         /* MORPHKV_FUSION_* */
+  int32_t dtype;          /* element type of q/K/V: MORPHKV_DTYPE_* */
+  int32_t evict_every;    /* T of Appendix A.5; this build supports 1 */
+  int32_t max_prompt_len; /* largest Nmax that will be passed to prefill_select */
+  float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */
+} morphkv_config;
+
+typedef struct morphkv_handle morphkv_handle;
+
+/* Bytes the caller must provide (device memory, 256-byte aligned) for a configuration. */
+int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_bytes, size_t *scratch_bytes);
+
+/* Host-only handle over caller-owned DEVICE buffers of at least morphkv_sizes bytes.
+ * The buffers need no initialisation; prefill_select writes all state.  They must
+ * stay valid until morphkv_destroy.  Ownership stays with the caller. */
+int morphkv_create(morphkv_handle **h, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch);
+int morphkv_destroy(morphkv_handle *h);
+
+/* Selection over the prompt (Section 4 "Implementation"; Eq.4-7), once per batch.
+ *  Q_window  device [L][B][M][R][d]   queries of the last min(R,N_b) prompt tokens of each
+ *                                     sequence; row j = query of position N_b - min(R,N_b) + j
+ *  K, V      device [L][B][M'][Nmax][d]  prompt keys/values, rows >= N_b are ignored padding
+ *  prompt_len HOST  [B]               1 <= N_b <= Nmax <= cfg.max_prompt_len
+ * For every unit: causal softmax rows of the window queries over the whole prompt, summed
+ * over the group's heads (Algorithm 1), fused over the rows (Eq.5/6) for the older tokens
+ * k < N_b - min(R,N_b), top-min(C, count) kept (ties keep the lower position), K/V gathered
+ * into the cache, and the recorded rows seeded.  Inputs are only read. */
+int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                           const int32_t *prompt_len, int32_t Nmax, void *stream /* hipStream_t */);
+
+/* One decode step for all units (Eq.1, Algorithm 1, Eq.7).
+ *  q      device [L][B][M][d]    query of the new token
+ *  k_new  device [L][B][M'][d]   its key   (enters the window after the step)
+ *  v_new  device [L][B][M'][d]   its value
+ *  out    device [L][B][M][d]    fp32 attention output over the resident cache plus the token itself
+ * Inputs are only read; cache and scores_ring are updated in place. */
+int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
+                        void *stream /* hipStream_t */);
+
+/* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
+ *  pos    [U][C+R] int32: slots [0,C) = older tokens (-1 = empty), [C,C+R) = window slot (position mod R)
+ *  n_snap [U]      int32: older tokens currently held */
+int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream);
+/* evicted [U] int32 device: position evicted by the last decode step, -1 if none. */
+int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream);
+
+/* Optional capture of the fused scores each decode step takes its decision on:
+ * F device [U][C+1] fp32 (slot order; [C] = the token leaving the window), or NULL to stop.
+ * Costs 4 bytes written per older token per step while enabled. */
+int morphkv_capture_scores(morphkv_handle *h, float *F);
+
+const char *morphkv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,182 @@
+"""Thin ctypes binding over libmorphkv.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch is used here for
+device memory and the current stream.  There is no CPU fallback: if the shared
+library is missing or the tensors are not on a GPU this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmorphkv.so")
+
+OK, EINVAL, ESTATE, EHIP = 0, -1, -2, -3
+FUSION = {"sum": 0, "max": 1}
+DTYPE = {"f32": 0, "bf16": 1}
+_TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
+           "morphkv_export_positions", "morphkv_export_evicted", "morphkv_capture_scores", "morphkv_last_error")
+
+
+class MorphKVError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libmorphkv error {code}: {text}")
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "C", "R", "fusion", "dtype",
+                 "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float)]
+
+
+_lib = None
+
+
+def load_library():
+    """Load the built library; build it first only if no built library is there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    L = C.CDLL(LIB_PATH)
+    vp = C.c_void_p
+    szp = C.POINTER(C.c_size_t)
+    L.morphkv_sizes.argtypes = [C.POINTER(Config), szp, szp, szp]
+    L.morphkv_create.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, vp, vp]
+    L.morphkv_destroy.argtypes = [vp]
+    L.morphkv_prefill_select.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
+    L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
+    L.morphkv_export_evicted.argtypes = [vp, vp, vp]
+    L.morphkv_capture_scores.argtypes = [vp, vp]
+    L.morphkv_last_error.argtypes = []
+    L.morphkv_last_error.restype = C.c_char_p
+    for f in EXPORTS[:-1]:
+        getattr(L, f).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise MorphKVError(rc, load_library().morphkv_last_error().decode())
+
+
+def _dev_ptr(t: torch.Tensor):
+    if not t.is_cuda:
+        raise ValueError("libmorphkv works on device memory only: tensor is on " + str(t.device))
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def make_config(*, n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, fusion, dtype, max_prompt_len,
+                evict_every=1, softmax_scale=0.0) -> Config:
+    return Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, FUSION[fusion], DTYPE[dtype],
+                  evict_every, max_prompt_len, softmax_scale)
+
+
+def morphkv_sizes(cfg: Config):
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(load_library().morphkv_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+class MorphKV:
+    """One handle over caller-owned device buffers (allocated here as torch tensors)."""
+
+    def __init__(self, cfg: Config, device="cuda:0"):
+        self.lib = load_library()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        if self.device.type != "cuda":
+            raise ValueError("libmorphkv needs a GPU device")
+        self.U = cfg.n_layers * cfg.batch * cfg.n_kv_heads
+        self.n = cfg.C + cfg.evict_every - 1 + cfg.R
+        self.dtype = _TORCH_DTYPE["f32" if cfg.dtype == 0 else "bf16"]
+        cb, rb, sb = morphkv_sizes(cfg)
+        self.bytes = (cb, rb, sb)
+        self.cache = torch.empty(cb, dtype=torch.uint8, device=self.device)
+        self.scores_ring = torch.empty(rb, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        _check(self.lib.morphkv_create(C.byref(self._h), C.byref(cfg), _dev_ptr(self.cache),
+                                       _dev_ptr(self.scores_ring), _dev_ptr(self.scratch)))
+        self.out_shape = (cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim)
+        self._scoreF = None
+
+    @classmethod
+    def from_workload(cls, wl, device="cuda:0", **kw):
+        cfg = make_config(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                          head_dim=wl.head_dim, C_=wl.C, R=wl.R, fusion=wl.fusion, dtype=wl.dtype,
+                          max_prompt_len=wl.Nmax, evict_every=wl.evict_every, **kw)
+        return cls(cfg, device)
+
+    def close(self):
+        if self._h:
+            self.lib.morphkv_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self):
+        return C.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _want(self, t, shape):
+        if t.dtype != self.dtype or tuple(t.shape) != tuple(shape):
+            raise ValueError(f"expected {self.dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+    def prefill_select(self, Q_window, K, V, prompt_len):
+        c = self.cfg
+        Nmax = K.shape[3]
+        self._want(Q_window, (c.n_layers, c.batch, c.n_q_heads, c.R, c.head_dim))
+        self._want(K, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        self._want(V, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        pl = (C.c_int32 * c.batch)(*[int(x) for x in prompt_len])
+        _check(self.lib.morphkv_prefill_select(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V), pl, Nmax,
+                                               self._stream()))
+
+    def decode_step(self, q, k_new, v_new, out=None):
+        c = self.cfg
+        self._want(q, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._want(k_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._want(v_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        if out is None:
+            out = torch.empty(self.out_shape, dtype=torch.float32, device=self.device)
+        _check(self.lib.morphkv_decode_step(self._h, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out),
+                                            self._stream()))
+        return out
+
+    def export_positions(self):
+        """(pos [U, C+R] int32, n_snap [U] int32) device tensors."""
+        pos = torch.empty(self.U, self.n, dtype=torch.int32, device=self.device)
+        n_snap = torch.empty(self.U, dtype=torch.int32, device=self.device)
+        _check(self.lib.morphkv_export_positions(self._h, _dev_ptr(pos), _dev_ptr(n_snap), self._stream()))
+        return pos, n_snap
+
+    def export_evicted(self):
+        ev = torch.empty(self.U, dtype=torch.int32, device=self.device)
+        _check(self.lib.morphkv_export_evicted(self._h, _dev_ptr(ev), self._stream()))
+        return ev
+
+    def capture_scores(self, enable=True):
+        """Returns the [U, C+1] fp32 device tensor the next decode steps write their fused scores to."""
+        if enable:
+            self._scoreF = torch.zeros(self.U, self.n - self.cfg.R + 1, dtype=torch.float32, device=self.device)
+            _check(self.lib.morphkv_capture_scores(self._h, _dev_ptr(self._scoreF)))
+        else:
+            _check(self.lib.morphkv_capture_scores(self._h, None))
+            self._scoreF = None
+        return self._scoreF

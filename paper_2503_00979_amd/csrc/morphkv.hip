@@ -1,0 +1,340 @@
+// C-ABI of libmorphkv (see include/morphkv.h): argument checks, buffer carve-up, kernel launches.
+// Host code only enqueues work on the caller's stream; all device memory is the caller's.
+#include "../../include/morphkv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+#include "decode.h"
+#include "prefill.h"
+
+using namespace mkv;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(MORPHKV_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  int U, G, Cs, n, cps, esz;
+  // cache
+  size_t offK, offV, offPos, offMeta, cache_bytes;
+  // scores_ring
+  size_t offRing, offSfx, offNw, ring_bytes;
+  // scratch
+  size_t offSrow, offF, offSel, offPlen, scratch_bytes;
+};
+
+int validate(const morphkv_config *c) {
+  if (!c) return fail(MORPHKV_EINVAL, "config is null");
+  if (c->n_layers < 1 || c->batch < 1) return fail(MORPHKV_EINVAL, "n_layers and batch must be >= 1");
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads)
+    return fail(MORPHKV_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", c->n_q_heads,
+                c->n_kv_heads);
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G > 8) return fail(MORPHKV_EINVAL, "group size %d not supported (1..8)", G);
+  if (c->head_dim != 64 && c->head_dim != 128) return fail(MORPHKV_EINVAL, "head_dim must be 64 or 128");
+  if (c->C < 1) return fail(MORPHKV_EINVAL, "C must be >= 1");
+  if (c->R < 1 || c->R > 1024) return fail(MORPHKV_EINVAL, "R must be in 1..1024");
+  if (c->fusion != MORPHKV_FUSION_SUM && c->fusion != MORPHKV_FUSION_MAX)
+    return fail(MORPHKV_EINVAL, "fusion must be 0 (sum) or 1 (max)");
+  if (c->dtype != MORPHKV_DTYPE_F32 && c->dtype != MORPHKV_DTYPE_BF16)
+    return fail(MORPHKV_EINVAL, "dtype must be 0 (f32) or 1 (bf16)");
+  if (c->evict_every != 1) return fail(MORPHKV_EINVAL, "evict_every must be 1");
+  if (c->max_prompt_len < 1) return fail(MORPHKV_EINVAL, "max_prompt_len must be >= 1");
+  if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale))
+    return fail(MORPHKV_EINVAL, "softmax_scale must be finite and >= 0");
+  const long long U = (long long)c->n_layers * c->batch * c->n_kv_heads;
+  if (U > 65535) return fail(MORPHKV_EINVAL, "too many units (layers*batch*kv_heads must be <= 65535)");
+  if ((long long)c->C + c->R > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
+  return MORPHKV_OK;
+}
+
+Layout make_layout(const morphkv_config *c) {
+  Layout L{};
+  L.U = c->n_layers * c->batch * c->n_kv_heads;
+  L.G = c->n_q_heads / c->n_kv_heads;
+  L.Cs = c->C + c->evict_every - 1;
+  L.n = L.Cs + c->R;
+  L.cps = (L.Cs + c->R - 1) / c->R;
+  L.esz = c->dtype == MORPHKV_DTYPE_F32 ? 4 : 2;
+  const size_t U = (size_t)L.U, n = (size_t)L.n, d = (size_t)c->head_dim, R = (size_t)c->R, Cs = (size_t)L.Cs;
+  size_t o = 0;
+  L.offK = o; o = align_up(o + U * n * d * L.esz);
+  L.offV = o; o = align_up(o + U * n * d * L.esz);
+  L.offPos = o; o = align_up(o + U * n * 4);
+  L.offMeta = o; o = align_up(o + U * META * 4);
+  L.cache_bytes = o;
+  o = 0;
+  L.offRing = o; o = align_up(o + U * R * n * 4);
+  L.offSfx = o; o = align_up(o + U * R * Cs * 4);
+  L.offNw = o; o = align_up(o + U * Cs * 4);
+  L.ring_bytes = o;
+  o = 0;
+  const size_t Nm = (size_t)c->max_prompt_len;
+  L.offSrow = o; o = align_up(o + U * R * Nm * 4);
+  L.offF = o; o = align_up(o + U * Nm * 4);
+  L.offSel = o; o = align_up(o + U * Cs * 4);
+  L.offPlen = o; o = align_up(o + (size_t)c->batch * 4);
+  L.scratch_bytes = o;
+  return L;
+}
+
+}  // namespace
+
+struct morphkv_handle {
+  morphkv_config cfg;
+  Layout L;
+  char *cache, *ring, *scratch;
+  float *dbgF;
+  bool prefilled;
+  float scale_log2;
+  int n_cu;
+};
+
+namespace {
+
+DecodeParams decode_params(const morphkv_handle *h) {
+  DecodeParams P{};
+  const Layout &L = h->L;
+  P.K = h->cache + L.offK;
+  P.V = h->cache + L.offV;
+  P.pos = (int32_t *)(h->cache + L.offPos);
+  P.meta = (int32_t *)(h->cache + L.offMeta);
+  P.ring = (float *)(h->ring + L.offRing);
+  P.sfx = (float *)(h->ring + L.offSfx);
+  P.nw = (float *)(h->ring + L.offNw);
+  P.dbgF = h->dbgF;
+  P.Cs = L.Cs; P.R = h->cfg.R; P.n = L.n; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads;
+  P.fusion = h->cfg.fusion; P.cps = L.cps; P.scale_log2 = h->scale_log2;
+  return P;
+}
+
+PrefillParams prefill_params(const morphkv_handle *h) {
+  PrefillParams P{};
+  const Layout &L = h->L;
+  P.plen = (const int32_t *)(h->scratch + L.offPlen);
+  P.Srow = (float *)(h->scratch + L.offSrow);
+  P.F = (float *)(h->scratch + L.offF);
+  P.sel = (int32_t *)(h->scratch + L.offSel);
+  P.Kc = h->cache + L.offK;
+  P.Vc = h->cache + L.offV;
+  P.pos = (int32_t *)(h->cache + L.offPos);
+  P.meta = (int32_t *)(h->cache + L.offMeta);
+  P.ring = (float *)(h->ring + L.offRing);
+  P.sfx = (float *)(h->ring + L.offSfx);
+  P.nw = (float *)(h->ring + L.offNw);
+  P.B = h->cfg.batch; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads; P.C = h->cfg.C; P.Cs = L.Cs;
+  P.R = h->cfg.R; P.n = L.n; P.fusion = h->cfg.fusion; P.cps = L.cps; P.scale_log2 = h->scale_log2;
+  return P;
+}
+
+// threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
+// over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
+int decode_threads(const morphkv_handle *h) {
+  const int U = h->L.U, cu = h->n_cu > 0 ? h->n_cu : 256;
+  if (U >= 4 * cu) return 256;
+  if (U >= 2 * cu) return 512;
+  return 1024;
+}
+
+template <typename T, int D, int G>
+int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
+  const int NT = decode_threads(h);
+  const size_t lds = decode_lds_bytes(P.n, GPad<G>::v, G, D, NT, P.R);
+  if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
+  auto kern = decode_fused_kernel<T, D, G>;
+  static size_t attr_set = 0;  // per instantiation
+  if (lds > attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = lds;
+  }
+  hipLaunchKernelGGL(kern, dim3(h->L.U), dim3(NT), lds, st, P);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+template <typename T, int D, int G>
+int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
+  const int U = h->L.U;
+  hipLaunchKernelGGL((prefill_rows_kernel<T, D, G>), dim3(P.R, U), dim3(256), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(prefill_fuse_kernel, dim3((P.Nmax + 255) / 256, U), dim3(256), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(prefill_select_kernel, dim3(U), dim3(1024), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
+  hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n + SPB - 1) / SPB, U), dim3(256), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n + 255) / 256, U), dim3(256), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(prefill_state_kernel, dim3((P.Cs + 255) / 256, U), dim3(256), 0, st, P);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+// dispatch over (dtype, head_dim, group size)
+#define MKV_DISPATCH_G(FN, T, D, G, ...)                                      \
+  switch (G) {                                                                \
+    case 1: return FN<T, D, 1>(__VA_ARGS__);                                  \
+    case 2: return FN<T, D, 2>(__VA_ARGS__);                                  \
+    case 3: return FN<T, D, 3>(__VA_ARGS__);                                  \
+    case 4: return FN<T, D, 4>(__VA_ARGS__);                                  \
+    case 5: return FN<T, D, 5>(__VA_ARGS__);                                  \
+    case 6: return FN<T, D, 6>(__VA_ARGS__);                                  \
+    case 7: return FN<T, D, 7>(__VA_ARGS__);                                  \
+    case 8: return FN<T, D, 8>(__VA_ARGS__);                                  \
+    default: return fail(MORPHKV_EINVAL, "group size %d not supported", G);   \
+  }
+
+#define MKV_DISPATCH(FN, h, ...)                                              \
+  do {                                                                        \
+    const int G_ = (h)->L.G, D_ = (h)->cfg.head_dim;                          \
+    if ((h)->cfg.dtype == MORPHKV_DTYPE_BF16) {                               \
+      if (D_ == 128) { MKV_DISPATCH_G(FN, bf16_t, 128, G_, __VA_ARGS__) }     \
+      else { MKV_DISPATCH_G(FN, bf16_t, 64, G_, __VA_ARGS__) }                \
+    } else {                                                                  \
+      if (D_ == 128) { MKV_DISPATCH_G(FN, float, 128, G_, __VA_ARGS__) }      \
+      else { MKV_DISPATCH_G(FN, float, 64, G_, __VA_ARGS__) }                 \
+    }                                                                         \
+  } while (0)
+
+int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
+  MKV_DISPATCH(launch_decode, h, h, P, st);
+}
+int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
+  MKV_DISPATCH(launch_prefill, h, h, P, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *morphkv_last_error(void) { return g_err; }
+
+int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_bytes, size_t *scratch_bytes) {
+  int rc = validate(cfg);
+  if (rc) return rc;
+  const Layout L = make_layout(cfg);
+  if (cache_bytes) *cache_bytes = L.cache_bytes;
+  if (ring_bytes) *ring_bytes = L.ring_bytes;
+  if (scratch_bytes) *scratch_bytes = L.scratch_bytes;
+  return MORPHKV_OK;
+}
+
+int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch) {
+  if (!out) return fail(MORPHKV_EINVAL, "handle pointer is null");
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc) return rc;
+  if (!cache || !scores_ring || !scratch) return fail(MORPHKV_EINVAL, "cache, scores_ring and scratch must be non-null");
+  if (((uintptr_t)cache | (uintptr_t)scores_ring | (uintptr_t)scratch) & 255)
+    return fail(MORPHKV_EINVAL, "buffers must be 256-byte aligned");
+  morphkv_handle *h = new (std::nothrow) morphkv_handle();
+  if (!h) return fail(MORPHKV_EINVAL, "out of host memory");
+  h->cfg = *cfg;
+  h->L = make_layout(cfg);
+  h->cache = (char *)cache;
+  h->ring = (char *)scores_ring;
+  h->scratch = (char *)scratch;
+  h->dbgF = nullptr;
+  h->prefilled = false;
+  const double scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
+  h->scale_log2 = (float)(scale * 1.4426950408889634074);
+  h->n_cu = 0;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+    h->n_cu = prop.multiProcessorCount;
+  else
+    (void)hipGetLastError();
+  *out = h;
+  return MORPHKV_OK;
+}
+
+int morphkv_destroy(morphkv_handle *h) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  delete h;
+  return MORPHKV_OK;
+}
+
+int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                           const int32_t *prompt_len, int32_t Nmax, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!Q_window || !K || !V || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
+  if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
+    return fail(MORPHKV_EINVAL, "Nmax %d outside 1..max_prompt_len (%d)", Nmax, h->cfg.max_prompt_len);
+  for (int b = 0; b < h->cfg.batch; ++b)
+    if (prompt_len[b] < 1 || prompt_len[b] > Nmax)
+      return fail(MORPHKV_EINVAL, "prompt_len[%d] = %d outside 1..Nmax (%d)", b, prompt_len[b], Nmax);
+  hipStream_t st = (hipStream_t)stream;
+  PrefillParams P = prefill_params(h);
+  P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax;
+  HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
+  int rc = dispatch_prefill(h, P, st);
+  if (rc) return rc;
+  h->prefilled = true;
+  return MORPHKV_OK;
+}
+
+int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
+                        void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!q || !k_new || !v_new || !out) return fail(MORPHKV_EINVAL, "null pointer");
+  if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step before prefill_select");
+  DecodeParams P = decode_params(h);
+  P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
+  return dispatch_decode(h, P, (hipStream_t)stream);
+}
+
+int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!pos) return fail(MORPHKV_EINVAL, "pos is null");
+  if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
+  const Layout &L = h->L;
+  hipLaunchKernelGGL(export_positions_kernel, dim3((L.n + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
+                     (const int32_t *)(h->cache + L.offPos), (const int32_t *)(h->cache + L.offMeta), pos, n_snap,
+                     L.n, L.U);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!evicted) return fail(MORPHKV_EINVAL, "evicted is null");
+  if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
+  const Layout &L = h->L;
+  hipLaunchKernelGGL(export_evicted_kernel, dim3((L.U + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                     (const int32_t *)(h->cache + L.offMeta), evicted, L.U);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+int morphkv_capture_scores(morphkv_handle *h, float *F) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  h->dbgF = F;
+  return MORPHKV_OK;
+}
+
+}  // extern "C"

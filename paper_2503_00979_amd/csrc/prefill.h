@@ -1,0 +1,310 @@
+// Selection over the prompt (Section 4 "Implementation"; Eq.4-7): window-query softmax rows over the
+// whole prompt, group sum (Algorithm 1), fusion over the rows, top-C with ties to the lower position,
+// gather into cache slots, and the recorded rows / aggregate state the decode step continues from.
+#pragma once
+#include "common.h"
+#include "decode.h"
+
+namespace mkv {
+
+struct PrefillParams {
+  const void *Qw, *K, *V;  // [L][B][M][R][D], [L][B][M'][Nmax][D] x2
+  const int32_t *plen;     // device [B]
+  float *Srow;             // scratch [U][R][Nmax]: group-summed weights of window query j on key k
+  float *F;                // scratch [U][Nmax]: fused score per older token
+  int32_t *sel;            // scratch [U][Cs]: retained positions, ascending
+  // state written
+  void *Kc, *Vc;
+  int32_t *pos, *meta;
+  float *ring, *sfx, *nw;
+  int32_t B, Mq, Mkv, C, Cs, R, n, Nmax, fusion, cps;
+  float scale_log2;
+};
+
+// ---- P1: one workgroup per (window query j, unit): softmax statistics, then the group-summed row
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
+  constexpr int EPL = Elem<T>::EPL, LPR = D / EPL, RPL = WAVE / LPR, UNR = 4, RPT = RPL * UNR;
+  __shared__ float sm[4][8], sz[4][8];
+  const int j = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, NW = blockDim.x / WAVE;
+  const int wave = tid / WAVE, lane = tid % WAVE, chunk = lane % LPR, rowsub = lane / LPR;
+  const int lb = u / P.Mkv, kh = u % P.Mkv, b = lb % P.B;
+  const int N = P.plen[b], R = P.R, Rw = N < R ? N : R;
+  if (j >= Rw) return;
+  const int pj = N - Rw + j, nk = pj + 1;  // causal: keys 0..pj
+  const T *Kb = (const T *)P.K + (size_t)u * P.Nmax * D;
+
+  float qf[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const T *qp = (const T *)P.Qw + (((size_t)(lb * P.Mq + kh * G + g)) * R + j) * D;
+    uint4 r = ((const uint4 *)qp)[chunk];
+    Elem<T>::unpack(r, qf[g]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[g][e] *= P.scale_log2;
+  }
+
+  auto logits = [&](int tile, float (&l)[UNR][G], bool (&ok)[UNR]) {
+    uint4 r[UNR];
+#pragma unroll
+    for (int i = 0; i < UNR; ++i) {
+      const int k = tile * RPT + i * RPL + rowsub;
+      ok[i] = k < nk;
+      if (ok[i]) r[i] = ((const uint4 *)(Kb + (size_t)k * D))[chunk];
+    }
+#pragma unroll
+    for (int i = 0; i < UNR; ++i) {
+      float kf[EPL];
+      if (ok[i]) Elem<T>::unpack(r[i], kf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float d = 0.f;
+        if (ok[i]) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+        }
+#pragma unroll
+        for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
+        l[i][g] = d;
+      }
+    }
+  };
+
+  // pass A: running (max, sum of exp2) per head
+  float m[G], z[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) { m[g] = -INFINITY; z[g] = 0.f; }
+  for (int tile = wave; tile * RPT < nk; tile += NW) {
+    float l[UNR][G];
+    bool ok[UNR];
+    logits(tile, l, ok);
+#pragma unroll
+    for (int i = 0; i < UNR; ++i)
+      if (ok[i]) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const float mn = fmaxf(m[g], l[i][g]);
+          z[g] = z[g] * exp2f(m[g] - mn) + exp2f(l[i][g] - mn);
+          m[g] = mn;
+        }
+      }
+  }
+  // merge row groups of the wave (lanes of one row group hold identical values), then the waves
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int s = LPR; s < WAVE; s <<= 1) {
+      const float om = __shfl_xor(m[g], s), oz = __shfl_xor(z[g], s);
+      const float mn = fmaxf(m[g], om);
+      const float a = m[g] == -INFINITY ? 0.f : z[g] * exp2f(m[g] - mn);
+      const float c = om == -INFINITY ? 0.f : oz * exp2f(om - mn);
+      z[g] = a + c;
+      m[g] = mn;
+    }
+    if (lane == 0) { sm[wave][g] = m[g]; sz[wave][g] = z[g]; }
+  }
+  __syncthreads();
+  float Mx[G], inv[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mm = -INFINITY;
+    for (int x = 0; x < NW; ++x) mm = fmaxf(mm, sm[x][g]);
+    float zz = 0.f;
+    for (int x = 0; x < NW; ++x) zz += sm[x][g] == -INFINITY ? 0.f : sz[x][g] * exp2f(sm[x][g] - mm);
+    Mx[g] = mm;
+    inv[g] = 1.0f / zz;
+  }
+  // pass B: weights, summed over the group's heads
+  float *Sr = P.Srow + ((size_t)u * R + j) * P.Nmax;
+  for (int tile = wave; tile * RPT < nk; tile += NW) {
+    float l[UNR][G];
+    bool ok[UNR];
+    logits(tile, l, ok);
+#pragma unroll
+    for (int i = 0; i < UNR; ++i) {
+      const int k = tile * RPT + i * RPL + rowsub;
+      if (ok[i] && chunk == 0) {
+        float S = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) S += exp2f(l[i][g] - Mx[g]) * inv[g];
+        Sr[k] = S;
+      }
+    }
+  }
+}
+
+// ---- P2: fused score of every older token (Eq.5 / Eq.6 over the window rows)
+__global__ __launch_bounds__(256) void prefill_fuse_kernel(PrefillParams P) {
+  const int u = blockIdx.y, k = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R, Rw = N < R ? N : R, n_old = N - Rw;
+  if (k >= n_old) return;
+  const float *Sr = P.Srow + (size_t)u * R * P.Nmax;
+  float F = Sr[k];
+  for (int j = 1; j < Rw; ++j) F = fuse2(P.fusion, F, Sr[(size_t)j * P.Nmax + k]);
+  P.F[(size_t)u * P.Nmax + k] = F;
+}
+
+// ---- P3: keep the min(C, n_old) largest scores, ties keep the lower position; ascending positions out.
+// Radix select (4 x 8 bits, scores are non-negative floats so their bit patterns order like integers)
+// finds the value of the C-th largest; an ordered compaction then keeps everything above it and the
+// first few equal to it.
+__global__ __launch_bounds__(1024) void prefill_select_kernel(PrefillParams P) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned s_prefix, s_need;
+  __shared__ int wsum[16][2];
+  __shared__ int carry[2];
+  const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, lane = tid % WAVE, wave = tid / WAVE;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R, Rw = N < R ? N : R, n_old = N - Rw;
+  const float *F = P.F + (size_t)u * P.Nmax;
+  int32_t *sel = P.sel + (size_t)u * P.Cs;
+  const int keep = n_old < P.C ? n_old : P.C;
+  if (tid == 0) {
+    int32_t *m = P.meta + (size_t)u * META;
+    m[0] = keep; m[1] = N; m[2] = -1; m[3] = 0;
+  }
+  if (n_old <= P.C) {
+    for (int k = tid; k < n_old; k += NT) sel[k] = k;
+    return;
+  }
+  if (tid == 0) { s_prefix = 0u; s_need = (unsigned)keep; }
+  __syncthreads();
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 256; i += NT) hist[i] = 0u;
+    __syncthreads();
+    const unsigned prefix = s_prefix;
+    const unsigned himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+    for (int k = tid; k < n_old; k += NT) {
+      const unsigned bits = __float_as_uint(F[k]);
+      if ((bits & himask) == prefix) atomicAdd(&hist[(bits >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned need = s_need, cum = 0u;
+      int bin = 255;
+      for (; bin > 0; --bin) {
+        if (cum + hist[bin] >= need) break;
+        cum += hist[bin];
+      }
+      s_need = need - cum;  // how many are wanted from this bin
+      s_prefix = prefix | ((unsigned)bin << shift);
+    }
+    __syncthreads();
+  }
+  const unsigned tau = s_prefix;  // bit pattern of the C-th largest score
+  const int need_eq = (int)s_need; // how many of the scores equal to it are kept (lowest positions first)
+  if (tid == 0) { carry[0] = 0; carry[1] = 0; }
+  __syncthreads();
+  for (int base = 0; base < n_old; base += NT) {
+    const int k = base + tid;
+    unsigned bits = 0u;
+    if (k < n_old) bits = __float_as_uint(F[k]);
+    const int is_eq = (k < n_old && bits == tau) ? 1 : 0;
+    const int is_gt = (k < n_old && bits > tau) ? 1 : 0;
+    // exclusive rank among equals
+    int xe = is_eq;
+#pragma unroll
+    for (int s = 1; s < WAVE; s <<= 1) { const int o = __shfl_up(xe, s); if (lane >= s) xe += o; }
+    if (lane == WAVE - 1) wsum[wave][0] = xe;
+    __syncthreads();
+    int eoff = carry[0];
+    for (int x = 0; x < wave; ++x) eoff += wsum[x][0];
+    const int eq_rank = eoff + xe - is_eq;
+    const int kept = is_gt | (is_eq && eq_rank < need_eq ? 1 : 0);
+    int xk = kept;
+#pragma unroll
+    for (int s = 1; s < WAVE; s <<= 1) { const int o = __shfl_up(xk, s); if (lane >= s) xk += o; }
+    if (lane == WAVE - 1) wsum[wave][1] = xk;
+    __syncthreads();
+    int koff = carry[1];
+    for (int x = 0; x < wave; ++x) koff += wsum[x][1];
+    if (kept) sel[koff + xk - 1] = k;
+    __syncthreads();
+    if (tid == NT - 1) { carry[0] = eoff + xe; carry[1] = koff + xk; }
+    __syncthreads();
+  }
+}
+
+// source prompt position of cache slot `slot` of a unit after prefill, -1 if empty
+__device__ inline int prefill_slot_source(const PrefillParams &P, int u, int slot, int N, int n_snap) {
+  if (slot < P.Cs) return slot < n_snap ? P.sel[(size_t)u * P.Cs + slot] : -1;
+  const int x = slot - P.Cs, R = P.R;
+  if (N >= R) return N - R + pmod(x - (N - R), R);
+  return x < N ? x : -1;
+}
+
+// ---- P4a: gather K/V rows and positions into the cache slots
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
+  constexpr int LPR = D / Elem<T>::EPL;       // 16-byte pieces per row
+  constexpr int SPB = 256 / (2 * LPR);        // slots per block
+  const int u = blockIdx.y, tid = threadIdx.x;
+  const int slot = blockIdx.x * SPB + tid / (2 * LPR), which = (tid / LPR) & 1, ck = tid % LPR;
+  if (slot >= P.n) return;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b];
+  const int n_snap = P.meta[(size_t)u * META];
+  const int src = prefill_slot_source(P, u, slot, N, n_snap);
+  if (which == 0 && ck == 0) P.pos[(size_t)u * P.n + slot] = src;
+  if (src < 0) return;
+  const T *in = (which ? (const T *)P.V : (const T *)P.K) + ((size_t)u * P.Nmax + src) * D;
+  T *outp = (which ? (T *)P.Vc : (T *)P.Kc) + ((size_t)u * P.n + slot) * D;
+  ((uint4 *)outp)[ck] = ((const uint4 *)in)[ck];
+}
+
+// ---- P4b: recorded rows restricted to the resident columns
+__global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
+  const int u = blockIdx.y, col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= P.n) return;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R, Rw = N < R ? N : R;
+  const int n_snap = P.meta[(size_t)u * META];
+  const int src = prefill_slot_source(P, u, col, N, n_snap);
+  const float *Sr = P.Srow + (size_t)u * R * P.Nmax;
+  float *ringu = P.ring + (size_t)u * R * P.n;
+  for (int r = 0; r < R; ++r) {
+    // the window query whose position is congruent to r, if any
+    int j = -1;
+    if (N >= R) j = pmod(r - (N - R), R);
+    else if (r < N) j = r;
+    float v = 0.f;
+    if (j >= 0 && src >= 0) {
+      const int pj = N - Rw + j;
+      if (src <= pj) v = Sr[(size_t)j * P.Nmax + src];
+    }
+    ringu[(size_t)r * P.n + col] = v;
+  }
+}
+
+// ---- P5: aggregate state of every older-token column, as of the end of step N-1
+__global__ __launch_bounds__(256) void prefill_state_kernel(PrefillParams P) {
+  const int u = blockIdx.y, c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= P.Cs) return;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R;
+  const int n_snap = P.meta[(size_t)u * META];
+  const float *ringu = P.ring + (size_t)u * R * P.n;
+  float *sfxu = P.sfx + (size_t)u * R * P.Cs;
+  float nwv = 0.f;
+  if (c < n_snap) {
+    const int p_end = N - 1;
+    const int p0 = last_rebuild_before(p_end, c / P.cps, R);
+    nwv = column_scan(
+        p_end, p0, R, P.fusion, [&](int t) { return t >= 0 ? ringu[(size_t)pmod(t, R) * P.n + c] : 0.f; },
+        [&](int r, float x) { sfxu[(size_t)r * P.Cs + c] = x; });
+  } else {
+    for (int r = 0; r < R; ++r) sfxu[(size_t)r * P.Cs + c] = 0.f;
+  }
+  P.nw[(size_t)u * P.Cs + c] = nwv;
+}
+
+// ---- exports
+__global__ void export_positions_kernel(const int32_t *pos, const int32_t *meta, int32_t *out_pos,
+                                        int32_t *out_nsnap, int n, int U) {
+  const int u = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out_pos[(size_t)u * n + i] = pos[(size_t)u * n + i];
+  if (i == 0 && out_nsnap) out_nsnap[u] = meta[(size_t)u * META];
+  (void)U;
+}
+__global__ void export_evicted_kernel(const int32_t *meta, int32_t *out, int U) {
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u < U) out[u] = meta[(size_t)u * META + 2];
+}
+
+}  // namespace mkv

@@ -1,0 +1,82 @@
+"""CPU-only checks: the C-ABI library loads and exports every symbol the header declares; host-side
+validation; the seeded generators are reproducible and slice-consistent."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_00979_amd import binding, inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "morphkv.h")).read()
+    declared = set(re.findall(r"\b(morphkv_[a-z_]+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS)
+    lib = binding.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_oracle_exports(oracle_lib):
+    hdr = open(os.path.join(ROOT, "oracle", "morphkv_ref.h")).read()
+    declared = set(re.findall(r"\b(morphkv_ref_[a-z_]+)\s*\(", hdr))
+    lib = oracle_lib.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_sizes_and_validation_on_host():
+    cfg = binding.make_config(n_layers=1, batch=32, n_q_heads=32, n_kv_heads=8, head_dim=128, C_=2048, R=128,
+                              fusion="sum", dtype="bf16", max_prompt_len=8192)
+    cb, rb, sb = binding.morphkv_sizes(cfg)
+    U, n = 256, 2176
+    assert cb >= 2 * U * n * 128 * 2 + U * n * 4
+    assert rb >= U * 128 * n * 4
+    assert cb % 256 == 0 and rb % 256 == 0 and sb % 256 == 0
+    bad = [dict(n_q_heads=33), dict(head_dim=96), dict(C_=0), dict(R=0), dict(R=2000), dict(fusion_="x"),
+           dict(evict_every=0), dict(max_prompt_len=0), dict(n_q_heads=72, n_kv_heads=8)]
+    base = dict(n_layers=1, batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, C_=16, R=4, fusion="sum",
+                dtype="bf16", max_prompt_len=64)
+    for b in bad:
+        kw = dict(base)
+        if "fusion_" in b:
+            c = binding.make_config(**kw)
+            c.fusion = 7
+        else:
+            kw.update(b)
+            c = binding.make_config(**kw)
+        with pytest.raises(binding.MorphKVError) as e:
+            binding.morphkv_sizes(c)
+        assert e.value.code == binding.EINVAL
+        assert binding.load_library().morphkv_last_error()
+
+
+def test_generator_is_counter_based():
+    a = inputs.normal(5, 3, (1000,))
+    b = inputs.normal(5, 3, (400,), offset=600)
+    assert torch.equal(a[600:], b)
+    assert not torch.equal(a, inputs.normal(6, 3, (1000,)))
+    big = inputs.normal(1, 1, (200000,))
+    assert abs(float(big.mean())) < 0.01 and abs(float(big.std()) - 1.0) < 0.01
+
+
+def test_workload_shapes_and_subsets():
+    wl = inputs.workload("c3")
+    assert wl.n_units == 256 and wl.G == 4 and len(wl.prompt_lens) == 32
+    assert all(1024 <= x <= 8192 for x in wl.prompt_lens)
+    assert inputs.workload("c5").G == 7 and inputs.workload("c4").n_units == 2048
+    s = inputs.small_workload(9, L=2, B=3, M=4, Mkv=2, d=16, dtype="bf16", C=4, R=3, prompt_lens=(5, 9, 7), steps=2,
+                              n_outlier_channels=2)
+    Q, K, V = s.prompt()
+    Qs, Ks, Vs = s.prompt(batch_index=[2, 0])
+    assert torch.equal(Ks[:, 0], K[:, 2]) and torch.equal(Qs[:, 1], Q[:, 0]) and torch.equal(Vs[:, 0], V[:, 2])
+    q, k, v = s.decode_inputs(1)
+    qs, ks, vs = s.decode_inputs(1, batch_index=[2, 0])
+    assert torch.equal(qs[:, 0], q[:, 2]) and torch.equal(ks[:, 1], k[:, 0])
+    sc = s.key_channel_scale()
+    assert int((sc == 5.0).sum()) <= 2 * 2 * 2 and int((sc == 5.0).sum()) >= 2 * 2

@@ -1,0 +1,143 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the same seeded inputs.
+
+Bars (written here as the tests enforce them):
+  * retained positions: bit-exact, except near-ties at the top-C boundary (< 1e-5 relative in the
+    oracle's scores), which are adopted and counted;
+  * attention output: max abs error <= 2e-3 for bf16 inputs (fp32 accumulation), <= 1e-5 for fp32;
+  * fused scores (where captured): relative error <= 1e-5 against the oracle's fp64 scores.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_00979_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _lockstep(*a, **k):
+    from lockstep import LockStep
+    return LockStep(*a, **k)
+
+
+def _report(name, rep):
+    print(f"[{name}] steps={rep.steps} evictions={rep.evictions} near_ties(prefill/decode)="
+          f"{rep.near_ties_prefill}/{rep.near_ties_decode} max_out_err={rep.max_out_err:.3e} "
+          f"max_score_rel_err={rep.max_score_rel_err:.3e}", flush=True)
+
+
+SMALL = [
+    # id, kwargs
+    ("f32_g4_d64", dict(L=1, B=2, M=8, Mkv=2, d=64, dtype="f32", C=40, R=16, fusion="sum", prompt_lens=(100, 70), steps=80)),
+    ("f32_g1_d128_max", dict(L=2, B=1, M=2, Mkv=2, d=128, dtype="f32", C=33, R=7, fusion="max", prompt_lens=(64,), steps=60)),
+    ("bf16_g2_d64", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=50, R=9, fusion="sum", prompt_lens=(90, 61), steps=70)),
+    ("bf16_g3_d128", dict(L=1, B=1, M=6, Mkv=2, d=128, dtype="bf16", C=64, R=16, fusion="max", prompt_lens=(200,), steps=70)),
+    ("bf16_g7_d128", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(300, 150), steps=60)),
+    ("bf16_g8_d128", dict(L=1, B=1, M=8, Mkv=1, d=128, dtype="bf16", C=70, R=10, fusion="sum", prompt_lens=(111,), steps=60)),
+    ("bf16_g5_d64", dict(L=1, B=1, M=5, Mkv=1, d=64, dtype="bf16", C=30, R=6, fusion="sum", prompt_lens=(77,), steps=50)),
+    ("bf16_g6_d128", dict(L=1, B=1, M=12, Mkv=2, d=128, dtype="bf16", C=30, R=6, fusion="max", prompt_lens=(77,), steps=50)),
+    # ragged / degenerate: prompt shorter than R, shorter than C+R (cache fills during decode), C = 1, R = 1
+    ("short_prompts", dict(L=1, B=4, M=4, Mkv=2, d=64, dtype="f32", C=12, R=8, fusion="sum", prompt_lens=(1, 5, 8, 17), steps=60)),
+    ("c_is_1", dict(L=1, B=1, M=4, Mkv=1, d=64, dtype="bf16", C=1, R=5, fusion="max", prompt_lens=(30,), steps=40)),
+    ("r_is_1", dict(L=1, B=1, M=4, Mkv=2, d=64, dtype="f32", C=9, R=1, fusion="sum", prompt_lens=(30,), steps=40)),
+    ("r_gt_c", dict(L=1, B=1, M=2, Mkv=1, d=64, dtype="f32", C=3, R=40, fusion="sum", prompt_lens=(100,), steps=90)),
+    ("many_units", dict(L=3, B=5, M=8, Mkv=4, d=64, dtype="bf16", C=21, R=4, fusion="sum", prompt_lens=(30, 9, 50, 26, 3), steps=40)),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_shapes(case, oracle_lib):
+    name, kw = case
+    wl = inputs.small_workload(1000 + SMALL.index(case), **kw)
+    ls = _lockstep(wl, DEV, capture_scores=True).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report(name, rep)
+    assert rep.max_score_rel_err <= 1e-5
+
+
+def test_c1_full(oracle_lib):
+    """c1: toy single layer, fp32, all 64 steps, every unit."""
+    wl = inputs.workload("c1")
+    ls = _lockstep(wl, DEV, capture_scores=True).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report("c1", rep)
+    assert rep.evictions == wl.steps * wl.n_units
+    assert rep.max_score_rel_err <= 1e-5
+
+
+def test_c2_full(oracle_lib):
+    """c2: 8B-shaped layer, batch 1, outlier key channels, max fusion, all 2048 steps, every unit."""
+    wl = inputs.workload("c2")
+    ls = _lockstep(wl, DEV).prefill()
+    rep = ls.run(wl.steps, check_every=64)
+    _report("c2", rep)
+    assert rep.evictions == wl.steps * wl.n_units
+
+
+def test_c3_sampled_units_full_size(oracle_lib):
+    """c3 at full size on the GPU (batch 32, ragged prompts 1k-8k, C=2048, R=128, sum fusion) in the launch
+    configuration the benchmark times; the oracle follows a sample of sequences (shortest prompt, whose
+    cache is still filling, and the longest) step by step."""
+    wl = inputs.workload("c3")
+    lens = list(wl.prompt_lens)
+    sample = sorted({lens.index(min(lens)), lens.index(max(lens))})
+    ls = _lockstep(wl, DEV, batch_index=sample, gen_device=DEV).prefill()
+    rep = ls.run(256, check_every=32)
+    _report("c3", rep)
+
+
+def test_c4_sampled_units_full_size(oracle_lib):
+    """c4: 32 layers x batch 8, per-layer independent selection; oracle follows one sequence (all layers)."""
+    wl = inputs.workload("c4")
+    ls = _lockstep(wl, DEV, batch_index=[3], gen_device=DEV).prefill()
+    rep = ls.run(96, check_every=32)
+    _report("c4", rep)
+
+
+def test_c5_sampled_units_full_size(oracle_lib):
+    """c5: wide GQA (G=7), batch 64, 16k prompts, C=4096, R=256, max fusion; prefill_select over the full
+    prompt plus decode; oracle follows one sequence."""
+    wl = inputs.workload("c5")
+    ls = _lockstep(wl, DEV, batch_index=[17], gen_device=DEV).prefill()
+    rep = ls.run(64, check_every=32)
+    _report("c5", rep)
+
+
+def test_rerun_is_bit_identical(oracle_lib):
+    """The in-place compaction is the only write-after-read hazard: two runs must agree bit for bit."""
+    from paper_2503_00979_amd import binding
+    wl = inputs.small_workload(4242, L=1, B=3, M=8, Mkv=2, d=128, dtype="bf16", C=96, R=16, fusion="sum",
+                               prompt_lens=(300, 40, 120), steps=80)
+    res = []
+    for _ in range(2):
+        g = binding.MorphKV.from_workload(wl, DEV)
+        Qw, K, V = (t.to(DEV) for t in wl.prompt())
+        g.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())
+        outs = []
+        for t in range(wl.steps):
+            q, k, v = (x.to(DEV) for x in wl.decode_inputs(t))
+            outs.append(g.decode_step(q, k, v).clone())
+        pos, ns = g.export_positions()
+        res.append((torch.stack(outs).cpu(), pos.cpu(), ns.cpu()))
+    assert torch.equal(res[0][0], res[1][0])
+    assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
+
+
+def test_error_paths(oracle_lib):
+    from paper_2503_00979_amd import binding
+    with pytest.raises(binding.MorphKVError) as e:
+        binding.morphkv_sizes(binding.make_config(n_layers=1, batch=1, n_q_heads=3, n_kv_heads=2, head_dim=64,
+                                                  C_=4, R=2, fusion="sum", dtype="f32", max_prompt_len=8))
+    assert e.value.code == binding.EINVAL
+    wl = inputs.small_workload(7, L=1, B=1, M=2, Mkv=1, d=64, dtype="f32", C=4, R=2, prompt_lens=(8,), steps=1)
+    g = binding.MorphKV.from_workload(wl, DEV)
+    q, k, v = (x.to(DEV) for x in wl.decode_inputs(0))
+    with pytest.raises(binding.MorphKVError) as e:
+        g.decode_step(q, k, v)
+    assert e.value.code == binding.ESTATE
+    Qw, K, V = (t.to(DEV) for t in wl.prompt())
+    with pytest.raises(binding.MorphKVError) as e:
+        g.prefill_select(Qw, K, V, [9])
+    assert e.value.code == binding.EINVAL
