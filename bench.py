@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the MorphKV decode hot path on one MI355X.
+
+A "step" is one morphkv_decode_step call over all units of the workload: attention of the new token
+over the C+R resident tokens, recording the row, score fusion, top-C selection and K/V compaction.
+Default workload: c3 (Llama-3.1-8B-shaped layer, batch 32, C=2048, R=128, sum fusion, bf16), measured
+in steady state (every cache full), inputs resident in HBM before the timed region.
+
+Prints ONE JSON line (see the keys below).  `roofline` prices the fused decode kernel against the HBM
+peak using the algorithmic bytes per step; `cpu_baseline` is the CPU oracle timed on a bounded sample
+of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes_per_step(wl) -> int:
+    """Bytes the method must move per decode step in steady state (per unit, times U):
+    K and V of the C+R resident tokens read once; the new row of recorded weights written;
+    the score state (one aggregate row read, the running aggregate read and written);
+    q, k_new, v_new in, the new token's K/V written, fp32 output; one K/V row moved and one
+    column of the R rows moved on compaction."""
+    n, d, s, G, C, R = wl.C + wl.R, wl.head_dim, wl.elem_bytes, wl.G, wl.C, wl.R
+    per_unit = (2 * n * d * s) + 4 * n + 12 * (C + 1) + (G + 4) * d * s + 4 * G * d + 4 * d * s + 8 * R
+    return per_unit * wl.n_units
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch of the decode kernel measured with rocprofv3 counters (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", f"decode_fused_{name}_hbm_traffic.json")
+    if os.path.exists(path):
+        with open(path) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    return None
+
+
+def cpu_baseline(wl, Qw, K, V, dec_inputs, n_steps=12):
+    """The oracle as it stands, on a bounded sample: sequences whose cache is full right after the
+    prompt (steady state from the first step), all their KV heads."""
+    import torch
+    from oracle import ref as oref
+    full = [b for b in range(wl.batch) if wl.prompt_lens[b] - wl.R >= wl.C]
+    sample = full[:4] if len(full) >= 4 else (full or [0])
+    wl_s = wl.with_batch_subset(sample)
+    ix = torch.tensor(sample, device=K.device)
+    Qs, Ks, Vs = (t.index_select(1, ix).cpu().contiguous() for t in (Qw, K, V))
+    o = oref.RefMorphKV.from_workload(wl_s)
+    t0 = time.perf_counter()
+    o.prefill_select(Qs, Ks, Vs, wl_s.prompt_len_tensor().numpy())
+    t_prefill = time.perf_counter() - t0
+    ins = []
+    for t in range(n_steps):
+        q, k, v = dec_inputs(t)
+        ins.append(tuple(x.index_select(1, ix).cpu().contiguous() for x in (q, k, v)))
+    t0 = time.perf_counter()
+    for q, k, v in ins:
+        o.decode_step(q, k, v)
+    dt = time.perf_counter() - t0
+    frac = wl_s.n_units / wl.n_units
+    return {
+        "value": (n_steps / dt) * frac, "unit": "steps/s", "cores": oref.num_threads(), "kind": "oracle",
+        "sample": f"{len(sample)} of {wl.batch} sequences ({wl_s.n_units} of {wl.n_units} units), {n_steps} "
+                  f"steady-state decode steps in {dt:.2f}s, scaled by {frac:.4f} to the full batch; "
+                  f"oracle prefill of the sample took {t_prefill:.1f}s (not in value)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repetitions of --steps; the median is reported")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (units are independent caches; there is no collective to "
+              "measure). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_00979_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    wl = inputs.workload(args.workload)
+    K_steps, W = args.steps, args.warmup
+
+    # ---- setup (untimed): prompts, prompt-time selection, run until every cache is full
+    g = binding.MorphKV.from_workload(wl, dev)
+    Qw, K, V = wl.prompt(dev)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())
+    e1.record()
+    torch.cuda.synchronize()
+    prefill_ms = e0.elapsed_time(e1)
+    fill_steps = max(0, max(wl.C + wl.R - n for n in wl.prompt_lens))
+    step_no = 0
+    out = torch.empty(g.out_shape, dtype=torch.float32, device=dev)
+
+    def dec_inputs(t):
+        return wl.decode_inputs(t, dev)
+
+    for _ in range(fill_steps):
+        q, k, v = dec_inputs(step_no)
+        g.decode_step(q, k, v, out)
+        step_no += 1
+    torch.cuda.synchronize()
+    pos, n_snap = g.export_positions()
+    assert int(n_snap.min()) == wl.C, "not in steady state"
+
+    # ---- inputs of the timed region, resident in HBM (a pool that is cycled if K is large)
+    pool = min(K_steps + W, 512)
+    qs, ks, vs = [], [], []
+    for t in range(pool):
+        q, k, v = dec_inputs(step_no + t)
+        qs.append(q); ks.append(k); vs.append(v)
+    Qp, Kp, Vp = torch.stack(qs), torch.stack(ks), torch.stack(vs)
+    del qs, ks, vs
+    stream = torch.cuda.current_stream(dev)
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    qb, kb, vb = Qp[0].numel() * Qp.element_size(), Kp[0].numel() * Kp.element_size(), Vp[0].numel() * Vp.element_size()
+    qptr = [ctypes.c_void_p(Qp.data_ptr() + i * qb) for i in range(pool)]
+    kptr = [ctypes.c_void_p(Kp.data_ptr() + i * kb) for i in range(pool)]
+    vptr = [ctypes.c_void_p(Vp.data_ptr() + i * vb) for i in range(pool)]
+    optr = ctypes.c_void_p(out.data_ptr())
+
+    def run(nsteps, start):
+        for i in range(nsteps):
+            j = (start + i) % pool
+            g.decode_step_ptrs(qptr[j], kptr[j], vptr[j], optr, sp)
+
+    run(W, 0)
+    torch.cuda.synchronize()
+    times = []
+    for r in range(max(1, args.repeats)):
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        run(K_steps, W + r * K_steps)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        times.append((ev0.elapsed_time(ev1) / 1e3, wall))
+    times.sort()
+    dev_s, wall_s = times[len(times) // 2]
+    sec = max(dev_s, 0.0)                      # HIP events on the launch stream bracket exactly the K kernels
+    ms_per_step = sec / K_steps * 1e3
+    A = algorithmic_bytes_per_step(wl)
+    achieved = A / (sec / K_steps) / 1e9
+    res = {
+        "metric": "decode steps/s incl. KV selection (B=32, 8B shape) on 1 GPU; % HBM roofline",
+        "value": K_steps / sec, "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: L={wl.n_layers} B={wl.batch} M={wl.n_q_heads} M'={wl.n_kv_heads} "
+                               f"d={wl.head_dim} C={wl.C} R={wl.R} fusion={wl.fusion} {wl.dtype}, steady state",
+                   "units": wl.n_units, "fill_steps": fill_steps, "repeats": args.repeats,
+                   "wall_ms_per_step": wall_s / K_steps * 1e3, "prefill_select_ms": prefill_ms,
+                   "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),
+                     "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A,
+                     "avg_launch_us": sec / K_steps * 1e6},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, Qw, K, V, lambda t: dec_inputs(step_no + t))
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

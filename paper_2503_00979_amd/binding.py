@@ -159,6 +159,12 @@ class MorphKV:
                                             self._stream()))
         return out
 
+    def decode_step_ptrs(self, q_ptr: int, k_ptr: int, v_ptr: int, out_ptr: int, stream_ptr: int):
+        """Same call with raw device addresses (no shape checks): for tight loops over pre-checked tensors."""
+        rc = self.lib.morphkv_decode_step(self._h, q_ptr, k_ptr, v_ptr, out_ptr, stream_ptr)
+        if rc != OK:
+            _check(rc)
+
     def export_positions(self):
         """(pos [U, C+R] int32, n_snap [U] int32) device tensors."""
         pos = torch.empty(self.U, self.n, dtype=torch.int32, device=self.device)
