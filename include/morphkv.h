@@ -101,6 +101,11 @@ int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream);
  * Costs 4 bytes written per older token per step while enabled. */
 int morphkv_capture_scores(morphkv_handle *h, float *F);
 
+/* Diagnostics: clocks device [U][8] int64, or NULL to stop.  While set, every decode step stores the
+ * constant-rate device clock (100 MHz) per unit at: 0 kernel start, 1 end of the K pass, 2 end of
+ * softmax/record, 3 end of the V pass, 4 end of the step. */
+int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks);
+
 const char *morphkv_last_error(void);
 
 #ifdef __cplusplus

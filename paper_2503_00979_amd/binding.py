@@ -20,7 +20,8 @@ DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
-           "morphkv_export_positions", "morphkv_export_evicted", "morphkv_capture_scores", "morphkv_last_error")
+           "morphkv_export_positions", "morphkv_export_evicted", "morphkv_capture_scores",
+           "morphkv_capture_phase_clocks", "morphkv_last_error")
 
 
 class MorphKVError(RuntimeError):
@@ -57,6 +58,7 @@ def load_library():
     L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
     L.morphkv_export_evicted.argtypes = [vp, vp, vp]
     L.morphkv_capture_scores.argtypes = [vp, vp]
+    L.morphkv_capture_phase_clocks.argtypes = [vp, vp]
     L.morphkv_last_error.argtypes = []
     L.morphkv_last_error.restype = C.c_char_p
     for f in EXPORTS[:-1]:
@@ -186,3 +188,13 @@ class MorphKV:
             _check(self.lib.morphkv_capture_scores(self._h, None))
             self._scoreF = None
         return self._scoreF
+
+    def capture_phase_clocks(self, enable=True):
+        """[U, 8] int64 device tensor of per-unit phase time stamps of the next decode steps (100 MHz clock)."""
+        if enable:
+            self._clocks = torch.zeros(self.U, 8, dtype=torch.int64, device=self.device)
+            _check(self.lib.morphkv_capture_phase_clocks(self._h, _dev_ptr(self._clocks)))
+        else:
+            _check(self.lib.morphkv_capture_phase_clocks(self._h, None))
+            self._clocks = None
+        return self._clocks

@@ -1,14 +1,22 @@
 // Fused MorphKV decode step: one workgroup per unit (layer, sequence, KV head).
 //
 // Per unit and step (Eq.1, Algorithm 1, Eq.4-7):
-//   K pass   : logits of the G query heads against every resident slot (wave-level split over slots)
-//   softmax  : exact max / sum over slots + the token itself; weights stay in LDS
+//   K pass   : logits of the G query heads against every resident slot; waves take slot tiles from a
+//              shared counter, so the pass is a wave-level split over the cache
+//   softmax  : exact max / sum over slots + the token itself; fp32 weights stay in LDS
 //   record   : S[j] = sum_g p_g[j] -> newest ring row; per-column running aggregate and fused score
 //   V pass   : O_g = sum_j p_g[j] V_j + p_g[self] v_new
 //   select   : evict argmin fused score among C older tokens + the token leaving the window
 //              (ties evict the higher position), or append while fewer than C are held
 //   compact  : token leaving the window takes the freed slot (K, V, position, its column of the R rows,
 //              its aggregate state); the new token takes the window slot.
+//
+// Two data paths:
+//   bf16 : K and V live in MFMA-operand tile order (see TiledLayout) so that a wave reads 1 KB
+//          contiguous per load and feeds v_mfma_f32_16x16x32_bf16 directly; Q.K^T and P.V are dense
+//          enough across the G grouped heads only in the sense that the matrix core makes the
+//          arithmetic free next to the HBM stream -- the bound stays HBM.
+//   fp32 : row-major K/V, plain fp32 FMAs (small/toy configurations).
 #pragma once
 #include "common.h"
 
@@ -16,8 +24,11 @@ namespace mkv {
 
 constexpr int META = 4;  // per unit: n_snap, next_pos, last_evicted, reserved
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
 struct DecodeParams {
-  void *K, *V;             // [U][n][D]
+  void *K, *V;             // per unit n_pad * D elements, layout by element type (see Layout<>)
   int32_t *pos;            // [U][n]
   int32_t *meta;           // [U][META]
   float *ring;             // [U][R][n]   recorded rows, row index = query position mod R
@@ -26,157 +37,380 @@ struct DecodeParams {
   const void *q, *k_new, *v_new;
   float *out;
   float *dbgF;             // nullable: [U][Cs+1]
-  int32_t Cs, R, n, Mq, Mkv, fusion, cps;
+  long long *dbgT;         // nullable: [U][8] phase time stamps (diagnostics)
+  int32_t Cs, R, n, n_pad, Mq, Mkv, fusion, cps;
   float scale_log2;        // softmax scale * log2(e)
 };
 
-template <int G> struct GPad { static constexpr int v = G <= 1 ? 1 : G <= 2 ? 2 : G <= 4 ? 4 : 8; };
+// ---- cache layouts -----------------------------------------------------------------------------------
+// Element offset of (slot j, channel ch) inside one unit's K or V array of n_pad slots.
+template <typename T, int D> struct Layout;
 
-// LDS floats needed by decode_fused_kernel
-inline size_t decode_lds_bytes(int n, int GPv, int G, int D, int NT, int R) {
-  size_t lg = (size_t)n * GPv, om = (size_t)(NT / 64) * G * D;
-  size_t fl = (lg > om ? lg : om) + 16 * 8 * 2 + 8 + (size_t)R + 16 * 3 + 8 + 4;
+// fp32: row-major [slot][channel]
+template <int D> struct Layout<float, D> {
+  static constexpr bool tiled = false;
+  __device__ __host__ static inline size_t k_off(int j, int ch) { return (size_t)j * D + ch; }
+  __device__ __host__ static inline size_t v_off(int j, int ch) { return (size_t)j * D + ch; }
+};
+
+// bf16: MFMA 16x16x32 operand order.
+//  K: tiles of 16 slots; inside a tile [k-block of 32 channels][8-channel group kq][slot m][8 channels]:
+//     lane l = kq*16 + m of a wave reads its A-operand fragment of k-block kb at tile + kb*512 + l*8.
+//  V: tiles of 32 slots; inside a tile [16-channel block cb][8-slot group kq][channel nn][8 slots]:
+//     lane l = kq*16 + nn reads its B-operand fragment of channel block cb at tile + cb*512 + l*8.
+template <int D> struct Layout<bf16_t, D> {
+  static constexpr bool tiled = true;
+  static constexpr int KB = D / 32, CB = D / 16;
+  __device__ __host__ static inline size_t k_off(int j, int ch) {
+    return ((((size_t)(j >> 4) * KB + (ch >> 5)) * 4 + ((ch & 31) >> 3)) * 16 + (j & 15)) * 8 + (ch & 7);
+  }
+  __device__ __host__ static inline size_t v_off(int j, int ch) {
+    return ((((size_t)(j >> 5) * CB + (ch >> 4)) * 4 + ((j & 31) >> 3)) * 16 + (ch & 15)) * 8 + (j & 7);
+  }
+};
+
+constexpr int MAXJ = 5;  // columns per thread whose state is prefetched before the K pass
+
+// LDS bytes of decode_fused_kernel
+inline size_t decode_lds_bytes(int n, int n_pad, int G, int D, int NT, int R, int cps) {
+  size_t lg = (size_t)G * n_pad, om = (size_t)(NT / 64) * G * D;
+  size_t fl = (lg > om ? lg : om) + (size_t)cps + (size_t)R + 16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
   return fl * 4;
+}
+
+__device__ inline bool slot_valid(int j, int n_snap, int Cs, int nwin) {
+  return j < n_snap || (j >= Cs && j < Cs + nwin);
+}
+
+// One wave rebuilds the aggregate state of the columns whose turn it is at the start of step p
+// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1, and prefetches the column of the
+// token that leaves the window.  turn[cc] receives f(rows p-R+1..p-1) of column c0+cc.
+//
+// Lanes are laid out as (column cc, row group q): a lane holds rows i = q, q+Q, q+2Q, ... (row i is the
+// row of step p-1-i), so that one load instruction reads Q rows x CP consecutive columns.  Each round
+// scans Q consecutive rows across the row groups with wave shuffles and carries the running aggregate.
+__device__ inline void rebuild_turn_columns(int lane, int p, int n_snap, int R, int n, int Cs, int cps, int fusion,
+                                            const float *ringu, float *sfxu, float *nwu, float *turn,
+                                            float *colv, bool win_full, int w) {
+  const int phi = pmod(p - 1, R), c0 = phi * cps;
+  int ncol = n_snap - c0;
+  ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
+  // column of the token leaving the window (rows p-R+1 .. p-1), oldest first
+  {
+    int r = pmod(p - R + 1 + lane, R);
+    for (int a = lane; a < R - 1; a += WAVE) {
+      colv[a] = win_full ? ringu[(size_t)r * n + Cs + w] : 0.f;
+      r += WAVE;
+      while (r >= R) r -= R;
+    }
+  }
+  constexpr int B = 32;  // rounds per batch: all loads of a batch are in flight together
+  for (int cg = 0; cg < ncol; cg += WAVE) {
+    const int nc = ncol - cg < WAVE ? ncol - cg : WAVE;
+    int CP = 1, lg2 = 0;
+    while (CP < nc) { CP <<= 1; ++lg2; }
+    const int Q = WAVE >> lg2;
+    const int cc = lane & (CP - 1), q = lane >> lg2;
+    const bool colok = cc < nc;
+    const int c = c0 + cg + cc;
+    int r_ld = pmod(p - 1 - q, R);  // ring row of row i = q
+    int r_st = pmod(p - 2 - q, R);  // sfx row its aggregate is read from (at step p-1-i+R-1)
+    float carry = 0.f;
+    const int rounds = (R - 1 + Q - 1) / Q;
+    for (int k0 = 0; k0 < rounds; k0 += B) {
+      float v[B];
+#pragma unroll
+      for (int k = 0; k < B; ++k) {
+        const int i = q + Q * (k0 + k);
+        v[k] = 0.f;
+        if (colok && i < R - 1) v[k] = ringu[(size_t)r_ld * n + c];
+        r_ld -= Q;
+        while (r_ld < 0) r_ld += R;
+      }
+#pragma unroll
+      for (int k = 0; k < B; ++k) {
+        if (k0 + k < rounds) {
+          const int i = q + Q * (k0 + k);
+          float x = v[k];
+          for (int s = CP; s < WAVE; s <<= 1) {
+            const float o = __shfl_up(x, s);
+            if (lane >= s) x = fuse2(fusion, x, o);
+          }
+          x = fuse2(fusion, x, carry);
+          if (colok && i < R - 1) sfxu[(size_t)r_st * Cs + c] = x;
+          carry = __shfl(x, (Q - 1) * CP + cc);
+          r_st -= Q;
+          while (r_st < 0) r_st += R;
+        }
+      }
+    }
+    if (colok && q == 0) {
+      sfxu[(size_t)pmod(p - 1, R) * Cs + c] = 0.f;
+      nwu[c] = 0.f;
+      turn[cg + cc] = carry;
+    }
+  }
+}
+
+// One wave computes the aggregate state of a single column from its R row values colv[a] (row of step
+// p-R+1+a), as of the end of step p with rebuild point p0 (same result as column_scan), and stores it.
+__device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion, const float *colv, float *sfx_col,
+                                      int Cs, float *nw_out) {
+  const int a0 = p0 - (p - R + 1);  // row index of the rebuild point, in [-1, R-2]
+  // new part: rows after the rebuild point
+  float nwv = 0.f;
+  for (int a = a0 + 1 + lane; a < R; a += WAVE) nwv = fuse2(fusion, nwv, colv[a]);
+  nwv = fusion == 0 ? wave_sum(nwv) : wave_max(nwv);
+  // old part: b = a0 - a counts back from the rebuild point; aggregate of rows a..a0 is stored in the sfx
+  // row (t-1) mod R with t = p-R+1+a, for a >= 1
+  float carry = 0.f;
+  int r = pmod(p - R + a0 - lane, R);
+  for (int b0 = 0; b0 < a0; b0 += WAVE) {
+    const int b = b0 + lane;
+    float x = b < a0 ? colv[a0 - b] : 0.f;
+#pragma unroll
+    for (int s = 1; s < WAVE; s <<= 1) {
+      const float o = __shfl_up(x, s);
+      if (lane >= s) x = fuse2(fusion, x, o);
+    }
+    x = fuse2(fusion, x, carry);
+    if (b < a0) sfx_col[(size_t)r * Cs] = x;
+    carry = __shfl(x, WAVE - 1);
+    r -= WAVE;
+    while (r < 0) r += R;
+  }
+  if (lane == 0) {
+    sfx_col[(size_t)pmod(p0, R) * Cs] = 0.f;
+    *nw_out = nwv;
+  }
 }
 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
-  constexpr int EPL = Elem<T>::EPL, LPR = D / EPL, RPL = WAVE / LPR, UNR = 4, RPT = RPL * UNR;
-  constexpr int GP = GPad<G>::v;
-  static_assert(LPR <= WAVE && WAVE % LPR == 0, "row must fit a wave");
-  extern __shared__ float smem[];
+  using L = Layout<T, D>;
+  constexpr int EPL = Elem<T>::EPL;
+  extern __shared__ __align__(16) float smem[];
 
   const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
-  const int wave = tid / WAVE, lane = tid % WAVE, chunk = lane % LPR, rowsub = lane / LPR;
-  const int Cs = P.Cs, R = P.R, n = P.n, fusion = P.fusion;
+  const int wave = tid / WAVE, lane = tid % WAVE;
+  const int Cs = P.Cs, R = P.R, n = P.n, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps;
   const int lb = u / P.Mkv, kh = u % P.Mkv;
 
   // ---- LDS carve-up
-  const size_t lgsz = max((size_t)n * GP, (size_t)NW * G * D);
-  float *lg = smem;                  // [n][GP] logits -> exp -> weights; later [NW][G][D] output partials
-  float *red = lg + lgsz;            // [16][8]
+  const size_t lgsz = max((size_t)G * n_pad, (size_t)NW * G * D);
+  float *lg = smem;                  // [G][n_pad] logits -> exp -> weights; later [NW][G][D] output partials
+  float *turn = lg + lgsz;           // [cps] old-part aggregate of the columns rebuilt this step
+  float *colv = turn + cps;          // [R]   column of the token leaving the window, oldest row first
+  float *red = colv + R;             // [16][8]
   float *red2 = red + 16 * 8;        // [16][8]
-  float *colv = red2 + 16 * 8 + 8;   // [R] column of the token leaving the window, oldest row first
-  float *bestF = colv + R;           // [16]
+  float *bestF = red2 + 16 * 8;      // [16]
   int *bestC = (int *)(bestF + 16);  // [16]
   int *bestP = bestC + 16;           // [16]
-  int *sh = bestP + 16;              // [8]  2: dest slot, 3: evicted position
-  float *shf = (float *)(sh + 8);    // [4]  0: weight of the new row on the token leaving the window
+  int *sh = bestP + 16;              // [16] 0,1: tile counters; 2: dest slot; 3: evicted; 4: new n_snap
+  float *shf = (float *)(sh + 16);   // [8]  0: weight of the new row on the token leaving the window
 
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1];
   const int w = p % R, nwin = p < R ? p : R;
   const bool win_full = p >= R;
+  const int turn0 = pmod(p - 1, R) * cps;  // first column rebuilt this step
 
-  const T *Kb = (const T *)P.K + (size_t)u * n * D;
-  const T *Vb = (const T *)P.V + (size_t)u * n * D;
+  const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
+  const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
   float *ringu = P.ring + (size_t)u * R * n;
   float *sfxu = P.sfx + (size_t)u * R * Cs;
   float *nwu = P.nw + (size_t)u * Cs;
   int32_t *posu = P.pos + (size_t)u * n;
+  const T *qb = (const T *)P.q + ((size_t)(lb * P.Mq + kh * G)) * D;
+  const T *knew = (const T *)P.k_new + (size_t)u * D;
+  const T *vnew = (const T *)P.v_new + (size_t)u * D;
 
-  // ---- query fragments (pre-scaled so that weights are exp2 of the logit), self logit
-  float qf[G][EPL];
+  if (tid == 0) { sh[0] = 0; sh[1] = 0; }
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
+
+  // ---- prefetch of the per-column state this thread will update after the softmax
+  float pn[MAXJ], ps[MAXJ];
+  int pp[MAXJ];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const T *qp = (const T *)P.q + ((size_t)(lb * P.Mq + kh * G + g)) * D;
-    uint4 r = ((const uint4 *)qp)[chunk];
-    Elem<T>::unpack(r, qf[g]);
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) qf[g][e] *= P.scale_log2;
+  for (int i = 0; i < MAXJ; ++i) {
+    const int j = tid + i * NT;
+    pn[i] = 0.f; ps[i] = 0.f; pp[i] = -1;
+    if (j < n_snap) { pn[i] = nwu[j]; ps[i] = sfxu[(size_t)w * Cs + j]; pp[i] = posu[j]; }
   }
+
+  // ---- self logit (every lane ends up with all G values)
   float selfl[G];
   {
-    uint4 r = ((const uint4 *)((const T *)P.k_new + (size_t)u * D))[chunk];
+    constexpr int LPR = D / EPL;
+    const int chunk = lane % LPR;
+    uint4 r = ((const uint4 *)knew)[chunk];
     float kf[EPL];
     Elem<T>::unpack(r, kf);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+      uint4 rq = ((const uint4 *)(qb + (size_t)g * D))[chunk];
+      float qf[EPL];
+      Elem<T>::unpack(rq, qf);
       float d = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+      for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
 #pragma unroll
       for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
-      selfl[g] = d;
+      selfl[g] = d * P.scale_log2;
     }
   }
+  __syncthreads();  // tile counters are initialised
 
-  // ---- columns whose turn it is: rebuild their aggregate state from the R rows of steps p-R .. p-1
-  if (p >= 1) {
-    const int phi = (p - 1) % R;
-    for (int cc = tid; cc < P.cps; cc += NT) {
-      const int c = phi * P.cps + cc;
-      if (c < n_snap) {
-        float nwv = column_scan(
-            p - 1, p - 1, R, fusion, [&](int t) { return ringu[(size_t)pmod(t, R) * n + c]; },
-            [&](int r, float x) { sfxu[(size_t)r * Cs + c] = x; });
-        nwu[c] = nwv;
-      }
-    }
-  }
+  // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
+  if (wave == NW - 1 && p >= 1)
+    rebuild_turn_columns(lane, p, n_snap, R, n, Cs, cps, fusion, ringu, sfxu, nwu, turn, colv, win_full, w);
 
   // ---- K pass
   float mx[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) mx[g] = -INFINITY;
-  for (int tile = wave; tile * RPT < n; tile += NW) {
-    uint4 r[UNR];
-    bool ok[UNR];
+
+  if constexpr (L::tiled) {
+    // MFMA: A = 16 slots x 32 channels of K, B = 32 channels x 16 heads of q (heads >= G are zero)
+    constexpr int KB = L::KB, TU = 2;  // tiles in flight per wave
+    const int head = lane & 15, kq = lane >> 4;
+    bf16x8_t qfr[KB];
 #pragma unroll
-    for (int i = 0; i < UNR; ++i) {
-      const int j = tile * RPT + i * RPL + rowsub;
-      ok[i] = j < n_snap || (j >= Cs && j < Cs + nwin);
-      if (ok[i]) r[i] = ((const uint4 *)(Kb + (size_t)j * D))[chunk];
+    for (int kb = 0; kb < KB; ++kb) {
+      uint4 r = {0u, 0u, 0u, 0u};
+      if (head < G) r = *(const uint4 *)(qb + (size_t)head * D + kb * 32 + kq * 8);
+      qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
     }
+    const int ntile = n_pad / 16, ngrp = (ntile + TU - 1) / TU;
+    int grp = 0;
+    if (lane == 0) grp = atomicAdd(&sh[0], 1);
+    grp = __shfl(grp, 0);
+    while (grp < ngrp) {
+      int nxt = 0;
+      if (lane == 0) nxt = atomicAdd(&sh[0], 1);
+      uint4 a[TU][KB];
 #pragma unroll
-    for (int i = 0; i < UNR; ++i) {
-      const int j = tile * RPT + i * RPL + rowsub;
-      float kf[EPL];
-      if (ok[i]) Elem<T>::unpack(r[i], kf);
-      float l[G];
+      for (int t = 0; t < TU; ++t) {
+        const int tile = grp * TU + t;
+        if (tile < ntile) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float d = 0.f;
-        if (ok[i]) {
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+          for (int kb = 0; kb < KB; ++kb)
+            a[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KB + kb) * 512 + lane * 8);
         }
-#pragma unroll
-        for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
-        l[g] = ok[i] ? d : -INFINITY;
-        mx[g] = fmaxf(mx[g], l[g]);
       }
-      if (chunk == 0 && j < n) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) lg[(size_t)j * GP + g] = l[g];
+      for (int t = 0; t < TU; ++t) {
+        const int tile = grp * TU + t;
+        if (tile < ntile) {
+          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[t][kb]), qfr[kb], acc, 0, 0, 0);
+          // acc[i] = logit of slot tile*16 + 4*kq + i for head `head`
+          if (head < G) {
+            float l4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int j = tile * 16 + 4 * kq + i;
+              l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
+            }
+            float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
+#pragma unroll
+            for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
+            *(float4 *)(lg + (size_t)head * n_pad + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
+          }
+        }
       }
+      grp = __shfl(nxt, 0);
     }
-  }
+    // each lane tracked only its own head: combine lanes of equal head, then spread all heads to lane 0
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < G; ++g) {
+      float v = mx[g];
 #pragma unroll
-    for (int m = LPR; m < WAVE; m <<= 1) mx[g] = fmaxf(mx[g], __shfl_xor(mx[g], m));
-    if (lane == 0) red[wave * 8 + g] = mx[g];
+      for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
+      if (lane == 0) red[wave * 8 + g] = v;
+    }
+  } else {
+    // plain FMAs on row-major K: LPR lanes share a row
+    constexpr int LPR = D / EPL, RPL = WAVE / LPR, UNR = 4, RPT = RPL * UNR;
+    const int chunk = lane % LPR, rowsub = lane / LPR;
+    float qf[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      uint4 r = ((const uint4 *)(qb + (size_t)g * D))[chunk];
+      Elem<T>::unpack(r, qf[g]);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qf[g][e] *= P.scale_log2;
+    }
+    const int ntile = (n_pad + RPT - 1) / RPT;
+    int tile = 0;
+    if (lane == 0) tile = atomicAdd(&sh[0], 1);
+    tile = __shfl(tile, 0);
+    while (tile < ntile) {
+      int nxt = 0;
+      if (lane == 0) nxt = atomicAdd(&sh[0], 1);
+      uint4 r[UNR];
+      bool ok[UNR];
+#pragma unroll
+      for (int i = 0; i < UNR; ++i) {
+        const int j = tile * RPT + i * RPL + rowsub;
+        ok[i] = slot_valid(j, n_snap, Cs, nwin);
+        if (ok[i]) r[i] = ((const uint4 *)(Kb + (size_t)j * D))[chunk];
+      }
+#pragma unroll
+      for (int i = 0; i < UNR; ++i) {
+        const int j = tile * RPT + i * RPL + rowsub;
+        float kf[EPL];
+        if (ok[i]) Elem<T>::unpack(r[i], kf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float d = 0.f;
+          if (ok[i]) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+          }
+#pragma unroll
+          for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
+          const float l = ok[i] ? d : -INFINITY;
+          mx[g] = fmaxf(mx[g], l);
+          if (chunk == 0 && j < n_pad) lg[(size_t)g * n_pad + j] = l;
+        }
+      }
+      tile = __shfl(nxt, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float v = mx[g];
+#pragma unroll
+      for (int m = LPR; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+      if (lane == 0) red[wave * 8 + g] = v;
+    }
   }
   __syncthreads();
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
   // ---- softmax: exact max, sum, weights
   float M[G], inv[G], pself[G];
+  {
+    // red holds [wave][8]: lane l looks at head l%8 of waves l/8 and l/8+8, then lanes of equal head combine
+    float v = -INFINITY;
+    if ((lane >> 3) < NW) v = red[lane];
+    if ((lane >> 3) + 8 < NW) v = fmaxf(v, red[lane + 64]);
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float m = selfl[g];
-    for (int x = 0; x < NW; ++x) m = fmaxf(m, red[x * 8 + g]);
-    M[g] = m;
+    for (int m = 8; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+#pragma unroll
+    for (int g = 0; g < G; ++g) M[g] = fmaxf(selfl[g], __shfl(v, g));
   }
   {
     float zs[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
-    for (int j = tid; j < n; j += NT) {
+    for (int j = tid; j < n_pad; j += NT) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float e = exp2f(lg[(size_t)j * GP + g] - M[g]);
-        lg[(size_t)j * GP + g] = e;
+        const float e = exp2f(lg[(size_t)g * n_pad + j] - M[g]);
+        lg[(size_t)g * n_pad + j] = e;
         zs[g] += e;
       }
     }
@@ -187,40 +421,53 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     }
   }
   __syncthreads();
+  {
+    float v = 0.f;
+    if ((lane >> 3) < NW) v = red2[lane];
+    if ((lane >> 3) + 8 < NW) v += red2[lane + 64];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float es = exp2f(selfl[g] - M[g]);
-    float z = es;
-    for (int x = 0; x < NW; ++x) z += red2[x * 8 + g];
-    inv[g] = 1.0f / z;
-    pself[g] = es * inv[g];
+    for (int m = 8; m < WAVE; m <<= 1) v += __shfl_xor(v, m);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float es = exp2f(selfl[g] - M[g]);
+      const float z = es + __shfl(v, g);
+      inv[g] = 1.0f / z;
+      pself[g] = es * inv[g];
+    }
   }
 
   // ---- record the row, update per-column aggregates, fused scores, local argmin
   float bF = INFINITY;
   int bP = -1, bC = -1;
-  for (int j = tid; j < n; j += NT) {
+  auto record = [&](int j, float nw_old, float sfx_old, int pj) {
     float S = 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float pg = lg[(size_t)j * GP + g] * inv[g];
-      lg[(size_t)j * GP + g] = pg;
+      const float pg = lg[(size_t)g * n_pad + j] * inv[g];
+      lg[(size_t)g * n_pad + j] = pg;
       S += pg;
     }
-    ringu[(size_t)w * n + j] = S;
+    if (j < n) ringu[(size_t)w * n + j] = S;
     if (j < n_snap) {
-      const float nv = fuse2(fusion, nwu[j], S);
+      if (j >= turn0 && j < turn0 + cps && p >= 1) { nw_old = 0.f; sfx_old = turn[j - turn0]; }
+      const float nv = fuse2(fusion, nw_old, S);
       nwu[j] = nv;
-      const float F = fuse2(fusion, sfxu[(size_t)w * Cs + j], nv);
+      const float F = fuse2(fusion, sfx_old, nv);
       if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-      const int pj = posu[j];
       if (F < bF || (F == bF && pj > bP)) { bF = F; bP = pj; bC = j; }
     }
     if (j == Cs + w) shf[0] = S;
+  };
+#pragma unroll
+  for (int i = 0; i < MAXJ; ++i) {
+    const int j = tid + i * NT;
+    if (j < n_pad) record(j, pn[i], ps[i], pp[i]);
   }
-  for (int a = tid; a < R - 1; a += NT) {
-    const int t = p - R + 1 + a;
-    colv[a] = win_full ? ringu[(size_t)pmod(t, R) * n + Cs + w] : 0.f;
+  for (int j = tid + MAXJ * NT; j < n_pad; j += NT) {
+    float a = 0.f, b = 0.f;
+    int pj = -1;
+    if (j < n_snap) { a = nwu[j]; b = sfxu[(size_t)w * Cs + j]; pj = posu[j]; }
+    record(j, a, b, pj);
   }
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
@@ -230,51 +477,107 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   }
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
   __syncthreads();
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 2] = wall_clock64();
 
   // ---- V pass
-  float acc[G][EPL];
+  if constexpr (L::tiled) {
+    // MFMA: A = 16 heads x 32 slots of weights (bf16 hi + lo parts, so the product keeps ~16 bits of p),
+    //       B = 32 slots x 16 channels of V
+    constexpr int CB = L::CB;
+    const int head = lane & 15, kq = lane >> 4;
+    f32x4_t acc[CB];
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+    for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int ntile = n_pad / 32;
+    // tiles are dealt out statically here: the order in which a wave adds up its tiles, and with it the
+    // rounding of the output, is then the same in every run
+    for (int tile = wave; tile < ntile; tile += NW) {
+      uint4 b[CB];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-  for (int tile = wave; tile * RPT < n; tile += NW) {
-    uint4 r[UNR];
-    bool ok[UNR];
+      for (int cb = 0; cb < CB; ++cb) b[cb] = *(const uint4 *)(Vb + ((size_t)tile * CB + cb) * 512 + lane * 8);
+      bf16x8_t ahi, alo;
+      {
+        float pv[8];
+        if (head < G) {
+          const float4 x = *(const float4 *)(lg + (size_t)head * n_pad + tile * 32 + kq * 8);
+          const float4 y = *(const float4 *)(lg + (size_t)head * n_pad + tile * 32 + kq * 8 + 4);
+          pv[0] = x.x; pv[1] = x.y; pv[2] = x.z; pv[3] = x.w; pv[4] = y.x; pv[5] = y.y; pv[6] = y.z; pv[7] = y.w;
+        } else {
 #pragma unroll
-    for (int i = 0; i < UNR; ++i) {
-      const int j = tile * RPT + i * RPL + rowsub;
-      ok[i] = j < n_snap || (j >= Cs && j < Cs + nwin);
-      if (ok[i]) r[i] = ((const uint4 *)(Vb + (size_t)j * D))[chunk];
-    }
+          for (int i = 0; i < 8; ++i) pv[i] = 0.f;
+        }
 #pragma unroll
-    for (int i = 0; i < UNR; ++i) {
-      const int j = tile * RPT + i * RPL + rowsub;
-      if (ok[i]) {
-        float vf[EPL];
-        Elem<T>::unpack(r[i], vf);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const float pg = lg[(size_t)j * GP + g];
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pg, vf[e], acc[g][e]);
+        for (int i = 0; i < 8; ++i) {
+          const __bf16 h = (__bf16)pv[i];
+          ahi[i] = h;
+          alo[i] = (__bf16)(pv[i] - (float)h);
         }
       }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, b[cb]);
+        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, bv, acc[cb], 0, 0, 0);
+        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
+      }
     }
-  }
+    __syncthreads();  // every wave is done reading the weights: lg may be reused
+    // acc[cb][i] = O[head 4*kq + i][channel cb*16 + (lane & 15)]
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int e = 0; e < EPL; ++e)
-#pragma unroll
-      for (int m = LPR; m < WAVE; m <<= 1) acc[g][e] += __shfl_xor(acc[g][e], m);
-  __syncthreads();  // every wave is done reading the weights: lg may be reused
-
-  if (rowsub == 0) {
+      for (int i = 0; i < 4; ++i) {
+        const int g = 4 * kq + i;
+        if (g < G) lg[(size_t)(wave * G + g) * D + cb * 16 + head] = acc[cb][i];
+      }
+  } else {
+    constexpr int LPR = D / EPL, RPL = WAVE / LPR, UNR = 4, RPT = RPL * UNR;
+    const int chunk = lane % LPR, rowsub = lane / LPR;
+    float acc[G][EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) lg[(size_t)(wave * G + g) * D + chunk * EPL + e] = acc[g][e];
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    const int ntile = (n_pad + RPT - 1) / RPT;
+    for (int tile = wave; tile < ntile; tile += NW) {
+      uint4 r[UNR];
+      bool ok[UNR];
+#pragma unroll
+      for (int i = 0; i < UNR; ++i) {
+        const int j = tile * RPT + i * RPL + rowsub;
+        ok[i] = slot_valid(j, n_snap, Cs, nwin);
+        if (ok[i]) r[i] = ((const uint4 *)(Vb + (size_t)j * D))[chunk];
+      }
+#pragma unroll
+      for (int i = 0; i < UNR; ++i) {
+        const int j = tile * RPT + i * RPL + rowsub;
+        if (ok[i]) {
+          float vf[EPL];
+          Elem<T>::unpack(r[i], vf);
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const float pg = lg[(size_t)g * n_pad + j];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pg, vf[e], acc[g][e]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e)
+#pragma unroll
+        for (int m = LPR; m < WAVE; m <<= 1) acc[g][e] += __shfl_xor(acc[g][e], m);
+    __syncthreads();  // every wave is done reading the weights: lg may be reused
+    if (rowsub == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) lg[(size_t)(wave * G + g) * D + chunk * EPL + e] = acc[g][e];
+    }
   }
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
+
   // ---- decision (wave 0)
   if (wave == 0) {
     float fd = 0.f;  // fused score of the token leaving the window
@@ -317,48 +620,56 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     float o = 0.f;
     for (int x = 0; x < NW; ++x) o += lg[(size_t)(x * G + g) * D + ch];
     float vn;
-    {
-      const T *vp = (const T *)P.v_new + (size_t)u * D;
-      if constexpr (sizeof(T) == 4) vn = ((const float *)vp)[ch];
-      else vn = __uint_as_float(((uint32_t)((const uint16_t *)vp)[ch]) << 16);
-    }
-    float ps = 0.f;
+    if constexpr (sizeof(T) == 4) vn = ((const float *)vnew)[ch];
+    else vn = __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+    float psg = 0.f;
 #pragma unroll
-    for (int gg = 0; gg < G; ++gg) ps = gg == g ? pself[gg] : ps;
-    o = fmaf(ps, vn, o);
+    for (int gg = 0; gg < G; ++gg) psg = gg == g ? pself[gg] : psg;
+    o = fmaf(psg, vn, o);
     P.out[((size_t)(lb * P.Mq + kh * G + g)) * D + ch] = o;
   }
 
-  // ---- compaction
+  // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot
   const int dest = sh[2];
-  if (tid < 2 * LPR) {
-    const int which = tid / LPR, ck = tid % LPR;
-    T *base = (which ? (T *)P.V : (T *)P.K) + (size_t)u * n * D;
-    const T *nsrc = (which ? (const T *)P.v_new : (const T *)P.k_new) + (size_t)u * D;
-    uint4 *wslot = (uint4 *)(base + (size_t)(Cs + w) * D) + ck;
-    if (dest >= 0) {
-      const uint4 r = *wslot;
-      ((uint4 *)(base + (size_t)dest * D))[ck] = r;
+  const int wslot = Cs + w;
+  T *Kw_ = (T *)P.K + (size_t)u * n_pad * D;
+  T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
+  constexpr int PCS = D / EPL;  // 16-byte pieces per row
+  if (tid < PCS) {              // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
+    const int ch0 = tid * EPL;
+    uint4 *src = (uint4 *)(Kw_ + L::k_off(wslot, ch0));
+    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = *src;
+    *src = ((const uint4 *)knew)[tid];
+  }
+  if constexpr (L::tiled) {
+    // V: one element per (slot, channel) in tile order.  Uses the threads after the K pieces.
+    for (int ch = tid - 64; ch >= 0 && ch < D; ch += NT) {
+      uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
+      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = *src;
+      *src = ((const uint16_t *)vnew)[ch];
     }
-    *wslot = ((const uint4 *)nsrc)[ck];
+  } else {
+    if (tid >= 64 && tid < 64 + PCS) {
+      const int ch0 = (tid - 64) * EPL;
+      uint4 *src = (uint4 *)(Vw_ + L::v_off(wslot, ch0));
+      if (dest >= 0) *(uint4 *)(Vw_ + L::v_off(dest, ch0)) = *src;
+      *src = ((const uint4 *)vnew)[tid - 64];
+    }
   }
   if (dest >= 0) {
     for (int a = tid; a < R; a += NT) ringu[(size_t)pmod(p - R + 1 + a, R) * n + dest] = colv[a];
-    if (tid == NT - 1) {
-      posu[dest] = p - R;
-      const int p0 = last_rebuild_before(p, dest / P.cps, R);
-      const float nwv = column_scan(
-          p, p0, R, fusion, [&](int t) { return colv[t - (p - R + 1)]; },
-          [&](int r, float x) { sfxu[(size_t)r * Cs + dest] = x; });
-      nwu[dest] = nwv;
+    if (wave == NW - 1) {
+      if (lane == 0) posu[dest] = p - R;
+      move_scan_wave(lane, p, last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, Cs, nwu + dest);
     }
   }
   if (tid == 0) {
-    posu[Cs + w] = p;
+    posu[wslot] = p;
     int32_t *m = P.meta + (size_t)u * META;
     m[0] = sh[4];
     m[1] = p + 1;
     m[2] = sh[3];
+    if (P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
   }
 }
 

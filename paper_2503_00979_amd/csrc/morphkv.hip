@@ -36,8 +36,8 @@ int fail(int code, const char *fmt, ...) {
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
-struct Layout {
-  int U, G, Cs, n, cps, esz;
+struct BufLayout {
+  int U, G, Cs, n, n_pad, cps, esz;
   // cache
   size_t offK, offV, offPos, offMeta, cache_bytes;
   // scores_ring
@@ -71,18 +71,20 @@ int validate(const morphkv_config *c) {
   return MORPHKV_OK;
 }
 
-Layout make_layout(const morphkv_config *c) {
-  Layout L{};
+BufLayout make_layout(const morphkv_config *c) {
+  BufLayout L{};
   L.U = c->n_layers * c->batch * c->n_kv_heads;
   L.G = c->n_q_heads / c->n_kv_heads;
   L.Cs = c->C + c->evict_every - 1;
   L.n = L.Cs + c->R;
+  L.n_pad = (L.n + 31) / 32 * 32;  // K/V slot arrays are padded to whole tiles
   L.cps = (L.Cs + c->R - 1) / c->R;
   L.esz = c->dtype == MORPHKV_DTYPE_F32 ? 4 : 2;
-  const size_t U = (size_t)L.U, n = (size_t)L.n, d = (size_t)c->head_dim, R = (size_t)c->R, Cs = (size_t)L.Cs;
+  const size_t U = (size_t)L.U, n = (size_t)L.n, np = (size_t)L.n_pad, d = (size_t)c->head_dim, R = (size_t)c->R,
+               Cs = (size_t)L.Cs;
   size_t o = 0;
-  L.offK = o; o = align_up(o + U * n * d * L.esz);
-  L.offV = o; o = align_up(o + U * n * d * L.esz);
+  L.offK = o; o = align_up(o + U * np * d * L.esz);
+  L.offV = o; o = align_up(o + U * np * d * L.esz);
   L.offPos = o; o = align_up(o + U * n * 4);
   L.offMeta = o; o = align_up(o + U * META * 4);
   L.cache_bytes = o;
@@ -105,9 +107,10 @@ Layout make_layout(const morphkv_config *c) {
 
 struct morphkv_handle {
   morphkv_config cfg;
-  Layout L;
+  BufLayout L;
   char *cache, *ring, *scratch;
   float *dbgF;
+  long long *dbgT;
   bool prefilled;
   float scale_log2;
   int n_cu;
@@ -117,7 +120,7 @@ namespace {
 
 DecodeParams decode_params(const morphkv_handle *h) {
   DecodeParams P{};
-  const Layout &L = h->L;
+  const BufLayout &L = h->L;
   P.K = h->cache + L.offK;
   P.V = h->cache + L.offV;
   P.pos = (int32_t *)(h->cache + L.offPos);
@@ -126,14 +129,15 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.sfx = (float *)(h->ring + L.offSfx);
   P.nw = (float *)(h->ring + L.offNw);
   P.dbgF = h->dbgF;
-  P.Cs = L.Cs; P.R = h->cfg.R; P.n = L.n; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads;
+  P.dbgT = h->dbgT;
+  P.Cs = L.Cs; P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads;
   P.fusion = h->cfg.fusion; P.cps = L.cps; P.scale_log2 = h->scale_log2;
   return P;
 }
 
 PrefillParams prefill_params(const morphkv_handle *h) {
   PrefillParams P{};
-  const Layout &L = h->L;
+  const BufLayout &L = h->L;
   P.plen = (const int32_t *)(h->scratch + L.offPlen);
   P.Srow = (float *)(h->scratch + L.offSrow);
   P.F = (float *)(h->scratch + L.offF);
@@ -146,7 +150,8 @@ PrefillParams prefill_params(const morphkv_handle *h) {
   P.sfx = (float *)(h->ring + L.offSfx);
   P.nw = (float *)(h->ring + L.offNw);
   P.B = h->cfg.batch; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads; P.C = h->cfg.C; P.Cs = L.Cs;
-  P.R = h->cfg.R; P.n = L.n; P.fusion = h->cfg.fusion; P.cps = L.cps; P.scale_log2 = h->scale_log2;
+  P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.fusion = h->cfg.fusion; P.cps = L.cps;
+  P.scale_log2 = h->scale_log2;
   return P;
 }
 
@@ -162,7 +167,7 @@ int decode_threads(const morphkv_handle *h) {
 template <typename T, int D, int G>
 int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
   const int NT = decode_threads(h);
-  const size_t lds = decode_lds_bytes(P.n, GPad<G>::v, G, D, NT, P.R);
+  const size_t lds = decode_lds_bytes(P.n, P.n_pad, G, D, NT, P.R, P.cps);
   if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
   auto kern = decode_fused_kernel<T, D, G>;
   static size_t attr_set = 0;  // per instantiation
@@ -185,7 +190,7 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
   hipLaunchKernelGGL(prefill_select_kernel, dim3(U), dim3(1024), 0, st, P);
   HIP_TRY(hipGetLastError());
   constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
-  hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n + SPB - 1) / SPB, U), dim3(256), 0, st, P);
+  hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
@@ -236,7 +241,7 @@ const char *morphkv_last_error(void) { return g_err; }
 int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_bytes, size_t *scratch_bytes) {
   int rc = validate(cfg);
   if (rc) return rc;
-  const Layout L = make_layout(cfg);
+  const BufLayout L = make_layout(cfg);
   if (cache_bytes) *cache_bytes = L.cache_bytes;
   if (ring_bytes) *ring_bytes = L.ring_bytes;
   if (scratch_bytes) *scratch_bytes = L.scratch_bytes;
@@ -259,6 +264,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   h->ring = (char *)scores_ring;
   h->scratch = (char *)scratch;
   h->dbgF = nullptr;
+  h->dbgT = nullptr;
   h->prefilled = false;
   const double scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
   h->scale_log2 = (float)(scale * 1.4426950408889634074);
@@ -312,7 +318,7 @@ int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, v
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!pos) return fail(MORPHKV_EINVAL, "pos is null");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
-  const Layout &L = h->L;
+  const BufLayout &L = h->L;
   hipLaunchKernelGGL(export_positions_kernel, dim3((L.n + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
                      (const int32_t *)(h->cache + L.offPos), (const int32_t *)(h->cache + L.offMeta), pos, n_snap,
                      L.n, L.U);
@@ -324,7 +330,7 @@ int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!evicted) return fail(MORPHKV_EINVAL, "evicted is null");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
-  const Layout &L = h->L;
+  const BufLayout &L = h->L;
   hipLaunchKernelGGL(export_evicted_kernel, dim3((L.U + 255) / 256), dim3(256), 0, (hipStream_t)stream,
                      (const int32_t *)(h->cache + L.offMeta), evicted, L.U);
   HIP_TRY(hipGetLastError());
@@ -334,6 +340,12 @@ int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream) {
 int morphkv_capture_scores(morphkv_handle *h, float *F) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   h->dbgF = F;
+  return MORPHKV_OK;
+}
+
+int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  h->dbgT = clocks;
   return MORPHKV_OK;
 }
 

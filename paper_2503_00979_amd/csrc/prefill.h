@@ -17,7 +17,7 @@ struct PrefillParams {
   void *Kc, *Vc;
   int32_t *pos, *meta;
   float *ring, *sfx, *nw;
-  int32_t B, Mq, Mkv, C, Cs, R, n, Nmax, fusion, cps;
+  int32_t B, Mq, Mkv, C, Cs, R, n, n_pad, Nmax, fusion, cps;
   float scale_log2;
 };
 
@@ -232,22 +232,36 @@ __device__ inline int prefill_slot_source(const PrefillParams &P, int u, int slo
   return x < N ? x : -1;
 }
 
-// ---- P4a: gather K/V rows and positions into the cache slots
+// ---- P4a: gather K/V rows and positions into the cache slots (layout of the element type);
+// empty and padding slots are zero-filled so that a zero weight times their content stays zero
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
-  constexpr int LPR = D / Elem<T>::EPL;       // 16-byte pieces per row
-  constexpr int SPB = 256 / (2 * LPR);        // slots per block
+  using L = Layout<T, D>;
+  constexpr int EPL = Elem<T>::EPL, LPR = D / EPL;  // 16-byte pieces per row
+  constexpr int SPB = 256 / (2 * LPR);              // slots per block
   const int u = blockIdx.y, tid = threadIdx.x;
   const int slot = blockIdx.x * SPB + tid / (2 * LPR), which = (tid / LPR) & 1, ck = tid % LPR;
-  if (slot >= P.n) return;
+  if (slot >= P.n_pad) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b];
   const int n_snap = P.meta[(size_t)u * META];
-  const int src = prefill_slot_source(P, u, slot, N, n_snap);
-  if (which == 0 && ck == 0) P.pos[(size_t)u * P.n + slot] = src;
-  if (src < 0) return;
-  const T *in = (which ? (const T *)P.V : (const T *)P.K) + ((size_t)u * P.Nmax + src) * D;
-  T *outp = (which ? (T *)P.Vc : (T *)P.Kc) + ((size_t)u * P.n + slot) * D;
-  ((uint4 *)outp)[ck] = ((const uint4 *)in)[ck];
+  const int src = slot < P.n ? prefill_slot_source(P, u, slot, N, n_snap) : -1;
+  if (which == 0 && ck == 0 && slot < P.n) P.pos[(size_t)u * P.n + slot] = src;
+  uint4 r = {0u, 0u, 0u, 0u};
+  if (src >= 0) {
+    const T *in = (which ? (const T *)P.V : (const T *)P.K) + ((size_t)u * P.Nmax + src) * D;
+    r = ((const uint4 *)in)[ck];
+  }
+  T *outp = (which ? (T *)P.Vc : (T *)P.Kc) + (size_t)u * P.n_pad * D;
+  const int ch0 = ck * EPL;
+  if (which == 0) {
+    *(uint4 *)(outp + L::k_off(slot, ch0)) = r;
+  } else if constexpr (L::tiled) {
+    const uint16_t *e = (const uint16_t *)&r;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) ((uint16_t *)outp)[L::v_off(slot, ch0 + i)] = e[i];
+  } else {
+    *(uint4 *)(outp + L::v_off(slot, ch0)) = r;
+  }
 }
 
 // ---- P4b: recorded rows restricted to the resident columns
