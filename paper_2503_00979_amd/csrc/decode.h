@@ -262,8 +262,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   __syncthreads();  // tile counters are initialised
 
   // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
-  if (wave == NW - 1 && p >= 1)
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
+  if (wave == NW - 1 && p >= 1) {
     rebuild_turn_columns(lane, p, n_snap, R, n, Cs, cps, fusion, ringu, sfxu, nwu, turn, colv, win_full, w);
+    if (P.dbgT && lane == 0) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
+  }
 
   // ---- K pass
   float mx[G];
@@ -387,6 +390,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       if (lane == 0) red[wave * 8 + g] = v;
     }
   }
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
   __syncthreads();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
