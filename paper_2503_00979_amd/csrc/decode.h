@@ -12,11 +12,14 @@
 //              its aggregate state); the new token takes the window slot.
 //
 // Two data paths:
-//   bf16 : K and V live in MFMA-operand tile order (see TiledLayout) so that a wave reads 1 KB
-//          contiguous per load and feeds v_mfma_f32_16x16x32_bf16 directly; Q.K^T and P.V are dense
-//          enough across the G grouped heads only in the sense that the matrix core makes the
+//   bf16 : K and V live in MFMA-operand tile order (see Layout<bf16_t, D>) so that a wave reads 1 KB
+//          contiguous per load and feeds v_mfma_f32_16x16x32_bf16 directly: the matrix core makes the
 //          arithmetic free next to the HBM stream -- the bound stays HBM.
 //   fp32 : row-major K/V, plain fp32 FMAs (small/toy configurations).
+//
+// Timeline of a workgroup: the HBM stream (K tiles, then V tiles) is the critical path; the last wave
+// spends the start of the K pass rebuilding the aggregate state of the columns whose turn it is; the
+// first V tile of every wave is already in flight while the softmax runs.
 #pragma once
 #include "common.h"
 
@@ -29,16 +32,16 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 struct DecodeParams {
   void *K, *V;             // per unit n_pad * D elements, layout by element type (see Layout<>)
-  int32_t *pos;            // [U][n]
+  int32_t *pos;            // [U][n_pad]
   int32_t *meta;           // [U][META]
-  float *ring;             // [U][R][n]   recorded rows, row index = query position mod R
-  float *sfx;              // [U][R][Cs]  old-part aggregates (see column_scan)
-  float *nw;               // [U][Cs]     new-part aggregates
+  float *ring;             // [U][R][n_pad]  recorded rows, row index = query position mod R
+  float *sfx;              // [U][R][CsP]    old-part aggregates (see column_scan)
+  float *nw;               // [U][CsP]       new-part aggregates
   const void *q, *k_new, *v_new;
   float *out;
   float *dbgF;             // nullable: [U][Cs+1]
   long long *dbgT;         // nullable: [U][8] phase time stamps (diagnostics)
-  int32_t Cs, R, n, n_pad, Mq, Mkv, fusion, cps;
+  int32_t Cs, CsP, R, n, n_pad, Mq, Mkv, fusion, cps, cpt;
   float scale_log2;        // softmax scale * log2(e)
 };
 
@@ -49,6 +52,7 @@ template <typename T, int D> struct Layout;
 // fp32: row-major [slot][channel]
 template <int D> struct Layout<float, D> {
   static constexpr bool tiled = false;
+  static constexpr int KB = 1, CB = 1;
   __device__ __host__ static inline size_t k_off(int j, int ch) { return (size_t)j * D + ch; }
   __device__ __host__ static inline size_t v_off(int j, int ch) { return (size_t)j * D + ch; }
 };
@@ -69,12 +73,20 @@ template <int D> struct Layout<bf16_t, D> {
   }
 };
 
-constexpr int MAXJ = 5;  // columns per thread whose state is prefetched before the K pass
+constexpr int MAXQ = 2;  // groups of 4 columns per thread whose state is prefetched before the K pass
+
+// columns rebuilt per step, padded the way the staging area lays them out
+__host__ __device__ inline int turn_cols_padded(int cps) {
+  if (cps <= 64) { int c = 1; while (c < cps) c <<= 1; return c; }
+  return (cps + 63) / 64 * 64;
+}
 
 // LDS bytes of decode_fused_kernel
-inline size_t decode_lds_bytes(int n, int n_pad, int G, int D, int NT, int R, int cps) {
-  size_t lg = (size_t)G * n_pad, om = (size_t)(NT / 64) * G * D;
-  size_t fl = (lg > om ? lg : om) + (size_t)cps + (size_t)R + 16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
+inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps) {
+  const size_t lg = (size_t)G * n_pad, om = (size_t)(NT / 64) * G * D;
+  const size_t cpt = (size_t)turn_cols_padded(cps);
+  const size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
+                    16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
   return fl * 4;
 }
 
@@ -82,29 +94,86 @@ __device__ inline bool slot_valid(int j, int n_snap, int Cs, int nwin) {
   return j < n_snap || (j >= Cs && j < Cs + nwin);
 }
 
+// workgroup barrier that orders LDS traffic only: outstanding global loads/stores stay in flight
+__device__ inline void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// ---- wave reductions on DPP (no LDS traffic) ---------------------------------------------------------
+template <int CTRL> __device__ inline float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL> __device__ inline int dpp_mov_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+__device__ inline float lane_bcast(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ inline float wave_sum_dpp(float v) {
+  v += dpp_mov<DPP_XOR1>(v); v += dpp_mov<DPP_XOR2>(v); v += dpp_mov<DPP_HALF_MIRROR>(v); v += dpp_mov<DPP_MIRROR>(v);
+  return (lane_bcast(v, 0) + lane_bcast(v, 16)) + (lane_bcast(v, 32) + lane_bcast(v, 48));
+}
+__device__ inline float wave_max_dpp(float v) {
+  v = fmaxf(v, dpp_mov<DPP_XOR1>(v)); v = fmaxf(v, dpp_mov<DPP_XOR2>(v));
+  v = fmaxf(v, dpp_mov<DPP_HALF_MIRROR>(v)); v = fmaxf(v, dpp_mov<DPP_MIRROR>(v));
+  return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
+}
+// eviction candidate order: does (of, op) go before (f, p)?  smaller score first, on equal score the
+// higher position
+__device__ inline bool cand_before(float f, int p, float of, int op) { return of < f || (of == f && op > p); }
+template <int CTRL> __device__ inline void argmin_step(float &f, int &p, int &c) {
+  const float of = dpp_mov<CTRL>(f);
+  const int op = dpp_mov_i<CTRL>(p), oc = dpp_mov_i<CTRL>(c);
+  if (cand_before(f, p, of, op)) { f = of; p = op; c = oc; }
+}
+__device__ inline void wave_argmin(float &f, int &p, int &c) {
+  argmin_step<DPP_XOR1>(f, p, c); argmin_step<DPP_XOR2>(f, p, c);
+  argmin_step<DPP_HALF_MIRROR>(f, p, c); argmin_step<DPP_MIRROR>(f, p, c);
+#pragma unroll
+  for (int m = 16; m <= 32; m <<= 1) {
+    const float of = __shfl_xor(f, m);
+    const int op = __shfl_xor(p, m), oc = __shfl_xor(c, m);
+    if (cand_before(f, p, of, op)) { f = of; p = op; c = oc; }
+  }
+}
+
 // One wave rebuilds the aggregate state of the columns whose turn it is at the start of step p
-// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1, and prefetches the column of the
-// token that leaves the window.  turn[cc] receives f(rows p-R+1..p-1) of column c0+cc.
-//
-// Lanes are laid out as (column cc, row group q): a lane holds rows i = q, q+Q, q+2Q, ... (row i is the
-// row of step p-1-i), so that one load instruction reads Q rows x CP consecutive columns.  Each round
-// scans Q consecutive rows across the row groups with wave shuffles and carries the running aggregate.
-__device__ inline void rebuild_turn_columns(int lane, int p, int n_snap, int R, int n, int Cs, int cps, int fusion,
-                                            const float *ringu, float *sfxu, float *nwu, float *turn,
-                                            float *colv, bool win_full, int w) {
+// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1, and fetches the column of the
+// token that leaves the window.  Results stay in LDS:
+//   stage[i*cpt + cc] = f(rows of steps p-1-i .. p-1) of column c0+cc   (i = 0..R-2), to be stored to
+//                       sfx row (p-2-i) mod R by the whole workgroup later;
+//   turn[cc]          = f(all R-1 rows): the old part of this step's score for that column.
+// Lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc).
+__device__ inline void rebuild_turn_columns(int lane, int p, int n_snap, int R, int rs, int Cs, int cps, int cpt,
+                                            int fusion, const float *ringu, float *stage, float *turn, float *colv,
+                                            bool win_full, int w) {
   const int phi = pmod(p - 1, R), c0 = phi * cps;
   int ncol = n_snap - c0;
   ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
+  constexpr int B = 16;
   // column of the token leaving the window (rows p-R+1 .. p-1), oldest first
   {
+    float cv[B];
     int r = pmod(p - R + 1 + lane, R);
-    for (int a = lane; a < R - 1; a += WAVE) {
-      colv[a] = win_full ? ringu[(size_t)r * n + Cs + w] : 0.f;
+#pragma unroll
+    for (int k = 0; k < B; ++k) {
+      const int a = lane + k * WAVE;
+      cv[k] = 0.f;
+      if (a < R - 1 && win_full) cv[k] = ringu[(size_t)r * rs + Cs + w];
       r += WAVE;
       while (r >= R) r -= R;
     }
+#pragma unroll
+    for (int k = 0; k < B; ++k) {
+      const int a = lane + k * WAVE;
+      if (a < R - 1) colv[a] = cv[k];
+    }
   }
-  constexpr int B = 32;  // rounds per batch: all loads of a batch are in flight together
+  const int r_top = pmod(p - 1, R);  // ring row of row i = 0
   for (int cg = 0; cg < ncol; cg += WAVE) {
     const int nc = ncol - cg < WAVE ? ncol - cg : WAVE;
     int CP = 1, lg2 = 0;
@@ -113,54 +182,57 @@ __device__ inline void rebuild_turn_columns(int lane, int p, int n_snap, int R, 
     const int cc = lane & (CP - 1), q = lane >> lg2;
     const bool colok = cc < nc;
     const int c = c0 + cg + cc;
-    int r_ld = pmod(p - 1 - q, R);  // ring row of row i = q
-    int r_st = pmod(p - 2 - q, R);  // sfx row its aggregate is read from (at step p-1-i+R-1)
-    float carry = 0.f;
-    const int rounds = (R - 1 + Q - 1) / Q;
-    for (int k0 = 0; k0 < rounds; k0 += B) {
+    const int Lc = (R - 1 + Q - 1) / Q;
+    const int i0 = min(q * Lc, R - 1), i1 = min(i0 + Lc, R - 1);
+    float *st = stage + cg + cc;
+    // raw rows -> stage
+    for (int ib = i0; ib < i1; ib += B) {
       float v[B];
+      int r = r_top - ib;
+      while (r < 0) r += R;
 #pragma unroll
       for (int k = 0; k < B; ++k) {
-        const int i = q + Q * (k0 + k);
         v[k] = 0.f;
-        if (colok && i < R - 1) v[k] = ringu[(size_t)r_ld * n + c];
-        r_ld -= Q;
-        while (r_ld < 0) r_ld += R;
+        if (colok && ib + k < i1) v[k] = ringu[(size_t)r * rs + c];
+        r = r == 0 ? R - 1 : r - 1;
       }
 #pragma unroll
-      for (int k = 0; k < B; ++k) {
-        if (k0 + k < rounds) {
-          const int i = q + Q * (k0 + k);
-          float x = v[k];
-          for (int s = CP; s < WAVE; s <<= 1) {
-            const float o = __shfl_up(x, s);
-            if (lane >= s) x = fuse2(fusion, x, o);
-          }
-          x = fuse2(fusion, x, carry);
-          if (colok && i < R - 1) sfxu[(size_t)r_st * Cs + c] = x;
-          carry = __shfl(x, (Q - 1) * CP + cc);
-          r_st -= Q;
-          while (r_st < 0) r_st += R;
-        }
-      }
+      for (int k = 0; k < B; ++k)
+        if (ib + k < i1) st[(size_t)(ib + k) * cpt] = v[k];
     }
-    if (colok && q == 0) {
-      sfxu[(size_t)pmod(p - 1, R) * Cs + c] = 0.f;
-      nwu[c] = 0.f;
-      turn[cg + cc] = carry;
+    // running aggregate inside the chunk
+    float acc = 0.f;
+#pragma unroll 8
+    for (int i = i0; i < i1; ++i) {
+      acc = fuse2(fusion, acc, st[(size_t)i * cpt]);
+      st[(size_t)i * cpt] = acc;
     }
+    // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
+    float incl = acc;
+    for (int s = CP; s < WAVE; s <<= 1) {
+      const float o = __shfl_up(incl, s);
+      if (lane >= s) incl = fuse2(fusion, incl, o);
+    }
+    float carry = __shfl_up(incl, CP);
+    if (q == 0) carry = 0.f;
+    const float total = __shfl(incl, (Q - 1) * CP + cc);
+    if (q > 0) {
+#pragma unroll 8
+      for (int i = i0; i < i1; ++i) st[(size_t)i * cpt] = fuse2(fusion, st[(size_t)i * cpt], carry);
+    }
+    if (q == 0) turn[cg + cc] = total;
   }
 }
 
 // One wave computes the aggregate state of a single column from its R row values colv[a] (row of step
 // p-R+1+a), as of the end of step p with rebuild point p0 (same result as column_scan), and stores it.
 __device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion, const float *colv, float *sfx_col,
-                                      int Cs, float *nw_out) {
+                                      int CsP, float *nw_out) {
   const int a0 = p0 - (p - R + 1);  // row index of the rebuild point, in [-1, R-2]
   // new part: rows after the rebuild point
   float nwv = 0.f;
   for (int a = a0 + 1 + lane; a < R; a += WAVE) nwv = fuse2(fusion, nwv, colv[a]);
-  nwv = fusion == 0 ? wave_sum(nwv) : wave_max(nwv);
+  nwv = fusion == 0 ? wave_sum_dpp(nwv) : wave_max_dpp(nwv);
   // old part: b = a0 - a counts back from the rebuild point; aggregate of rows a..a0 is stored in the sfx
   // row (t-1) mod R with t = p-R+1+a, for a >= 1
   float carry = 0.f;
@@ -174,13 +246,13 @@ __device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion
       if (lane >= s) x = fuse2(fusion, x, o);
     }
     x = fuse2(fusion, x, carry);
-    if (b < a0) sfx_col[(size_t)r * Cs] = x;
+    if (b < a0) sfx_col[(size_t)r * CsP] = x;
     carry = __shfl(x, WAVE - 1);
     r -= WAVE;
     while (r < 0) r += R;
   }
   if (lane == 0) {
-    sfx_col[(size_t)pmod(p0, R) * Cs] = 0.f;
+    sfx_col[(size_t)pmod(p0, R) * CsP] = 0.f;
     *nw_out = nwv;
   }
 }
@@ -193,49 +265,57 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 
   const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
   const int wave = tid / WAVE, lane = tid % WAVE;
-  const int Cs = P.Cs, R = P.R, n = P.n, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps;
+  const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps, cpt = P.cpt;
   const int lb = u / P.Mkv, kh = u % P.Mkv;
 
   // ---- LDS carve-up
   const size_t lgsz = max((size_t)G * n_pad, (size_t)NW * G * D);
-  float *lg = smem;                  // [G][n_pad] logits -> exp -> weights; later [NW][G][D] output partials
-  float *turn = lg + lgsz;           // [cps] old-part aggregate of the columns rebuilt this step
-  float *colv = turn + cps;          // [R]   column of the token leaving the window, oldest row first
-  float *red = colv + R;             // [16][8]
-  float *red2 = red + 16 * 8;        // [16][8]
-  float *bestF = red2 + 16 * 8;      // [16]
-  int *bestC = (int *)(bestF + 16);  // [16]
-  int *bestP = bestC + 16;           // [16]
-  int *sh = bestP + 16;              // [16] 0,1: tile counters; 2: dest slot; 3: evicted; 4: new n_snap
-  float *shf = (float *)(sh + 16);   // [8]  0: weight of the new row on the token leaving the window
+  float *lg = smem;                       // [G][n_pad] logits -> exp -> weights; later [NW][G][D] output partials
+  float *stage = lg + lgsz;               // [R][cpt] rebuilt aggregates on their way to the sfx rows
+  float *turn = stage + (size_t)R * cpt;  // [cpt] old-part aggregate of the columns rebuilt this step
+  float *colv = turn + cpt;               // [R]   column of the token leaving the window, oldest row first
+  float *red = colv + R;                  // [16][8]
+  float *red2 = red + 16 * 8;             // [16][8]
+  float *bestF = red2 + 16 * 8;           // [16]
+  int *bestC = (int *)(bestF + 16);       // [16]
+  int *bestP = bestC + 16;                // [16]
+  int *sh = bestP + 16;                   // [16] 0: K tile counter; 2: dest slot; 3: evicted; 4: new n_snap
+  float *shf = (float *)(sh + 16);        // [8]  0: weight of the new row on the token leaving the window
 
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1];
   const int w = p % R, nwin = p < R ? p : R;
   const bool win_full = p >= R;
   const int turn0 = pmod(p - 1, R) * cps;  // first column rebuilt this step
+  int turn_n = n_snap - turn0;             // how many of them exist
+  turn_n = turn_n < 0 ? 0 : (turn_n > cps ? cps : turn_n);
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
-  float *ringu = P.ring + (size_t)u * R * n;
-  float *sfxu = P.sfx + (size_t)u * R * Cs;
-  float *nwu = P.nw + (size_t)u * Cs;
-  int32_t *posu = P.pos + (size_t)u * n;
+  float *ringu = P.ring + (size_t)u * R * n_pad;
+  float *sfxu = P.sfx + (size_t)u * R * CsP;
+  float *nwu = P.nw + (size_t)u * CsP;
+  int32_t *posu = P.pos + (size_t)u * n_pad;
   const T *qb = (const T *)P.q + ((size_t)(lb * P.Mq + kh * G)) * D;
   const T *knew = (const T *)P.k_new + (size_t)u * D;
   const T *vnew = (const T *)P.v_new + (size_t)u * D;
 
-  if (tid == 0) { sh[0] = 0; sh[1] = 0; }
+  if (tid == 0) sh[0] = 0;
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
 
-  // ---- prefetch of the per-column state this thread will update after the softmax
-  float pn[MAXJ], ps[MAXJ];
-  int pp[MAXJ];
+  // ---- prefetch of the per-column state this thread will update after the softmax (4 columns a group)
+  const int nq = n_pad / 4;
+  float4 pn[MAXQ], ps[MAXQ];
+  int4 pp[MAXQ];
 #pragma unroll
-  for (int i = 0; i < MAXJ; ++i) {
-    const int j = tid + i * NT;
-    pn[i] = 0.f; ps[i] = 0.f; pp[i] = -1;
-    if (j < n_snap) { pn[i] = nwu[j]; ps[i] = sfxu[(size_t)w * Cs + j]; pp[i] = posu[j]; }
+  for (int i = 0; i < MAXQ; ++i) {
+    const int j0 = 4 * (tid + i * NT);
+    pn[i] = make_float4(0.f, 0.f, 0.f, 0.f); ps[i] = pn[i]; pp[i] = make_int4(-1, -1, -1, -1);
+    if (j0 < n_snap) {
+      pn[i] = *(const float4 *)(nwu + j0);
+      ps[i] = *(const float4 *)(sfxu + (size_t)w * CsP + j0);
+      pp[i] = *(const int4 *)(posu + j0);
+    }
   }
 
   // ---- self logit (every lane ends up with all G values)
@@ -259,12 +339,12 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       selfl[g] = d * P.scale_log2;
     }
   }
-  __syncthreads();  // tile counters are initialised
+  lds_barrier();  // the tile counter is initialised
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
 
   // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
-  if (wave == NW - 1 && p >= 1) {
-    rebuild_turn_columns(lane, p, n_snap, R, n, Cs, cps, fusion, ringu, sfxu, nwu, turn, colv, win_full, w);
+  if (wave == NW - 1) {
+    rebuild_turn_columns(lane, p, n_snap, R, n_pad, Cs, cps, cpt, fusion, ringu, stage, turn, colv, win_full, w);
     if (P.dbgT && lane == 0) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   }
 
@@ -287,7 +367,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     const int ntile = n_pad / 16, ngrp = (ntile + TU - 1) / TU;
     int grp = 0;
     if (lane == 0) grp = atomicAdd(&sh[0], 1);
-    grp = __shfl(grp, 0);
+    grp = __builtin_amdgcn_readfirstlane(grp);
     while (grp < ngrp) {
       int nxt = 0;
       if (lane == 0) nxt = atomicAdd(&sh[0], 1);
@@ -317,22 +397,14 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
               const int j = tile * 16 + 4 * kq + i;
               l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
             }
-            float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
+            const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
 #pragma unroll
             for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
             *(float4 *)(lg + (size_t)head * n_pad + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
           }
         }
       }
-      grp = __shfl(nxt, 0);
-    }
-    // each lane tracked only its own head: combine lanes of equal head, then spread all heads to lane 0
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float v = mx[g];
-#pragma unroll
-      for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
-      if (lane == 0) red[wave * 8 + g] = v;
+      grp = __builtin_amdgcn_readfirstlane(nxt);
     }
   } else {
     // plain FMAs on row-major K: LPR lanes share a row
@@ -349,7 +421,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     const int ntile = (n_pad + RPT - 1) / RPT;
     int tile = 0;
     if (lane == 0) tile = atomicAdd(&sh[0], 1);
-    tile = __shfl(tile, 0);
+    tile = __builtin_amdgcn_readfirstlane(tile);
     while (tile < ntile) {
       int nxt = 0;
       if (lane == 0) nxt = atomicAdd(&sh[0], 1);
@@ -380,21 +452,30 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
           if (chunk == 0 && j < n_pad) lg[(size_t)g * n_pad + j] = l;
         }
       }
-      tile = __shfl(nxt, 0);
+      tile = __builtin_amdgcn_readfirstlane(nxt);
     }
+  }
+  // a lane saw only some heads / rows: combine across the wave
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float v = mx[g];
+  for (int g = 0; g < G; ++g) {
+    const float v = wave_max_dpp(mx[g]);
+    if (lane == 0) red[wave * 8 + g] = v;
+  }
+
+  // ---- first V tile of this wave goes in flight now: it does not depend on the softmax
+  [[maybe_unused]] uint4 vpre[L::CB];
+  if constexpr (L::tiled) {
+    constexpr int CB = L::CB;
+    if (wave < n_pad / 32) {
 #pragma unroll
-      for (int m = LPR; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
-      if (lane == 0) red[wave * 8 + g] = v;
+      for (int cb = 0; cb < CB; ++cb) vpre[cb] = *(const uint4 *)(Vb + ((size_t)wave * CB + cb) * 512 + lane * 8);
     }
   }
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
-  __syncthreads();
+  lds_barrier();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
-  // ---- softmax: exact max, sum, weights
+  // ---- softmax: exact max, sum, weights (4 slots per thread and head at a time)
   float M[G], inv[G], pself[G];
   {
     // red holds [wave][8]: lane l looks at head l%8 of waves l/8 and l/8+8, then lanes of equal head combine
@@ -404,27 +485,29 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 #pragma unroll
     for (int m = 8; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
 #pragma unroll
-    for (int g = 0; g < G; ++g) M[g] = fmaxf(selfl[g], __shfl(v, g));
+    for (int g = 0; g < G; ++g) M[g] = fmaxf(selfl[g], lane_bcast(v, g));
   }
   {
     float zs[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
-    for (int j = tid; j < n_pad; j += NT) {
+    for (int jq = tid; jq < nq; jq += NT) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float e = exp2f(lg[(size_t)g * n_pad + j] - M[g]);
-        lg[(size_t)g * n_pad + j] = e;
-        zs[g] += e;
+        float4 *pl = (float4 *)(lg + (size_t)g * n_pad + 4 * jq);
+        float4 l = *pl;
+        l.x = exp2f(l.x - M[g]); l.y = exp2f(l.y - M[g]); l.z = exp2f(l.z - M[g]); l.w = exp2f(l.w - M[g]);
+        *pl = l;
+        zs[g] += (l.x + l.y) + (l.z + l.w);
       }
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float s = wave_sum(zs[g]);
+      const float s = wave_sum_dpp(zs[g]);
       if (lane == 0) red2[wave * 8 + g] = s;
     }
   }
-  __syncthreads();
+  lds_barrier();
   {
     float v = 0.f;
     if ((lane >> 3) < NW) v = red2[lane];
@@ -434,7 +517,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float es = exp2f(selfl[g] - M[g]);
-      const float z = es + __shfl(v, g);
+      const float z = es + lane_bcast(v, g);
       inv[g] = 1.0f / z;
       pself[g] = es * inv[g];
     }
@@ -443,45 +526,107 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   // ---- record the row, update per-column aggregates, fused scores, local argmin
   float bF = INFINITY;
   int bP = -1, bC = -1;
-  auto record = [&](int j, float nw_old, float sfx_old, int pj) {
-    float S = 0.f;
+  auto record4 = [&](int j0, float4 nw_old, float4 sfx_old, int4 pj4) {
+    float S[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float pg = lg[(size_t)g * n_pad + j] * inv[g];
-      lg[(size_t)g * n_pad + j] = pg;
-      S += pg;
+      float4 *pl = (float4 *)(lg + (size_t)g * n_pad + j0);
+      float4 l = *pl;
+      l.x *= inv[g]; l.y *= inv[g]; l.z *= inv[g]; l.w *= inv[g];
+      *pl = l;
+      S[0] += l.x; S[1] += l.y; S[2] += l.z; S[3] += l.w;
     }
-    if (j < n) ringu[(size_t)w * n + j] = S;
-    if (j < n_snap) {
-      if (j >= turn0 && j < turn0 + cps && p >= 1) { nw_old = 0.f; sfx_old = turn[j - turn0]; }
-      const float nv = fuse2(fusion, nw_old, S);
-      nwu[j] = nv;
-      const float F = fuse2(fusion, sfx_old, nv);
-      if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-      if (F < bF || (F == bF && pj > bP)) { bF = F; bP = pj; bC = j; }
+    *(float4 *)(ringu + (size_t)w * n_pad + j0) = make_float4(S[0], S[1], S[2], S[3]);
+    if (j0 < n_snap) {
+      float nwo[4] = {nw_old.x, nw_old.y, nw_old.z, nw_old.w};
+      const float sfo[4] = {sfx_old.x, sfx_old.y, sfx_old.z, sfx_old.w};
+      const int pj[4] = {pj4.x, pj4.y, pj4.z, pj4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = j0 + i;
+        float so = sfo[i];
+        if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
+        nwo[i] = fuse2(fusion, nwo[i], S[i]);
+        if (j < n_snap) {
+          const float F = fuse2(fusion, so, nwo[i]);
+          if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
+          if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
+        }
+      }
+      *(float4 *)(nwu + j0) = make_float4(nwo[0], nwo[1], nwo[2], nwo[3]);
     }
-    if (j == Cs + w) shf[0] = S;
+    if (Cs + w >= j0 && Cs + w < j0 + 4) {
+      const int i = Cs + w - j0;
+      shf[0] = i == 0 ? S[0] : i == 1 ? S[1] : i == 2 ? S[2] : S[3];
+    }
   };
 #pragma unroll
-  for (int i = 0; i < MAXJ; ++i) {
-    const int j = tid + i * NT;
-    if (j < n_pad) record(j, pn[i], ps[i], pp[i]);
+  for (int i = 0; i < MAXQ; ++i) {
+    const int jq = tid + i * NT;
+    if (jq < nq) record4(4 * jq, pn[i], ps[i], pp[i]);
   }
-  for (int j = tid + MAXJ * NT; j < n_pad; j += NT) {
-    float a = 0.f, b = 0.f;
-    int pj = -1;
-    if (j < n_snap) { a = nwu[j]; b = sfxu[(size_t)w * Cs + j]; pj = posu[j]; }
-    record(j, a, b, pj);
+  for (int jq = tid + MAXQ * NT; jq < nq; jq += NT) {
+    const int j0 = 4 * jq;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    int4 pj = make_int4(-1, -1, -1, -1);
+    if (j0 < n_snap) {
+      a = *(const float4 *)(nwu + j0);
+      b = *(const float4 *)(sfxu + (size_t)w * CsP + j0);
+      pj = *(const int4 *)(posu + j0);
+    }
+    record4(j0, a, b, pj);
   }
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    const float oF = __shfl_xor(bF, m);
-    const int oP = __shfl_xor(bP, m), oC = __shfl_xor(bC, m);
-    if (oF < bF || (oF == bF && oP > bP)) { bF = oF; bP = oP; bC = oC; }
-  }
+  wave_argmin(bF, bP, bC);
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
-  __syncthreads();
+  // rebuilt aggregates of this step's turn columns go out to their sfx rows
+  if (turn_n > 0) {
+    const int r0 = pmod(p - 2, R), rz = pmod(p - 1, R);
+    const int total = R * cpt;  // row R-1 of the staging area stands for the zeroed row (p-1) mod R
+    for (int idx = tid; idx < total; idx += NT) {
+      const int i = idx / cpt, cc = idx - i * cpt;
+      if (cc < turn_n) {
+        int r = r0 - i;
+        if (r < 0) r += R;
+        const bool last = i == R - 1;
+        sfxu[(size_t)(last ? rz : r) * CsP + turn0 + cc] = last ? 0.f : stage[idx];
+      }
+    }
+  }
+  lds_barrier();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 2] = wall_clock64();
+
+  // ---- decision (wave 0, before its share of the V pass): needs only the scores
+  if (wave == 0) {
+    float fd = 0.f;  // fused score of the token leaving the window
+    for (int a = lane; a < R; a += WAVE) {
+      const float v = a == R - 1 ? shf[0] : colv[a];
+      fd = fuse2(fusion, fd, v);
+    }
+    fd = fusion == 0 ? wave_sum_dpp(fd) : wave_max_dpp(fd);
+    float f = INFINITY;
+    int bp = -1, bc = -1;
+    if (lane < NW) { f = bestF[lane]; bp = bestP[lane]; bc = bestC[lane]; }
+    wave_argmin(f, bp, bc);
+    if (lane == 0) {
+      colv[R - 1] = shf[0];
+      int dest = -1, evicted = -1, ns = n_snap;
+      if (win_full) {
+        if (n_snap < Cs) {
+          dest = n_snap;
+          ns = n_snap + 1;
+        } else if (fd <= f) {  // tie: the token leaving the window has the higher position, it goes
+          evicted = p - R;
+        } else {
+          dest = bc;
+          evicted = bp;
+        }
+        if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + Cs] = fd;
+      }
+      sh[2] = dest;
+      sh[3] = evicted;
+      sh[4] = ns;
+    }
+  }
 
   // ---- V pass
   if constexpr (L::tiled) {
@@ -497,8 +642,13 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     // rounding of the output, is then the same in every run
     for (int tile = wave; tile < ntile; tile += NW) {
       uint4 b[CB];
+      if (tile == wave) {
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) b[cb] = *(const uint4 *)(Vb + ((size_t)tile * CB + cb) * 512 + lane * 8);
+        for (int cb = 0; cb < CB; ++cb) b[cb] = vpre[cb];
+      } else {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) b[cb] = *(const uint4 *)(Vb + ((size_t)tile * CB + cb) * 512 + lane * 8);
+      }
       bf16x8_t ahi, alo;
       {
         float pv[8];
@@ -524,7 +674,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
       }
     }
-    __syncthreads();  // every wave is done reading the weights: lg may be reused
+    lds_barrier();  // every wave is done reading the weights: lg may be reused
     // acc[cb][i] = O[head 4*kq + i][channel cb*16 + (lane & 15)]
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
@@ -572,7 +722,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       for (int e = 0; e < EPL; ++e)
 #pragma unroll
         for (int m = LPR; m < WAVE; m <<= 1) acc[g][e] += __shfl_xor(acc[g][e], m);
-    __syncthreads();  // every wave is done reading the weights: lg may be reused
+    lds_barrier();  // every wave is done reading the weights: lg may be reused
     if (rowsub == 0) {
 #pragma unroll
       for (int g = 0; g < G; ++g)
@@ -581,41 +731,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     }
   }
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
-
-  // ---- decision (wave 0)
-  if (wave == 0) {
-    float fd = 0.f;  // fused score of the token leaving the window
-    for (int a = lane; a < R; a += WAVE) {
-      const float v = a == R - 1 ? shf[0] : colv[a];
-      fd = fuse2(fusion, fd, v);
-    }
-    fd = fusion == 0 ? wave_sum(fd) : wave_max(fd);
-    if (lane == 0) {
-      colv[R - 1] = shf[0];
-      int dest = -1, evicted = -1, ns = n_snap;
-      if (win_full) {
-        if (n_snap < Cs) {
-          dest = n_snap;
-          ns = n_snap + 1;
-        } else {
-          float f = bestF[0];
-          int bp = bestP[0], bc = bestC[0];
-          for (int x = 1; x < NW; ++x)
-            if (bestF[x] < f || (bestF[x] == f && bestP[x] > bp)) { f = bestF[x]; bp = bestP[x]; bc = bestC[x]; }
-          if (fd <= f) {  // tie: the token leaving the window has the higher position, it goes
-            evicted = p - R;
-          } else {
-            dest = bc;
-            evicted = bp;
-          }
-        }
-        if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + Cs] = fd;
-      }
-      sh[2] = dest;
-      sh[3] = evicted;
-      sh[4] = ns;
-    }
-  }
+  // full barrier: besides the output partials in LDS, every global store of the record phase has landed
+  // before the compaction below rewrites some of the same addresses (ring[w][dest], nw[dest], sfx[.][dest])
   __syncthreads();
 
   // ---- output
@@ -661,10 +778,17 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     }
   }
   if (dest >= 0) {
-    for (int a = tid; a < R; a += NT) ringu[(size_t)pmod(p - R + 1 + a, R) * n + dest] = colv[a];
     if (wave == NW - 1) {
       if (lane == 0) posu[dest] = p - R;
-      move_scan_wave(lane, p, last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, Cs, nwu + dest);
+      move_scan_wave(lane, p, last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP, nwu + dest);
+    } else {
+      const int stride = NT - WAVE;
+      int r = pmod(p - R + 1 + tid, R);
+      for (int a = tid; a < R; a += stride) {
+        ringu[(size_t)r * n_pad + dest] = colv[a];
+        r += stride;
+        while (r >= R) r -= R;
+      }
     }
   }
   if (tid == 0) {

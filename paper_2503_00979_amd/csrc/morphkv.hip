@@ -37,7 +37,7 @@ int fail(int code, const char *fmt, ...) {
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct BufLayout {
-  int U, G, Cs, n, n_pad, cps, esz;
+  int U, G, Cs, CsP, n, n_pad, cps, cpt, esz;
   // cache
   size_t offK, offV, offPos, offMeta, cache_bytes;
   // scores_ring
@@ -78,26 +78,28 @@ BufLayout make_layout(const morphkv_config *c) {
   L.Cs = c->C + c->evict_every - 1;
   L.n = L.Cs + c->R;
   L.n_pad = (L.n + 31) / 32 * 32;  // K/V slot arrays are padded to whole tiles
+  L.CsP = (L.Cs + 31) / 32 * 32;   // row stride of the per-column state
   L.cps = (L.Cs + c->R - 1) / c->R;
+  L.cpt = turn_cols_padded(L.cps);
   L.esz = c->dtype == MORPHKV_DTYPE_F32 ? 4 : 2;
-  const size_t U = (size_t)L.U, n = (size_t)L.n, np = (size_t)L.n_pad, d = (size_t)c->head_dim, R = (size_t)c->R,
-               Cs = (size_t)L.Cs;
+  const size_t U = (size_t)L.U, np = (size_t)L.n_pad, d = (size_t)c->head_dim, R = (size_t)c->R,
+               CsP = (size_t)L.CsP;
   size_t o = 0;
   L.offK = o; o = align_up(o + U * np * d * L.esz);
   L.offV = o; o = align_up(o + U * np * d * L.esz);
-  L.offPos = o; o = align_up(o + U * n * 4);
+  L.offPos = o; o = align_up(o + U * np * 4);
   L.offMeta = o; o = align_up(o + U * META * 4);
   L.cache_bytes = o;
   o = 0;
-  L.offRing = o; o = align_up(o + U * R * n * 4);
-  L.offSfx = o; o = align_up(o + U * R * Cs * 4);
-  L.offNw = o; o = align_up(o + U * Cs * 4);
+  L.offRing = o; o = align_up(o + U * R * np * 4);
+  L.offSfx = o; o = align_up(o + U * R * CsP * 4);
+  L.offNw = o; o = align_up(o + U * CsP * 4);
   L.ring_bytes = o;
   o = 0;
   const size_t Nm = (size_t)c->max_prompt_len;
   L.offSrow = o; o = align_up(o + U * R * Nm * 4);
   L.offF = o; o = align_up(o + U * Nm * 4);
-  L.offSel = o; o = align_up(o + U * Cs * 4);
+  L.offSel = o; o = align_up(o + U * (size_t)L.Cs * 4);
   L.offPlen = o; o = align_up(o + (size_t)c->batch * 4);
   L.scratch_bytes = o;
   return L;
@@ -130,8 +132,8 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.nw = (float *)(h->ring + L.offNw);
   P.dbgF = h->dbgF;
   P.dbgT = h->dbgT;
-  P.Cs = L.Cs; P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads;
-  P.fusion = h->cfg.fusion; P.cps = L.cps; P.scale_log2 = h->scale_log2;
+  P.Cs = L.Cs; P.CsP = L.CsP; P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.Mq = h->cfg.n_q_heads;
+  P.Mkv = h->cfg.n_kv_heads; P.fusion = h->cfg.fusion; P.cps = L.cps; P.cpt = L.cpt; P.scale_log2 = h->scale_log2;
   return P;
 }
 
@@ -149,7 +151,7 @@ PrefillParams prefill_params(const morphkv_handle *h) {
   P.ring = (float *)(h->ring + L.offRing);
   P.sfx = (float *)(h->ring + L.offSfx);
   P.nw = (float *)(h->ring + L.offNw);
-  P.B = h->cfg.batch; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads; P.C = h->cfg.C; P.Cs = L.Cs;
+  P.B = h->cfg.batch; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads; P.C = h->cfg.C; P.Cs = L.Cs; P.CsP = L.CsP;
   P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.fusion = h->cfg.fusion; P.cps = L.cps;
   P.scale_log2 = h->scale_log2;
   return P;
@@ -167,7 +169,7 @@ int decode_threads(const morphkv_handle *h) {
 template <typename T, int D, int G>
 int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
   const int NT = decode_threads(h);
-  const size_t lds = decode_lds_bytes(P.n, P.n_pad, G, D, NT, P.R, P.cps);
+  const size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps);
   if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
   auto kern = decode_fused_kernel<T, D, G>;
   static size_t attr_set = 0;  // per instantiation
@@ -192,9 +194,9 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
   constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
   hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n + 255) / 256, U), dim3(256), 0, st, P);
+  hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n_pad + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(prefill_state_kernel, dim3((P.Cs + 255) / 256, U), dim3(256), 0, st, P);
+  hipLaunchKernelGGL(prefill_state_kernel, dim3((P.CsP + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }
@@ -321,7 +323,7 @@ int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, v
   const BufLayout &L = h->L;
   hipLaunchKernelGGL(export_positions_kernel, dim3((L.n + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
                      (const int32_t *)(h->cache + L.offPos), (const int32_t *)(h->cache + L.offMeta), pos, n_snap,
-                     L.n, L.U);
+                     L.n, L.n_pad);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }

@@ -17,7 +17,7 @@ struct PrefillParams {
   void *Kc, *Vc;
   int32_t *pos, *meta;
   float *ring, *sfx, *nw;
-  int32_t B, Mq, Mkv, C, Cs, R, n, n_pad, Nmax, fusion, cps;
+  int32_t B, Mq, Mkv, C, Cs, CsP, R, n, n_pad, Nmax, fusion, cps;
   float scale_log2;
 };
 
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
   const int b = (u / P.Mkv) % P.B, N = P.plen[b];
   const int n_snap = P.meta[(size_t)u * META];
   const int src = slot < P.n ? prefill_slot_source(P, u, slot, N, n_snap) : -1;
-  if (which == 0 && ck == 0 && slot < P.n) P.pos[(size_t)u * P.n + slot] = src;
+  if (which == 0 && ck == 0) P.pos[(size_t)u * P.n_pad + slot] = src;
   uint4 r = {0u, 0u, 0u, 0u};
   if (src >= 0) {
     const T *in = (which ? (const T *)P.V : (const T *)P.K) + ((size_t)u * P.Nmax + src) * D;
@@ -267,12 +267,12 @@ __global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
 // ---- P4b: recorded rows restricted to the resident columns
 __global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
   const int u = blockIdx.y, col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= P.n) return;
+  if (col >= P.n_pad) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R, Rw = N < R ? N : R;
   const int n_snap = P.meta[(size_t)u * META];
-  const int src = prefill_slot_source(P, u, col, N, n_snap);
+  const int src = col < P.n ? prefill_slot_source(P, u, col, N, n_snap) : -1;
   const float *Sr = P.Srow + (size_t)u * R * P.Nmax;
-  float *ringu = P.ring + (size_t)u * R * P.n;
+  float *ringu = P.ring + (size_t)u * R * P.n_pad;
   for (int r = 0; r < R; ++r) {
     // the window query whose position is congruent to r, if any
     int j = -1;
@@ -283,38 +283,37 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
       const int pj = N - Rw + j;
       if (src <= pj) v = Sr[(size_t)j * P.Nmax + src];
     }
-    ringu[(size_t)r * P.n + col] = v;
+    ringu[(size_t)r * P.n_pad + col] = v;
   }
 }
 
 // ---- P5: aggregate state of every older-token column, as of the end of step N-1
 __global__ __launch_bounds__(256) void prefill_state_kernel(PrefillParams P) {
   const int u = blockIdx.y, c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= P.Cs) return;
+  if (c >= P.CsP) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R;
   const int n_snap = P.meta[(size_t)u * META];
-  const float *ringu = P.ring + (size_t)u * R * P.n;
-  float *sfxu = P.sfx + (size_t)u * R * P.Cs;
+  const float *ringu = P.ring + (size_t)u * R * P.n_pad;
+  float *sfxu = P.sfx + (size_t)u * R * P.CsP;
   float nwv = 0.f;
   if (c < n_snap) {
     const int p_end = N - 1;
     const int p0 = last_rebuild_before(p_end, c / P.cps, R);
     nwv = column_scan(
-        p_end, p0, R, P.fusion, [&](int t) { return t >= 0 ? ringu[(size_t)pmod(t, R) * P.n + c] : 0.f; },
-        [&](int r, float x) { sfxu[(size_t)r * P.Cs + c] = x; });
+        p_end, p0, R, P.fusion, [&](int t) { return t >= 0 ? ringu[(size_t)pmod(t, R) * P.n_pad + c] : 0.f; },
+        [&](int r, float x) { sfxu[(size_t)r * P.CsP + c] = x; });
   } else {
-    for (int r = 0; r < R; ++r) sfxu[(size_t)r * P.Cs + c] = 0.f;
+    for (int r = 0; r < R; ++r) sfxu[(size_t)r * P.CsP + c] = 0.f;
   }
-  P.nw[(size_t)u * P.Cs + c] = nwv;
+  P.nw[(size_t)u * P.CsP + c] = nwv;
 }
 
 // ---- exports
 __global__ void export_positions_kernel(const int32_t *pos, const int32_t *meta, int32_t *out_pos,
-                                        int32_t *out_nsnap, int n, int U) {
+                                        int32_t *out_nsnap, int n, int n_pad) {
   const int u = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out_pos[(size_t)u * n + i] = pos[(size_t)u * n + i];
+  if (i < n) out_pos[(size_t)u * n + i] = pos[(size_t)u * n_pad + i];
   if (i == 0 && out_nsnap) out_nsnap[u] = meta[(size_t)u * META];
-  (void)U;
 }
 __global__ void export_evicted_kernel(const int32_t *meta, int32_t *out, int U) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
