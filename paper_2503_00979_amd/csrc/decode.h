@@ -142,87 +142,98 @@ __device__ inline void wave_argmin(float &f, int &p, int &c) {
 }
 
 // One wave rebuilds the aggregate state of the columns whose turn it is at the start of step p
-// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1, and fetches the column of the
-// token that leaves the window.  Results stay in LDS:
+// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1.  Results stay in LDS:
 //   stage[i*cpt + cc] = f(rows of steps p-1-i .. p-1) of column c0+cc   (i = 0..R-2), to be stored to
 //                       sfx row (p-2-i) mod R by the whole workgroup later;
 //   turn[cc]          = f(all R-1 rows): the old part of this step's score for that column.
-// Lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc).
-__device__ inline void rebuild_turn_columns(int lane, int p, int n_snap, int R, int rs, int Cs, int cps, int cpt,
-                                            int fusion, const float *ringu, float *stage, float *turn, float *colv,
-                                            bool win_full, int w) {
-  const int phi = pmod(p - 1, R), c0 = phi * cps;
-  int ncol = n_snap - c0;
-  ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
-  constexpr int B = 16;
-  // column of the token leaving the window (rows p-R+1 .. p-1), oldest first
-  {
-    float cv[B];
-    int r = pmod(p - R + 1 + lane, R);
-#pragma unroll
-    for (int k = 0; k < B; ++k) {
-      const int a = lane + k * WAVE;
-      cv[k] = 0.f;
-      if (a < R - 1 && win_full) cv[k] = ringu[(size_t)r * rs + Cs + w];
-      r += WAVE;
-      while (r >= R) r -= R;
-    }
-#pragma unroll
-    for (int k = 0; k < B; ++k) {
-      const int a = lane + k * WAVE;
-      if (a < R - 1) colv[a] = cv[k];
-    }
+// Lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc).  The first
+// batch of row loads is issued by begin() before the workgroup's first barrier, so that it is served
+// ahead of the K stream; finish() consumes it and loops over what is left.
+constexpr int RB = 16;  // rows per lane and batch
+struct TurnRebuild {
+  int lane, p, R, rs, cpt, fusion, c0, ncol, r_top;
+  const float *ringu;
+  // current column group
+  int cg, CP, lg2, Q, cc, q, c, Lc, i0, i1;
+  bool colok;
+
+  __device__ inline void init(int lane_, int p_, int n_snap, int R_, int rs_, int cps, int cpt_, int fusion_,
+                              const float *ringu_) {
+    lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_;
+    c0 = pmod(p - 1, R) * cps;
+    ncol = n_snap - c0;
+    ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
+    r_top = pmod(p - 1, R);  // ring row of row i = 0
   }
-  const int r_top = pmod(p - 1, R);  // ring row of row i = 0
-  for (int cg = 0; cg < ncol; cg += WAVE) {
+  __device__ inline void group(int cg_) {
+    cg = cg_;
     const int nc = ncol - cg < WAVE ? ncol - cg : WAVE;
-    int CP = 1, lg2 = 0;
+    CP = 1; lg2 = 0;
     while (CP < nc) { CP <<= 1; ++lg2; }
-    const int Q = WAVE >> lg2;
-    const int cc = lane & (CP - 1), q = lane >> lg2;
-    const bool colok = cc < nc;
-    const int c = c0 + cg + cc;
-    const int Lc = (R - 1 + Q - 1) / Q;
-    const int i0 = min(q * Lc, R - 1), i1 = min(i0 + Lc, R - 1);
-    float *st = stage + cg + cc;
-    // raw rows -> stage
-    for (int ib = i0; ib < i1; ib += B) {
-      float v[B];
-      int r = r_top - ib;
-      while (r < 0) r += R;
-#pragma unroll
-      for (int k = 0; k < B; ++k) {
-        v[k] = 0.f;
-        if (colok && ib + k < i1) v[k] = ringu[(size_t)r * rs + c];
-        r = r == 0 ? R - 1 : r - 1;
-      }
-#pragma unroll
-      for (int k = 0; k < B; ++k)
-        if (ib + k < i1) st[(size_t)(ib + k) * cpt] = v[k];
-    }
-    // running aggregate inside the chunk
-    float acc = 0.f;
-#pragma unroll 8
-    for (int i = i0; i < i1; ++i) {
-      acc = fuse2(fusion, acc, st[(size_t)i * cpt]);
-      st[(size_t)i * cpt] = acc;
-    }
-    // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
-    float incl = acc;
-    for (int s = CP; s < WAVE; s <<= 1) {
-      const float o = __shfl_up(incl, s);
-      if (lane >= s) incl = fuse2(fusion, incl, o);
-    }
-    float carry = __shfl_up(incl, CP);
-    if (q == 0) carry = 0.f;
-    const float total = __shfl(incl, (Q - 1) * CP + cc);
-    if (q > 0) {
-#pragma unroll 8
-      for (int i = i0; i < i1; ++i) st[(size_t)i * cpt] = fuse2(fusion, st[(size_t)i * cpt], carry);
-    }
-    if (q == 0) turn[cg + cc] = total;
+    Q = WAVE >> lg2;
+    cc = lane & (CP - 1); q = lane >> lg2;
+    colok = cc < nc;
+    c = c0 + cg + cc;
+    Lc = (R - 1 + Q - 1) / Q;
+    i0 = min(q * Lc, R - 1); i1 = min(i0 + Lc, R - 1);
   }
-}
+  // rows i0+b .. i0+b+RB-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
+  __device__ inline void load(int b, float (&v)[RB]) const {
+    // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is masked to
+    // the identity afterwards, so the batch is straight-line code with all loads in flight together
+    const int ib = i0 + b;
+    const int r0 = pmod(r_top - ib, R);
+    const float *colp = ringu + (colok ? c : c0);
+#pragma unroll
+    for (int k = 0; k < RB; ++k) {
+      int r = r0 - k;
+      while (r < 0) r += R;
+      v[k] = colp[r * rs];
+    }
+#pragma unroll
+    for (int k = 0; k < RB; ++k) v[k] = (colok && ib + k < i1) ? v[k] : 0.f;
+  }
+  __device__ inline void begin(float (&v)[RB]) {
+    if (ncol > 0) { group(0); load(0, v); }
+  }
+  __device__ inline void finish(float (&v)[RB], float *stage, float *turn) {
+    if (ncol <= 0) return;
+    int b = 0;
+    float acc = 0.f;
+    while (true) {
+      float *st = stage + cg + cc;
+      const int ib = i0 + b;
+#pragma unroll
+      for (int k = 0; k < RB; ++k)
+        if (ib + k < i1) {
+          acc = fuse2(fusion, acc, v[k]);
+          st[(ib + k) * cpt] = acc;
+        }
+      b += RB;
+      if (b >= Lc) {
+        // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
+        float incl = acc;
+        for (int s = CP; s < WAVE; s <<= 1) {
+          const float o = __shfl_up(incl, s);
+          if (lane >= s) incl = fuse2(fusion, incl, o);
+        }
+        float carry = __shfl_up(incl, CP);
+        if (q == 0) carry = 0.f;
+        const float total = __shfl(incl, (Q - 1) * CP + cc);
+        if (q > 0) {
+#pragma unroll 8
+          for (int i = i0; i < i1; ++i) st[i * cpt] = fuse2(fusion, st[i * cpt], carry);
+        }
+        if (q == 0) turn[cg + cc] = total;
+        if (cg + WAVE >= ncol) break;
+        group(cg + WAVE);
+        b = 0;
+        acc = 0.f;
+      }
+      load(b, v);
+    }
+  }
+};
 
 // One wave computes the aggregate state of a single column from its R row values colv[a] (row of step
 // p-R+1+a), as of the end of step p with rebuild point p0 (same result as column_scan), and stores it.
@@ -280,7 +291,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   int *bestC = (int *)(bestF + 16);       // [16]
   int *bestP = bestC + 16;                // [16]
   int *sh = bestP + 16;                   // [16] 0: K tile counter; 2: dest slot; 3: evicted; 4: new n_snap
-  float *shf = (float *)(sh + 16);        // [8]  0: weight of the new row on the token leaving the window
+  float *shf = (float *)(sh + 16);        // [16] 0: weight of the new row on the token leaving the window;
+                                          //      1..8: logits of the token against its own key
 
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1];
@@ -318,9 +330,33 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     }
   }
 
+  // ---- column of the token leaving the window (rows of steps p-R+1 .. p-1, oldest first): into registers
+  // now, into LDS after the K pass
+  constexpr int CVB = 4;  // R - 1 <= 1023 values over >= 256 threads
+  float cvr[CVB];
+  {
+    int r = pmod(p - R + 1 + tid, R);
+    const int rstep = NT % R;
+#pragma unroll
+    for (int k = 0; k < CVB; ++k) {
+      const int a = tid + k * NT;
+      cvr[k] = 0.f;
+      if (a < R - 1 && win_full) cvr[k] = ringu[r * n_pad + Cs + w];
+      r += rstep;
+      r -= r >= R ? R : 0;
+    }
+  }
+  // ---- the last wave rebuilds the columns whose turn it is: its first loads go out ahead of the K stream
+  TurnRebuild tr;
+  float rbv[RB];
+  if (wave == NW - 1) {
+    tr.init(lane, p, n_snap, R, n_pad, cps, cpt, fusion, ringu);
+    tr.begin(rbv);
+  }
+
   // ---- self logit (every lane ends up with all G values)
   float selfl[G];
-  {
+  if constexpr (!L::tiled) {
     constexpr int LPR = D / EPL;
     const int chunk = lane % LPR;
     uint4 r = ((const uint4 *)knew)[chunk];
@@ -344,7 +380,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 
   // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
   if (wave == NW - 1) {
-    rebuild_turn_columns(lane, p, n_snap, R, n_pad, Cs, cps, cpt, fusion, ringu, stage, turn, colv, win_full, w);
+    tr.finish(rbv, stage, turn);
     if (P.dbgT && lane == 0) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   }
 
@@ -363,6 +399,18 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       uint4 r = {0u, 0u, 0u, 0u};
       if (head < G) r = *(const uint4 *)(qb + (size_t)head * D + kb * 32 + kq * 8);
       qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
+    }
+    // wave 0: the token's own key as slot 0 of one more tile (other slots zero): its logits come out of
+    // the same MFMA and are handed to everybody through LDS
+    if (wave == 0) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        uint4 a = {0u, 0u, 0u, 0u};
+        if (head == 0) a = *(const uint4 *)(knew + kb * 32 + kq * 8);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), qfr[kb], acc, 0, 0, 0);
+      }
+      if (lane < G) shf[1 + lane] = acc[0] * P.scale_log2;  // lanes 0..15 (kq = 0): slot 0, head = lane
     }
     const int ntile = n_pad / 16, ngrp = (ntile + TU - 1) / TU;
     int grp = 0;
@@ -462,6 +510,12 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     if (lane == 0) red[wave * 8 + g] = v;
   }
 
+#pragma unroll
+  for (int k = 0; k < CVB; ++k) {
+    const int a = tid + k * NT;
+    if (a < R - 1) colv[a] = cvr[k];
+  }
+
   // ---- first V tile of this wave goes in flight now: it does not depend on the softmax
   [[maybe_unused]] uint4 vpre[L::CB];
   if constexpr (L::tiled) {
@@ -475,6 +529,10 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   lds_barrier();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
+  if constexpr (L::tiled) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) selfl[g] = shf[1 + g];
+  }
   // ---- softmax: exact max, sum, weights (4 slots per thread and head at a time)
   float M[G], inv[G], pself[G];
   {
@@ -641,14 +699,6 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     // tiles are dealt out statically here: the order in which a wave adds up its tiles, and with it the
     // rounding of the output, is then the same in every run
     for (int tile = wave; tile < ntile; tile += NW) {
-      uint4 b[CB];
-      if (tile == wave) {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) b[cb] = vpre[cb];
-      } else {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) b[cb] = *(const uint4 *)(Vb + ((size_t)tile * CB + cb) * 512 + lane * 8);
-      }
       bf16x8_t ahi, alo;
       {
         float pv[8];
@@ -669,9 +719,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       }
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
-        const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, b[cb]);
+        const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, vpre[cb]);
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, bv, acc[cb], 0, 0, 0);
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
+      }
+      // the next tile of this wave goes into the same registers
+      if (tile + NW < ntile) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+          vpre[cb] = *(const uint4 *)(Vb + ((size_t)(tile + NW) * CB + cb) * 512 + lane * 8);
       }
     }
     lds_barrier();  // every wave is done reading the weights: lg may be reused
