@@ -25,7 +25,7 @@
 
 namespace mkv {
 
-constexpr int META = 4;  // per unit: n_snap, next_pos, last_evicted, reserved
+constexpr int META = 4;  // per unit: n_snap, next_pos, last_evicted, next_pos mod R
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -42,6 +42,8 @@ struct DecodeParams {
   float *dbgF;             // nullable: [U][Cs+1]
   long long *dbgT;         // nullable: [U][8] phase time stamps (diagnostics)
   int32_t Cs, CsP, R, n, n_pad, Mq, Mkv, fusion, cps, cpt;
+  int32_t cpt_shift;       // log2(cpt) if cpt is a power of two, else -1
+  int32_t zig;             // parity of the step count: direction of the walk over the cache
   float scale_log2;        // softmax scale * log2(e)
 };
 
@@ -157,13 +159,13 @@ struct TurnRebuild {
   int cg, CP, lg2, Q, cc, q, c, Lc, i0, i1;
   bool colok;
 
-  __device__ inline void init(int lane_, int p_, int n_snap, int R_, int rs_, int cps, int cpt_, int fusion_,
-                              const float *ringu_) {
+  __device__ inline void init(int lane_, int p_, int wm1, int n_snap, int R_, int rs_, int cps, int cpt_,
+                              int fusion_, const float *ringu_) {
     lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_;
-    c0 = pmod(p - 1, R) * cps;
+    r_top = wm1;  // (p-1) mod R: ring row of row i = 0
+    c0 = wm1 * cps;
     ncol = n_snap - c0;
     ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
-    r_top = pmod(p - 1, R);  // ring row of row i = 0
   }
   __device__ inline void group(int cg_) {
     cg = cg_;
@@ -174,24 +176,25 @@ struct TurnRebuild {
     cc = lane & (CP - 1); q = lane >> lg2;
     colok = cc < nc;
     c = c0 + cg + cc;
-    Lc = (R - 1 + Q - 1) / Q;
+    Lc = (R - 1 + Q - 1) >> (6 - lg2);  // Q = 64 >> lg2
     i0 = min(q * Lc, R - 1); i1 = min(i0 + Lc, R - 1);
   }
   // rows i0+b .. i0+b+RB-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
   __device__ inline void load(int b, float (&v)[RB]) const {
-    // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is masked to
-    // the identity afterwards, so the batch is straight-line code with all loads in flight together
+    // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is ignored
+    // when the batch is consumed, so issuing it is straight-line code that waits for nothing
     const int ib = i0 + b;
-    const int r0 = pmod(r_top - ib, R);
-    const float *colp = ringu + (colok ? c : c0);
+    int r0 = r_top - ib;  // ib < R
+    r0 += r0 < 0 ? R : 0;
+    const unsigned coff = (unsigned)(colok ? c : c0);
 #pragma unroll
     for (int k = 0; k < RB; ++k) {
-      int r = r0 - k;
-      while (r < 0) r += R;
-      v[k] = colp[r * rs];
+      int r = r0 - k;       // rows of the chunk wrap at most once; past its end any row will do
+      r += r < 0 ? R : 0;
+      r = r < 0 ? 0 : r;
+      v[k] = ringu[(unsigned)(r * rs) + coff];
     }
-#pragma unroll
-    for (int k = 0; k < RB; ++k) v[k] = (colok && ib + k < i1) ? v[k] : 0.f;
+
   }
   __device__ inline void begin(float (&v)[RB]) {
     if (ncol > 0) { group(0); load(0, v); }
@@ -277,7 +280,6 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
   const int wave = tid / WAVE, lane = tid % WAVE;
   const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps, cpt = P.cpt;
-  const int lb = u / P.Mkv, kh = u % P.Mkv;
 
   // ---- LDS carve-up
   const size_t lgsz = max((size_t)G * n_pad, (size_t)NW * G * D);
@@ -294,25 +296,62 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   float *shf = (float *)(sh + 16);        // [16] 0: weight of the new row on the token leaving the window;
                                           //      1..8: logits of the token against its own key
 
+  const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
+  const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
+  const T *qb = (const T *)P.q + (size_t)u * G * D;  // query heads of unit u are rows u*G .. u*G+G-1
+  // The cache is walked forwards on even steps and backwards on odd ones: what the previous step read
+  // last is read first, so the part of K/V that still sits in the memory-side cache is hit instead of
+  // being pushed out by the stream just ahead of its use.
+  const bool zig = P.zig != 0;
+
+  // the unit's state is asked for first and looked at only after the first K loads are on their way
   const int32_t *meta = P.meta + (size_t)u * META;
-  const int n_snap = meta[0], p = meta[1];
-  const int w = p % R, nwin = p < R ? p : R;
+  const int n_snap = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
+
+  // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
+  // depends on the unit's state (the addresses do not)
+  constexpr int KBc = L::KB, TU = 2;  // TU tiles in flight per wave
+  [[maybe_unused]] uint4 ka[TU][KBc];
+  [[maybe_unused]] bf16x8_t qfr[KBc];
+  [[maybe_unused]] const int kntile = n_pad / 16, kngrp = (kntile + TU - 1) / TU;
+  auto load_kgroup = [&](int grp) {
+    const int gidx = zig ? kngrp - 1 - grp : grp;
+#pragma unroll
+    for (int t = 0; t < TU; ++t) {
+      const int tile = gidx * TU + t;
+      if (tile < kntile) {
+#pragma unroll
+        for (int kb = 0; kb < KBc; ++kb) ka[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
+      }
+    }
+  };
+  if constexpr (L::tiled) {
+    if (wave < kngrp) load_kgroup(wave);
+    const int head = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int kb = 0; kb < KBc; ++kb) {
+      uint4 r = {0u, 0u, 0u, 0u};
+      if (head < G) r = *(const uint4 *)(qb + (size_t)head * D + kb * 32 + kq * 8);
+      qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
+    }
+  }
+
+  const int nwin = p < R ? p : R;
+  if (P.dbgT && tid == 0 && nwin >= 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
+  const int wm1 = w == 0 ? R - 1 : w - 1;  // (p-1) mod R
   const bool win_full = p >= R;
-  const int turn0 = pmod(p - 1, R) * cps;  // first column rebuilt this step
+  const int turn0 = wm1 * cps;             // first column rebuilt this step
   int turn_n = n_snap - turn0;             // how many of them exist
   turn_n = turn_n < 0 ? 0 : (turn_n > cps ? cps : turn_n);
 
-  const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
-  const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
   float *ringu = P.ring + (size_t)u * R * n_pad;
   float *sfxu = P.sfx + (size_t)u * R * CsP;
   float *nwu = P.nw + (size_t)u * CsP;
   int32_t *posu = P.pos + (size_t)u * n_pad;
-  const T *qb = (const T *)P.q + ((size_t)(lb * P.Mq + kh * G)) * D;
   const T *knew = (const T *)P.k_new + (size_t)u * D;
   const T *vnew = (const T *)P.v_new + (size_t)u * D;
 
-  if (tid == 0) sh[0] = 0;
+  if (tid == 0) sh[0] = NW;  // every wave starts on the tile group of its own index
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
 
   // ---- prefetch of the per-column state this thread will update after the softmax (4 columns a group)
@@ -335,22 +374,20 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   constexpr int CVB = 4;  // R - 1 <= 1023 values over >= 256 threads
   float cvr[CVB];
   {
-    int r = pmod(p - R + 1 + tid, R);
-    const int rstep = NT % R;
 #pragma unroll
     for (int k = 0; k < CVB; ++k) {
-      const int a = tid + k * NT;
-      cvr[k] = 0.f;
-      if (a < R - 1 && win_full) cvr[k] = ringu[r * n_pad + Cs + w];
-      r += rstep;
+      const int a = tid + k * NT;  // row of step p-R+1+a lives in ring row (w+1+a) mod R
+      int r = w + 1 + a;
       r -= r >= R ? R : 0;
+      cvr[k] = 0.f;
+      if (a < R - 1 && win_full) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
     }
   }
   // ---- the last wave rebuilds the columns whose turn it is: its first loads go out ahead of the K stream
   TurnRebuild tr;
   float rbv[RB];
   if (wave == NW - 1) {
-    tr.init(lane, p, n_snap, R, n_pad, cps, cpt, fusion, ringu);
+    tr.init(lane, p, wm1, n_snap, R, n_pad, cps, cpt, fusion, ringu);
     tr.begin(rbv);
   }
 
@@ -391,15 +428,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 
   if constexpr (L::tiled) {
     // MFMA: A = 16 slots x 32 channels of K, B = 32 channels x 16 heads of q (heads >= G are zero)
-    constexpr int KB = L::KB, TU = 2;  // tiles in flight per wave
+    constexpr int KB = L::KB;
     const int head = lane & 15, kq = lane >> 4;
-    bf16x8_t qfr[KB];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-      uint4 r = {0u, 0u, 0u, 0u};
-      if (head < G) r = *(const uint4 *)(qb + (size_t)head * D + kb * 32 + kq * 8);
-      qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
-    }
     // wave 0: the token's own key as slot 0 of one more tile (other slots zero): its logits come out of
     // the same MFMA and are handed to everybody through LDS
     if (wave == 0) {
@@ -412,31 +442,20 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       }
       if (lane < G) shf[1 + lane] = acc[0] * P.scale_log2;  // lanes 0..15 (kq = 0): slot 0, head = lane
     }
-    const int ntile = n_pad / 16, ngrp = (ntile + TU - 1) / TU;
-    int grp = 0;
-    if (lane == 0) grp = atomicAdd(&sh[0], 1);
-    grp = __builtin_amdgcn_readfirstlane(grp);
+    const int ntile = kntile, ngrp = kngrp;
+    int grp = wave;
     while (grp < ngrp) {
       int nxt = 0;
       if (lane == 0) nxt = atomicAdd(&sh[0], 1);
-      uint4 a[TU][KB];
+      const int gidx = zig ? ngrp - 1 - grp : grp;
 #pragma unroll
       for (int t = 0; t < TU; ++t) {
-        const int tile = grp * TU + t;
-        if (tile < ntile) {
-#pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
-            a[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KB + kb) * 512 + lane * 8);
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < TU; ++t) {
-        const int tile = grp * TU + t;
+        const int tile = gidx * TU + t;
         if (tile < ntile) {
           f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[t][kb]), qfr[kb], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t][kb]), qfr[kb], acc, 0, 0, 0);
           // acc[i] = logit of slot tile*16 + 4*kq + i for head `head`
           if (head < G) {
             float l4[4];
@@ -453,6 +472,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         }
       }
       grp = __builtin_amdgcn_readfirstlane(nxt);
+      if (grp < ngrp) load_kgroup(grp);
     }
   } else {
     // plain FMAs on row-major K: LPR lanes share a row
@@ -467,9 +487,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       for (int e = 0; e < EPL; ++e) qf[g][e] *= P.scale_log2;
     }
     const int ntile = (n_pad + RPT - 1) / RPT;
-    int tile = 0;
-    if (lane == 0) tile = atomicAdd(&sh[0], 1);
-    tile = __builtin_amdgcn_readfirstlane(tile);
+    int tile = wave;
     while (tile < ntile) {
       int nxt = 0;
       if (lane == 0) nxt = atomicAdd(&sh[0], 1);
@@ -521,11 +539,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   if constexpr (L::tiled) {
     constexpr int CB = L::CB;
     if (wave < n_pad / 32) {
+      const int t0 = zig ? n_pad / 32 - 1 - wave : wave;
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) vpre[cb] = *(const uint4 *)(Vb + ((size_t)wave * CB + cb) * 512 + lane * 8);
+      for (int cb = 0; cb < CB; ++cb) vpre[cb] = *(const uint4 *)(Vb + ((size_t)t0 * CB + cb) * 512 + lane * 8);
     }
   }
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
   lds_barrier();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
@@ -638,10 +656,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
   // rebuilt aggregates of this step's turn columns go out to their sfx rows
   if (turn_n > 0) {
-    const int r0 = pmod(p - 2, R), rz = pmod(p - 1, R);
+    const int rz = wm1, r0 = wm1 == 0 ? R - 1 : wm1 - 1;  // (p-1) mod R, (p-2) mod R
     const int total = R * cpt;  // row R-1 of the staging area stands for the zeroed row (p-1) mod R
+    const int csh = P.cpt_shift;
     for (int idx = tid; idx < total; idx += NT) {
-      const int i = idx / cpt, cc = idx - i * cpt;
+      const int i = csh >= 0 ? idx >> csh : idx / cpt, cc = idx - i * cpt;
       if (cc < turn_n) {
         int r = r0 - i;
         if (r < 0) r += R;
@@ -698,7 +717,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     const int ntile = n_pad / 32;
     // tiles are dealt out statically here: the order in which a wave adds up its tiles, and with it the
     // rounding of the output, is then the same in every run
-    for (int tile = wave; tile < ntile; tile += NW) {
+    for (int ti = wave; ti < ntile; ti += NW) {
+      const int tile = zig ? ntile - 1 - ti : ti;
       bf16x8_t ahi, alo;
       {
         float pv[8];
@@ -724,10 +744,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
       }
       // the next tile of this wave goes into the same registers
-      if (tile + NW < ntile) {
+      if (ti + NW < ntile) {
+        const int tn = zig ? ntile - 1 - (ti + NW) : ti + NW;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
-          vpre[cb] = *(const uint4 *)(Vb + ((size_t)(tile + NW) * CB + cb) * 512 + lane * 8);
+          vpre[cb] = *(const uint4 *)(Vb + ((size_t)tn * CB + cb) * 512 + lane * 8);
       }
     }
     lds_barrier();  // every wave is done reading the weights: lg may be reused
@@ -803,7 +824,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) psg = gg == g ? pself[gg] : psg;
     o = fmaf(psg, vn, o);
-    P.out[((size_t)(lb * P.Mq + kh * G + g)) * D + ch] = o;
+    P.out[((size_t)u * G + g) * D + ch] = o;
   }
 
   // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot
@@ -839,7 +860,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       move_scan_wave(lane, p, last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP, nwu + dest);
     } else {
       const int stride = NT - WAVE;
-      int r = pmod(p - R + 1 + tid, R);
+      int r = (w + 1 + tid) % R;
       for (int a = tid; a < R; a += stride) {
         ringu[(size_t)r * n_pad + dest] = colv[a];
         r += stride;
@@ -853,6 +874,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     m[0] = sh[4];
     m[1] = p + 1;
     m[2] = sh[3];
+    m[3] = w + 1 == R ? 0 : w + 1;
     if (P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
   }
 }

@@ -114,6 +114,7 @@ struct morphkv_handle {
   float *dbgF;
   long long *dbgT;
   bool prefilled;
+  unsigned steps;  // decode steps since the last prefill
   float scale_log2;
   int n_cu;
 };
@@ -132,6 +133,10 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.nw = (float *)(h->ring + L.offNw);
   P.dbgF = h->dbgF;
   P.dbgT = h->dbgT;
+  P.zig = (int32_t)(h->steps & 1u);
+  P.cpt_shift = -1;
+  for (int sft = 0; sft < 16; ++sft)
+    if ((1 << sft) == L.cpt) P.cpt_shift = sft;
   P.Cs = L.Cs; P.CsP = L.CsP; P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.Mq = h->cfg.n_q_heads;
   P.Mkv = h->cfg.n_kv_heads; P.fusion = h->cfg.fusion; P.cps = L.cps; P.cpt = L.cpt; P.scale_log2 = h->scale_log2;
   return P;
@@ -268,6 +273,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   h->dbgF = nullptr;
   h->dbgT = nullptr;
   h->prefilled = false;
+  h->steps = 0;
   const double scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
   h->scale_log2 = (float)(scale * 1.4426950408889634074);
   h->n_cu = 0;
@@ -303,6 +309,7 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
   int rc = dispatch_prefill(h, P, st);
   if (rc) return rc;
   h->prefilled = true;
+  h->steps = 0;
   return MORPHKV_OK;
 }
 
@@ -313,7 +320,9 @@ int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, con
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step before prefill_select");
   DecodeParams P = decode_params(h);
   P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
-  return dispatch_decode(h, P, (hipStream_t)stream);
+  const int rc = dispatch_decode(h, P, (hipStream_t)stream);
+  if (rc == MORPHKV_OK) ++h->steps;
+  return rc;
 }
 
 int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream) {
