@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=5, help="timed repetitions of --steps; the median is reported")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (units are independent caches; there is no collective to "
@@ -159,6 +161,13 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         times.append((ev0.elapsed_time(ev1) / 1e3, wall))
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            binding.calib_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     times.sort()
     dev_s, wall_s = times[len(times) // 2]
     sec = max(dev_s, 0.0)                      # HIP events on the launch stream bracket exactly the K kernels

@@ -106,6 +106,11 @@ int morphkv_capture_scores(morphkv_handle *h, float *F);
  * softmax/record, 3 end of the V pass, 4 end of the step. */
 int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks);
 
+/* Diagnostics: a plain device-to-device copy of `bytes` (multiple of 16) with a grid-stride kernel,
+ * enqueued on the stream.  It moves a known number of bytes each way and serves as the yardstick the
+ * profiler's HBM counters are scaled by. */
+int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 const char *morphkv_last_error(void);
 
 #ifdef __cplusplus

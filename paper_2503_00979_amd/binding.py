@@ -21,7 +21,7 @@ _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_capture_scores",
-           "morphkv_capture_phase_clocks", "morphkv_last_error")
+           "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_last_error")
 
 
 class MorphKVError(RuntimeError):
@@ -59,6 +59,7 @@ def load_library():
     L.morphkv_export_evicted.argtypes = [vp, vp, vp]
     L.morphkv_capture_scores.argtypes = [vp, vp]
     L.morphkv_capture_phase_clocks.argtypes = [vp, vp]
+    L.morphkv_calib_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.morphkv_last_error.argtypes = []
     L.morphkv_last_error.restype = C.c_char_p
     for f in EXPORTS[:-1]:
@@ -90,6 +91,14 @@ def morphkv_sizes(cfg: Config):
     a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(load_library().morphkv_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)))
     return a.value, b.value, c.value
+
+
+def calib_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Plain device copy through the library's yardstick kernel (same byte count read and written)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    stream = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream)
+    _check(load_library().morphkv_calib_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, stream))
 
 
 class MorphKV:

@@ -354,6 +354,17 @@ int morphkv_capture_scores(morphkv_handle *h, float *F) {
   return MORPHKV_OK;
 }
 
+int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream) {
+  if (!dst || !src || (bytes & 15)) return fail(MORPHKV_EINVAL, "calib_copy needs non-null pointers and a multiple of 16 bytes");
+  const size_t nvec = bytes / 16;
+  if (nvec == 0) return MORPHKV_OK;
+  const unsigned blocks = (unsigned)((nvec + 1023) / 1024 > 65535u * 16u ? 65535u * 16u : (nvec + 1023) / 1024);
+  hipLaunchKernelGGL(calib_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst,
+                     (const uint4 *)src, nvec);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
 int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   h->dbgT = clocks;

@@ -308,6 +308,12 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(PrefillParams P) {
   P.nw[(size_t)u * P.CsP + c] = nwv;
 }
 
+// ---- plain copy: the yardstick hardware counters are scaled by (known bytes read and written)
+__global__ __launch_bounds__(256) void calib_copy_kernel(uint4 *dst, const uint4 *src, size_t nvec) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 // ---- exports
 __global__ void export_positions_kernel(const int32_t *pos, const int32_t *meta, int32_t *out_pos,
                                         int32_t *out_nsnap, int n, int n_pad) {
