@@ -45,13 +45,13 @@ def read_traffic(name: str):
     return None
 
 
-def cpu_baseline(wl, Qw, K, V, dec_inputs, n_steps=12):
+def cpu_baseline(wl, Qw, K, V, dec_inputs, n_steps=200, max_seqs=8):
     """The oracle as it stands, on a bounded sample: sequences whose cache is full right after the
     prompt (steady state from the first step), all their KV heads."""
     import torch
     from oracle import ref as oref
     full = [b for b in range(wl.batch) if wl.prompt_lens[b] - wl.R >= wl.C]
-    sample = full[:4] if len(full) >= 4 else (full or [0])
+    sample = full[:max_seqs] if full else [0]
     wl_s = wl.with_batch_subset(sample)
     ix = torch.tensor(sample, device=K.device)
     Qs, Ks, Vs = (t.index_select(1, ix).cpu().contiguous() for t in (Qw, K, V))
