@@ -103,7 +103,8 @@ int morphkv_capture_scores(morphkv_handle *h, float *F);
 
 /* Diagnostics: clocks device [U][8] int64, or NULL to stop.  While set, every decode step stores the
  * constant-rate device clock (100 MHz) per unit at: 0 kernel start, 1 end of the K pass, 2 end of
- * softmax/record, 3 end of the V pass, 4 end of the step. */
+ * softmax/record, 3 end of the V pass, 4 end of the step, 5 / 6 last / first wave reaches the first
+ * barrier, 7 first barrier passed. */
 int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks);
 
 /* Diagnostics: a plain device-to-device copy of `bytes` (multiple of 16) with a grid-stride kernel,

@@ -85,7 +85,7 @@ __host__ __device__ inline int turn_cols_padded(int cps) {
 
 // LDS bytes of decode_fused_kernel
 inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps) {
-  const size_t lg = (size_t)G * n_pad, om = (size_t)(NT / 64) * G * D;
+  const size_t lg = (size_t)G * (n_pad + 4), om = (size_t)(NT / 64) * G * D;
   const size_t cpt = (size_t)turn_cols_padded(cps);
   const size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
                     16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
@@ -282,8 +282,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps, cpt = P.cpt;
 
   // ---- LDS carve-up
-  const size_t lgsz = max((size_t)G * n_pad, (size_t)NW * G * D);
-  float *lg = smem;                       // [G][n_pad] logits -> exp -> weights; later [NW][G][D] output partials
+  // rows of the weight array are n_pad + 4 floats apart: the heads then start 4 banks apart and the 16-byte
+  // accesses of the MFMA passes (4 heads x 4 slot groups) spread over all 32 banks
+  const int lgs = n_pad + 4;
+  const size_t lgsz = max((size_t)G * lgs, (size_t)NW * G * D);
+  float *lg = smem;                       // [G][lgs] logits -> exp -> weights; later [NW][G][D] output partials
   float *stage = lg + lgsz;               // [R][cpt] rebuilt aggregates on their way to the sfx rows
   float *turn = stage + (size_t)R * cpt;  // [cpt] old-part aggregate of the columns rebuilt this step
   float *colv = turn + cpt;               // [R]   column of the token leaving the window, oldest row first
@@ -337,7 +340,6 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   }
 
   const int nwin = p < R ? p : R;
-  if (P.dbgT && tid == 0 && nwin >= 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
   const int wm1 = w == 0 ? R - 1 : w - 1;  // (p-1) mod R
   const bool win_full = p >= R;
   const int turn0 = wm1 * cps;             // first column rebuilt this step
@@ -388,7 +390,6 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   float rbv[RB];
   if (wave == NW - 1) {
     tr.init(lane, p, wm1, n_snap, R, n_pad, cps, cpt, fusion, ringu);
-    tr.begin(rbv);
   }
 
   // ---- self logit (every lane ends up with all G values)
@@ -412,13 +413,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       selfl[g] = d * P.scale_log2;
     }
   }
+  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
+  if (P.dbgT && tid == NT - 64) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   lds_barrier();  // the tile counter is initialised
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
 
   // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
   if (wave == NW - 1) {
+    tr.begin(rbv);
     tr.finish(rbv, stage, turn);
-    if (P.dbgT && lane == 0) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   }
 
   // ---- K pass
@@ -467,7 +470,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
             const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
 #pragma unroll
             for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
-            *(float4 *)(lg + (size_t)head * n_pad + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
+            *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
           }
         }
       }
@@ -515,7 +518,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
           for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m);
           const float l = ok[i] ? d : -INFINITY;
           mx[g] = fmaxf(mx[g], l);
-          if (chunk == 0 && j < n_pad) lg[(size_t)g * n_pad + j] = l;
+          if (chunk == 0 && j < n_pad) lg[(size_t)g * lgs + j] = l;
         }
       }
       tile = __builtin_amdgcn_readfirstlane(nxt);
@@ -570,7 +573,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     for (int jq = tid; jq < nq; jq += NT) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float4 *pl = (float4 *)(lg + (size_t)g * n_pad + 4 * jq);
+        float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
         l.x = exp2f(l.x - M[g]); l.y = exp2f(l.y - M[g]); l.z = exp2f(l.z - M[g]); l.w = exp2f(l.w - M[g]);
         *pl = l;
@@ -606,7 +609,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     float S[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float4 *pl = (float4 *)(lg + (size_t)g * n_pad + j0);
+      float4 *pl = (float4 *)(lg + (size_t)g * lgs + j0);
       float4 l = *pl;
       l.x *= inv[g]; l.y *= inv[g]; l.z *= inv[g]; l.w *= inv[g];
       *pl = l;
@@ -723,8 +726,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       {
         float pv[8];
         if (head < G) {
-          const float4 x = *(const float4 *)(lg + (size_t)head * n_pad + tile * 32 + kq * 8);
-          const float4 y = *(const float4 *)(lg + (size_t)head * n_pad + tile * 32 + kq * 8 + 4);
+          const float4 x = *(const float4 *)(lg + (size_t)head * lgs + tile * 32 + kq * 8);
+          const float4 y = *(const float4 *)(lg + (size_t)head * lgs + tile * 32 + kq * 8 + 4);
           pv[0] = x.x; pv[1] = x.y; pv[2] = x.z; pv[3] = x.w; pv[4] = y.x; pv[5] = y.y; pv[6] = y.z; pv[7] = y.w;
         } else {
 #pragma unroll
@@ -786,7 +789,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
           Elem<T>::unpack(r[i], vf);
 #pragma unroll
           for (int g = 0; g < G; ++g) {
-            const float pg = lg[(size_t)g * n_pad + j];
+            const float pg = lg[(size_t)g * lgs + j];
 #pragma unroll
             for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pg, vf[e], acc[g][e]);
           }

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -117,6 +118,7 @@ struct morphkv_handle {
   unsigned steps;  // decode steps since the last prefill
   float scale_log2;
   int n_cu;
+  int force_threads;  // MORPHKV_DECODE_THREADS (256/512/1024): tuning override, 0 = choose
 };
 
 namespace {
@@ -165,6 +167,7 @@ PrefillParams prefill_params(const morphkv_handle *h) {
 // threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
 // over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
 int decode_threads(const morphkv_handle *h) {
+  if (h->force_threads) return h->force_threads;
   const int U = h->L.U, cu = h->n_cu > 0 ? h->n_cu : 256;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
@@ -277,6 +280,11 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   const double scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
   h->scale_log2 = (float)(scale * 1.4426950408889634074);
   h->n_cu = 0;
+  h->force_threads = 0;
+  if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
+    const int v = std::atoi(e);
+    if (v == 256 || v == 512 || v == 1024) h->force_threads = v;
+  }
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
