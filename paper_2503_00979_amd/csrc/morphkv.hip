@@ -193,7 +193,10 @@ int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st
 template <typename T, int D, int G>
 int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
   const int U = h->L.U;
-  hipLaunchKernelGGL((prefill_rows_kernel<T, D, G>), dim3(P.R, U), dim3(256), 0, st, P);
+  if constexpr (Layout<T, D>::tiled)
+    hipLaunchKernelGGL((prefill_rows_mfma_kernel<D, G>), dim3((P.R + 15) / 16, U), dim3(256), 0, st, P);
+  else
+    hipLaunchKernelGGL((prefill_rows_kernel<T, D, G>), dim3(P.R, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(prefill_fuse_kernel, dim3((P.Nmax + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
