@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmorphkv.so")
+LIB_PATH = os.environ.get("MORPHKV_LIB") or os.path.join(_HERE, "libmorphkv.so")  # MORPHKV_LIB: another build
 
 OK, EINVAL, ESTATE, EHIP = 0, -1, -2, -3
 FUSION = {"sum": 0, "max": 1}

@@ -275,6 +275,10 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
+  // tile groups (K) and tiles (V) a wave keeps in flight.  Two of each (which needs groups of at most 512
+  // threads for the registers) was measured and brought nothing: the passes are not bound by the depth
+  // of a wave's request queue.
+  constexpr int KBUF = 1, VBUF = 1;
   extern __shared__ __align__(16) float smem[];
 
   const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
@@ -314,22 +318,22 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
   // depends on the unit's state (the addresses do not)
   constexpr int KBc = L::KB, TU = 2;  // TU tiles in flight per wave
-  [[maybe_unused]] uint4 ka[TU][KBc];
+  [[maybe_unused]] uint4 ka[KBUF][TU][KBc];
   [[maybe_unused]] bf16x8_t qfr[KBc];
   [[maybe_unused]] const int kntile = n_pad / 16, kngrp = (kntile + TU - 1) / TU;
-  auto load_kgroup = [&](int grp) {
+  auto load_kgroup = [&](uint4 (&dst)[TU][KBc], int grp) {
     const int gidx = zig ? kngrp - 1 - grp : grp;
 #pragma unroll
     for (int t = 0; t < TU; ++t) {
       const int tile = gidx * TU + t;
       if (tile < kntile) {
 #pragma unroll
-        for (int kb = 0; kb < KBc; ++kb) ka[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
+        for (int kb = 0; kb < KBc; ++kb) dst[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
       }
     }
   };
   if constexpr (L::tiled) {
-    if (wave < kngrp) load_kgroup(wave);
+    if (wave < kngrp) load_kgroup(ka[0], wave);
     const int head = lane & 15, kq = lane >> 4;
 #pragma unroll
     for (int kb = 0; kb < KBc; ++kb) {
@@ -353,7 +357,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   const T *knew = (const T *)P.k_new + (size_t)u * D;
   const T *vnew = (const T *)P.v_new + (size_t)u * D;
 
-  if (tid == 0) sh[0] = NW;  // every wave starts on the tile group of its own index
+  if (tid == 0) sh[0] = 2 * NW;  // every wave starts on the tile groups wave and wave + NW
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
 
   // ---- prefetch of the per-column state this thread will update after the softmax (4 columns a group)
@@ -413,6 +417,42 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       selfl[g] = d * P.scale_log2;
     }
   }
+  // ---- K pass, first part: each wave works off the tile group it asked for at the very start and asks
+  // for a second one, all before the workgroup's first barrier (late waves do not hold the others up)
+  float mx[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) mx[g] = -INFINITY;
+  [[maybe_unused]] const int head = lane & 15, kq = lane >> 4;
+  auto process_kgroup = [&](const uint4 (&src)[TU][KBc], int grp) {
+    const int gidx = zig ? kngrp - 1 - grp : grp;
+#pragma unroll
+    for (int t = 0; t < TU; ++t) {
+      const int tile = gidx * TU + t;
+      if (tile < kntile) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KBc; ++kb)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, src[t][kb]), qfr[kb], acc, 0, 0, 0);
+        // acc[i] = logit of slot tile*16 + 4*kq + i for head `head`
+        if (head < G) {
+          float l4[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int j = tile * 16 + 4 * kq + i;
+            l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
+          }
+          const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
+#pragma unroll
+          for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
+          *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
+        }
+      }
+    }
+  };
+  if constexpr (L::tiled) {
+    if (wave < kngrp) process_kgroup(ka[0], wave);
+    if (wave + NW < kngrp) load_kgroup(ka[0], wave + NW);
+  }
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
   if (P.dbgT && tid == NT - 64) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   lds_barrier();  // the tile counter is initialised
@@ -424,15 +464,10 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     tr.finish(rbv, stage, turn);
   }
 
-  // ---- K pass
-  float mx[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) mx[g] = -INFINITY;
-
+  // ---- K pass, the rest
   if constexpr (L::tiled) {
     // MFMA: A = 16 slots x 32 channels of K, B = 32 channels x 16 heads of q (heads >= G are zero)
     constexpr int KB = L::KB;
-    const int head = lane & 15, kq = lane >> 4;
     // wave 0: the token's own key as slot 0 of one more tile (other slots zero): its logits come out of
     // the same MFMA and are handed to everybody through LDS
     if (wave == 0) {
@@ -445,37 +480,32 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       }
       if (lane < G) shf[1 + lane] = acc[0] * P.scale_log2;  // lanes 0..15 (kq = 0): slot 0, head = lane
     }
-    const int ntile = kntile, ngrp = kngrp;
-    int grp = wave;
-    while (grp < ngrp) {
-      int nxt = 0;
-      if (lane == 0) nxt = atomicAdd(&sh[0], 1);
-      const int gidx = zig ? ngrp - 1 - grp : grp;
+    const int ngrp = kngrp;
+    // each buffer of the wave holds one group in flight; the first came with the wave's index, the
+    // others and all later ones are drawn from the shared counter
+    int gq[KBUF];
+    gq[0] = wave + NW;  // in flight since before the barrier
 #pragma unroll
-      for (int t = 0; t < TU; ++t) {
-        const int tile = gidx * TU + t;
-        if (tile < ntile) {
-          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int b = 1; b < KBUF; ++b) {
+      int x = 0;
+      if (lane == 0) x = atomicAdd(&sh[0], 1);
+      gq[b] = __builtin_amdgcn_readfirstlane(x);
+      if (gq[b] < ngrp) load_kgroup(ka[b], gq[b]);
+    }
+    bool more = true;
+    while (more) {
+      more = false;
 #pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t][kb]), qfr[kb], acc, 0, 0, 0);
-          // acc[i] = logit of slot tile*16 + 4*kq + i for head `head`
-          if (head < G) {
-            float l4[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int j = tile * 16 + 4 * kq + i;
-              l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
-            }
-            const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
-#pragma unroll
-            for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
-            *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
-          }
+      for (int b = 0; b < KBUF; ++b) {
+        if (gq[b] < ngrp) {
+          int nxt = 0;
+          if (lane == 0) nxt = atomicAdd(&sh[0], 1);
+          process_kgroup(ka[b], gq[b]);
+          gq[b] = __builtin_amdgcn_readfirstlane(nxt);
+          if (gq[b] < ngrp) load_kgroup(ka[b], gq[b]);
+          more = true;
         }
       }
-      grp = __builtin_amdgcn_readfirstlane(nxt);
-      if (grp < ngrp) load_kgroup(grp);
     }
   } else {
     // plain FMAs on row-major K: LPR lanes share a row
@@ -491,9 +521,10 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     }
     const int ntile = (n_pad + RPT - 1) / RPT;
     int tile = wave;
+    bool first = true;  // tiles wave and wave + NW are this wave's by right, the rest come from the counter
     while (tile < ntile) {
-      int nxt = 0;
-      if (lane == 0) nxt = atomicAdd(&sh[0], 1);
+      int nxt = wave + NW;
+      if (!first && lane == 0) nxt = atomicAdd(&sh[0], 1);
       uint4 r[UNR];
       bool ok[UNR];
 #pragma unroll
@@ -521,7 +552,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
           if (chunk == 0 && j < n_pad) lg[(size_t)g * lgs + j] = l;
         }
       }
-      tile = __builtin_amdgcn_readfirstlane(nxt);
+      tile = first ? nxt : __builtin_amdgcn_readfirstlane(nxt);
+      first = false;
     }
   }
   // a lane saw only some heads / rows: combine across the wave
@@ -538,14 +570,16 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   }
 
   // ---- first V tile of this wave goes in flight now: it does not depend on the softmax
-  [[maybe_unused]] uint4 vpre[L::CB];
-  if constexpr (L::tiled) {
-    constexpr int CB = L::CB;
-    if (wave < n_pad / 32) {
-      const int t0 = zig ? n_pad / 32 - 1 - wave : wave;
+  [[maybe_unused]] uint4 vbuf[VBUF][L::CB];
+  auto load_vtile = [&](uint4 (&dst)[L::CB], int ti) {
+    const int tile = zig ? n_pad / 32 - 1 - ti : ti;
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) vpre[cb] = *(const uint4 *)(Vb + ((size_t)t0 * CB + cb) * 512 + lane * 8);
-    }
+    for (int cb = 0; cb < L::CB; ++cb) dst[cb] = *(const uint4 *)(Vb + ((size_t)tile * L::CB + cb) * 512 + lane * 8);
+  };
+  if constexpr (L::tiled) {
+#pragma unroll
+    for (int b = 0; b < VBUF; ++b)
+      if (wave + b * NW < n_pad / 32) load_vtile(vbuf[b], wave + b * NW);
   }
   lds_barrier();
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
@@ -720,7 +754,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     const int ntile = n_pad / 32;
     // tiles are dealt out statically here: the order in which a wave adds up its tiles, and with it the
     // rounding of the output, is then the same in every run
-    for (int ti = wave; ti < ntile; ti += NW) {
+    auto process_vtile = [&](const uint4 (&src)[CB], int ti) {
       const int tile = zig ? ntile - 1 - ti : ti;
       bf16x8_t ahi, alo;
       {
@@ -742,16 +776,20 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       }
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
-        const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, vpre[cb]);
+        const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, src[cb]);
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, bv, acc[cb], 0, 0, 0);
         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
       }
-      // the next tile of this wave goes into the same registers
-      if (ti + NW < ntile) {
-        const int tn = zig ? ntile - 1 - (ti + NW) : ti + NW;
+    };
+    for (int ti0 = wave; ti0 < ntile; ti0 += VBUF * NW) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-          vpre[cb] = *(const uint4 *)(Vb + ((size_t)tn * CB + cb) * 512 + lane * 8);
+      for (int b = 0; b < VBUF; ++b) {
+        const int ti = ti0 + b * NW;
+        if (ti < ntile) {
+          process_vtile(vbuf[b], ti);
+          // the tile this buffer holds next goes into the same registers
+          if (ti + VBUF * NW < ntile) load_vtile(vbuf[b], ti + VBUF * NW);
+        }
       }
     }
     lds_barrier();  // every wave is done reading the weights: lg may be reused
