@@ -52,7 +52,8 @@ typedef struct morphkv_config {
   int32_t R;              /* recent window (H1), 1..1024 */
   int32_t fusion;         /* MORPHKV_FUSION_* */
   int32_t dtype;          /* element type of q/K/V: MORPHKV_DTYPE_* */
-  int32_t evict_every;    /* T of Appendix A.5; this build supports 1 */
+  int32_t evict_every;    /* T of Appendix A.5, 1..64: selection runs at steps whose token position is a
+                             multiple of T; in between up to C+T-1 older tokens are held */
   int32_t max_prompt_len; /* largest Nmax that will be passed to prefill_select */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */
 } morphkv_config;
@@ -90,14 +91,18 @@ int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, con
                         void *stream /* hipStream_t */);
 
 /* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
- *  pos    [U][C+R] int32: slots [0,C) = older tokens (-1 = empty), [C,C+R) = window slot (position mod R)
+ *  pos    [U][Cs+R] int32, Cs = C+evict_every-1: slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
+ *         window slot (position mod R)
  *  n_snap [U]      int32: older tokens currently held */
 int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream);
-/* evicted [U] int32 device: position evicted by the last decode step, -1 if none. */
+/* evicted [U] int32 device: position evicted by the last decode step, -1 if none (with evict_every > 1:
+ * the first of them). */
 int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream);
+/* evicted [U][evict_every] int32 device: every position evicted by the last decode step, -1 padded. */
+int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *stream);
 
 /* Optional capture of the fused scores each decode step takes its decision on:
- * F device [U][C+1] fp32 (slot order; [C] = the token leaving the window), or NULL to stop.
+ * F device [U][Cs+1] fp32 (slot order; [Cs] = the token leaving the window), or NULL to stop.
  * Costs 4 bytes written per older token per step while enabled. */
 int morphkv_capture_scores(morphkv_handle *h, float *F);
 

@@ -20,7 +20,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
-           "morphkv_export_positions", "morphkv_export_evicted", "morphkv_capture_scores",
+           "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
            "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_last_error")
 
 
@@ -57,6 +57,7 @@ def load_library():
     L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
     L.morphkv_export_evicted.argtypes = [vp, vp, vp]
+    L.morphkv_export_evicted_list.argtypes = [vp, vp, vp]
     L.morphkv_capture_scores.argtypes = [vp, vp]
     L.morphkv_capture_phase_clocks.argtypes = [vp, vp]
     L.morphkv_calib_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -186,6 +187,12 @@ class MorphKV:
     def export_evicted(self):
         ev = torch.empty(self.U, dtype=torch.int32, device=self.device)
         _check(self.lib.morphkv_export_evicted(self._h, _dev_ptr(ev), self._stream()))
+        return ev
+
+    def export_evicted_list(self):
+        """[U, evict_every] int32: every position the last step evicted, -1 padded."""
+        ev = torch.empty(self.U, self.cfg.evict_every, dtype=torch.int32, device=self.device)
+        _check(self.lib.morphkv_export_evicted_list(self._h, _dev_ptr(ev), self._stream()))
         return ev
 
     def capture_scores(self, enable=True):

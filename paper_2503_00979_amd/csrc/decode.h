@@ -43,6 +43,8 @@ struct DecodeParams {
   long long *dbgT;         // nullable: [U][8] phase time stamps (diagnostics)
   int32_t Cs, CsP, R, n, n_pad, Mq, Mkv, fusion, cps, cpt;
   int32_t cpt_shift;       // log2(cpt) if cpt is a power of two, else -1
+  int32_t C, T;            // older tokens kept by a selection; selection every T steps (Appendix A.5), Cs = C+T-1
+  int32_t *evl;            // [U][T] positions evicted by the last step, -1 padded
   int32_t zig;             // parity of the step count: direction of the walk over the cache
   float scale_log2;        // softmax scale * log2(e)
 };
@@ -84,11 +86,12 @@ __host__ __device__ inline int turn_cols_padded(int cps) {
 }
 
 // LDS bytes of decode_fused_kernel
-inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps) {
+inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, int CsP, int T) {
   const size_t lg = (size_t)G * (n_pad + 4), om = (size_t)(NT / 64) * G * D;
   const size_t cpt = (size_t)turn_cols_padded(cps);
-  const size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
-                    16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
+  size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
+              16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
+  if (T > 1) fl += (size_t)CsP /*scores*/ + (size_t)(NT / 64) * R /*a column per wave*/ + 4 * (size_t)T /*lists*/;
   return fl * 4;
 }
 
@@ -301,7 +304,12 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   int *bestP = bestC + 16;                // [16]
   int *sh = bestP + 16;                   // [16] 0: K tile counter; 2: dest slot; 3: evicted; 4: new n_snap
   float *shf = (float *)(sh + 16);        // [16] 0: weight of the new row on the token leaving the window;
-                                          //      1..8: logits of the token against its own key
+                                          //      1..8: logits of the token against its own key; 9: its score
+  // selection every T > 1 steps only:
+  const int Tev = P.T;
+  float *Fl = shf + 16;                   // [CsP] fused score per older-token slot
+  float *colw = Fl + (Tev > 1 ? CsP : 0);   // [NW][R] a column of the R rows per wave, oldest first
+  int *lists = (int *)(colw + (Tev > 1 ? NW * R : 0));  // [4][Tev]: evicted slot, hole, mover source, mover dest
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -663,6 +671,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         if (j < n_snap) {
           const float F = fuse2(fusion, so, nwo[i]);
           if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
+          if (Tev > 1) Fl[j] = F;
           if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         }
       }
@@ -723,11 +732,17 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     wave_argmin(f, bp, bc);
     if (lane == 0) {
       colv[R - 1] = shf[0];
-      int dest = -1, evicted = -1, ns = n_snap;
+      int dest = -1, evicted = -1, ns = n_snap, multi = 0;
       if (win_full) {
-        if (n_snap < Cs) {
+        // a selection is due when the step's position is a multiple of T and more than C older tokens
+        // would be held; otherwise the token leaving the window is simply kept
+        const bool due = Tev > 1 ? (p % Tev == 0 && n_snap + 1 > P.C) : n_snap >= Cs;
+        if (!due) {
           dest = n_snap;
           ns = n_snap + 1;
+        } else if (Tev > 1) {
+          multi = 1;  // top-C of up to C+T: done by the whole workgroup after the V pass
+          ns = P.C;
         } else if (fd <= f) {  // tie: the token leaving the window has the higher position, it goes
           evicted = p - R;
         } else {
@@ -739,6 +754,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       sh[2] = dest;
       sh[3] = evicted;
       sh[4] = ns;
+      sh[5] = multi;
+      shf[9] = fd;
     }
   }
 
@@ -866,6 +883,91 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     for (int gg = 0; gg < G; ++gg) psg = gg == g ? pself[gg] : psg;
     o = fmaf(psg, vn, o);
     P.out[((size_t)u * G + g) * D + ch] = o;
+  }
+
+  // ---- selection of the C best of up to C+T older tokens (Eq.7 with the coarse schedule of Appendix A.5):
+  // the n_snap+1-C candidates with the smallest scores go (ties: the higher position goes), survivors
+  // beyond slot C and the token leaving the window move into the freed slots below C.
+  if (Tev > 1) {
+    int32_t *evl = P.evl + (size_t)u * Tev;
+    const int n_ev = sh[5] ? n_snap + 1 - P.C : 0;  // 1..T at a selection step
+    if (tid >= n_ev && tid < Tev) evl[tid] = -1;
+    if (n_ev > 0) {
+      int *ev_slot = lists, *hole = lists + Tev, *msrc = lists + 2 * Tev, *mdst = lists + 3 * Tev;
+      const int wsl = Cs + w;
+      for (int it = 0; it < n_ev; ++it) {
+        float f = INFINITY;
+        int bp = -1, bc = -1;
+        for (int j = tid; j < n_snap; j += NT) {
+          const float F = Fl[j];
+          const int pj = posu[j];
+          if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
+        }
+        wave_argmin(f, bp, bc);
+        if (lane == 0) { bestF[wave] = f; bestP[wave] = bp; bestC[wave] = bc; }
+        lds_barrier();
+        if (wave == 0) {
+          f = INFINITY; bp = -1; bc = -1;
+          if (lane < NW) { f = bestF[lane]; bp = bestP[lane]; bc = bestC[lane]; }
+          wave_argmin(f, bp, bc);
+          if (lane == 0) {
+            const float fd = shf[9];  // +inf once the token leaving the window has been taken
+            if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; shf[9] = INFINITY; }
+            else Fl[bc] = INFINITY;
+            ev_slot[it] = bc;
+            evl[it] = bp;
+            if (it == 0) sh[3] = bp;
+          }
+        }
+        lds_barrier();
+      }
+      if (tid == 0) {
+        // holes: evicted slots below C; movers: survivors at or above C, then the window token.  There
+        // are as many of the one as of the other: n_ev minus the evicted at or above C.
+        int nh = 0, nm = 0;
+        bool w_gone = false;
+        for (int e = 0; e < n_ev; ++e) {
+          const int s = ev_slot[e];
+          if (s < P.C) hole[nh++] = s;
+          w_gone |= s == wsl;
+        }
+        for (int j = P.C; j < n_snap; ++j) {
+          bool gone = false;
+          for (int e = 0; e < n_ev; ++e) gone |= ev_slot[e] == j;
+          if (!gone && nm < nh) { msrc[nm] = j; mdst[nm] = hole[nm]; ++nm; }
+        }
+        if (!w_gone && nm < nh) { msrc[nm] = wsl; mdst[nm] = hole[nm]; ++nm; }
+        sh[6] = nm;
+      }
+      __syncthreads();
+      const int nm = sh[6];
+      T *Kx = (T *)P.K + (size_t)u * n_pad * D;
+      T *Vx = (T *)P.V + (size_t)u * n_pad * D;
+      for (int m = wave; m < nm; m += NW) {
+        const int src = msrc[m], dst = mdst[m];
+        float *cb = colw + (size_t)wave * R;
+        for (int a = lane; a < R; a += WAVE) {
+          int r = w + 1 + a;
+          r -= r >= R ? R : 0;
+          const float x = ringu[(size_t)r * n_pad + src];
+          cb[a] = x;
+          ringu[(size_t)r * n_pad + dst] = x;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+        move_scan_wave(lane, p, last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP, nwu + dst);
+        constexpr int PCSx = D / EPL;
+        if (lane < PCSx) *(uint4 *)(Kx + L::k_off(dst, lane * EPL)) = *(const uint4 *)(Kx + L::k_off(src, lane * EPL));
+        if constexpr (L::tiled) {
+          for (int ch = lane; ch < D; ch += WAVE) ((uint16_t *)Vx)[L::v_off(dst, ch)] = ((const uint16_t *)Vx)[L::v_off(src, ch)];
+        } else {
+          if (lane < PCSx) *(uint4 *)(Vx + L::v_off(dst, lane * EPL)) = *(const uint4 *)(Vx + L::v_off(src, lane * EPL));
+        }
+        if (lane == 0) posu[dst] = src == wsl ? p - R : posu[src];
+      }
+      __syncthreads();  // movers have read their sources before slots are cleared / the window slot is rewritten
+      for (int j = P.C + tid; j < Cs; j += NT) posu[j] = -1;
+    }
   }
 
   // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot

@@ -40,7 +40,7 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 struct BufLayout {
   int U, G, Cs, CsP, n, n_pad, cps, cpt, esz;
   // cache
-  size_t offK, offV, offPos, offMeta, cache_bytes;
+  size_t offK, offV, offPos, offMeta, offEvl, cache_bytes;
   // scores_ring
   size_t offRing, offSfx, offNw, ring_bytes;
   // scratch
@@ -62,7 +62,7 @@ int validate(const morphkv_config *c) {
     return fail(MORPHKV_EINVAL, "fusion must be 0 (sum) or 1 (max)");
   if (c->dtype != MORPHKV_DTYPE_F32 && c->dtype != MORPHKV_DTYPE_BF16)
     return fail(MORPHKV_EINVAL, "dtype must be 0 (f32) or 1 (bf16)");
-  if (c->evict_every != 1) return fail(MORPHKV_EINVAL, "evict_every must be 1");
+  if (c->evict_every < 1 || c->evict_every > 64) return fail(MORPHKV_EINVAL, "evict_every must be in 1..64");
   if (c->max_prompt_len < 1) return fail(MORPHKV_EINVAL, "max_prompt_len must be >= 1");
   if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale))
     return fail(MORPHKV_EINVAL, "softmax_scale must be finite and >= 0");
@@ -90,6 +90,7 @@ BufLayout make_layout(const morphkv_config *c) {
   L.offV = o; o = align_up(o + U * np * d * L.esz);
   L.offPos = o; o = align_up(o + U * np * 4);
   L.offMeta = o; o = align_up(o + U * META * 4);
+  L.offEvl = o; o = align_up(o + U * (size_t)c->evict_every * 4);
   L.cache_bytes = o;
   o = 0;
   L.offRing = o; o = align_up(o + U * R * np * 4);
@@ -135,6 +136,8 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.nw = (float *)(h->ring + L.offNw);
   P.dbgF = h->dbgF;
   P.dbgT = h->dbgT;
+  P.C = h->cfg.C; P.T = h->cfg.evict_every;
+  P.evl = (int32_t *)(h->cache + L.offEvl);
   P.zig = (int32_t)(h->steps & 1u);
   P.cpt_shift = -1;
   for (int sft = 0; sft < 16; ++sft)
@@ -177,7 +180,7 @@ int decode_threads(const morphkv_handle *h) {
 template <typename T, int D, int G>
 int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
   const int NT = decode_threads(h);
-  const size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps);
+  const size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps, P.CsP, P.T);
   if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
   auto kern = decode_fused_kernel<T, D, G>;
   static size_t attr_set = 0;  // per instantiation
@@ -356,6 +359,18 @@ int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream) {
   hipLaunchKernelGGL(export_evicted_kernel, dim3((L.U + 255) / 256), dim3(256), 0, (hipStream_t)stream,
                      (const int32_t *)(h->cache + L.offMeta), evicted, L.U);
   HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!evicted) return fail(MORPHKV_EINVAL, "evicted is null");
+  if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
+  const BufLayout &L = h->L;
+  const int T = h->cfg.evict_every;
+  if (T == 1) return morphkv_export_evicted(h, evicted, stream);
+  HIP_TRY(hipMemcpyAsync(evicted, h->cache + L.offEvl, (size_t)L.U * T * 4, hipMemcpyDeviceToDevice,
+                         (hipStream_t)stream));
   return MORPHKV_OK;
 }
 

@@ -50,7 +50,7 @@ def _gpu_sets(gpu, wl, umap):
     pos, n_snap = gpu.export_positions()
     pos = pos.cpu().numpy()[umap]
     n_snap = n_snap.cpu().numpy()[umap]
-    C = wl.C
+    C = wl.C + wl.evict_every - 1   # older-token slots (more than C are held between coarse selections)
     snaps, wins = [], []
     for i in range(len(umap)):
         s = pos[i, :C]
@@ -129,6 +129,9 @@ class LockStep:
         if self.scoreF is not None:
             pos_before = self.gpu.export_positions()[0].cpu().numpy()[self.umap]
         out = self.gpu.decode_step(q.to(self.device), k.to(self.device), v.to(self.device))
+        T = wl.evict_every
+        if T > 1:
+            return self._finish_step_multi(q, k, v, out, check_sets)
         ev = self.gpu.export_evicted().cpu().numpy()[self.umap]
         ix = torch.tensor(self.bidx, device=q.device)
         qo, ko, vo = (x.index_select(1, ix).cpu().contiguous() for x in (q, k, v))
@@ -164,6 +167,44 @@ class LockStep:
                 assert len(dem) == 1
                 rel = abs(Fg[wl.C] - F[dem[0]]) / max(abs(F[dem[0]]), 1e-30)
                 rep.max_score_rel_err = max(rep.max_score_rel_err, rel)
+        self.oracle.decode_commit(decided)
+        self.t += 1
+        rep.steps += 1
+        if check_sets:
+            self.check_sets()
+
+    def _finish_step_multi(self, q, k, v, out, check_sets):
+        """Coarse schedule (several evictions at once): the evicted SETS must agree; where they differ every
+        element of the symmetric difference must score within 1e-5 relative of the boundary (the largest
+        score the oracle evicts), and the oracle then adopts the GPU's set."""
+        wl, rep, t, T = self.wl, self.rep, self.t, self.wl.evict_every
+        evl = self.gpu.export_evicted_list().cpu().numpy()[self.umap]
+        ix = torch.tensor(self.bidx, device=q.device)
+        qo, ko, vo = (x.index_select(1, ix).cpu().contiguous() for x in (q, k, v))
+        oout = self.oracle.decode_begin(qo, ko, vo)
+        n_cand, cand_pos, cand_F, n_evict, choice = self.oracle.candidates()
+        gout = out.index_select(1, torch.tensor(self.bidx, device=out.device)).cpu().numpy().astype(np.float64)
+        err = float(np.max(np.abs(gout - oout)))
+        rep.max_out_err = max(rep.max_out_err, err)
+        assert err <= self.tol, f"step {t}: attention output off by {err:.3e} (> {self.tol})"
+        decided = np.full((len(self.umap), T), -1, np.int32)
+        for i in range(len(self.umap)):
+            g_set = set(int(x) for x in evl[i] if x >= 0)
+            if n_evict[i] == 0:
+                assert not g_set, f"step {t} unit {i}: GPU evicted {g_set} where nothing may be evicted"
+                continue
+            rep.evictions += int(n_evict[i])
+            o_set = set(int(x) for x in choice[i, :n_evict[i]])
+            assert len(g_set) == n_evict[i], f"step {t} unit {i}: GPU evicted {len(g_set)} tokens, {n_evict[i]} are due"
+            if g_set != o_set:
+                F = {int(cand_pos[i, x]): cand_F[i, x] for x in range(n_cand[i])}
+                bound = max(F[e] for e in o_set)
+                for e in g_set ^ o_set:
+                    assert e in F, f"step {t} unit {i}: {e} is not a candidate"
+                    assert abs(F[e] - bound) <= NEAR_TIE_REL * abs(bound), (
+                        f"step {t} unit {i}: evicted sets differ beyond a near-tie at {e}: F={F[e]!r} boundary={bound!r}")
+                rep.near_ties_decode += len(g_set - o_set)
+            decided[i, :len(g_set)] = sorted(g_set)
         self.oracle.decode_commit(decided)
         self.t += 1
         rep.steps += 1

@@ -57,6 +57,32 @@ def test_small_shapes(case, oracle_lib):
     assert rep.max_score_rel_err <= 1e-5
 
 
+COARSE = [
+    # selection every T steps (Appendix A.5): up to C+T-1 older tokens held in between
+    ("f32_T3", dict(L=1, B=2, M=8, Mkv=2, d=64, dtype="f32", C=40, R=16, fusion="sum", prompt_lens=(100, 70), steps=90, evict_every=3)),
+    ("f32_T8_max", dict(L=2, B=1, M=2, Mkv=2, d=128, dtype="f32", C=33, R=7, fusion="max", prompt_lens=(64,), steps=80, evict_every=8)),
+    ("bf16_T4", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=50, R=9, fusion="sum", prompt_lens=(90, 61), steps=90, evict_every=4)),
+    ("bf16_T8_g7", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(300, 150), steps=80, evict_every=8)),
+    ("bf16_T64", dict(L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=90, R=12, fusion="sum", prompt_lens=(250,), steps=200, evict_every=64)),
+    # cache still filling when the first selection steps come; T > R; C = 1
+    ("short_T5", dict(L=1, B=4, M=4, Mkv=2, d=64, dtype="f32", C=12, R=8, fusion="sum", prompt_lens=(1, 5, 8, 17), steps=70, evict_every=5)),
+    ("T_gt_R", dict(L=1, B=1, M=4, Mkv=2, d=64, dtype="bf16", C=20, R=3, fusion="max", prompt_lens=(40,), steps=60, evict_every=7)),
+    ("c_is_1_T2", dict(L=1, B=1, M=4, Mkv=1, d=64, dtype="bf16", C=1, R=5, fusion="sum", prompt_lens=(30,), steps=40, evict_every=2)),
+]
+
+
+@pytest.mark.parametrize("case", COARSE, ids=[c[0] for c in COARSE])
+def test_coarse_eviction(case, oracle_lib):
+    """Selection every T steps: the SET evicted at each selection step, the retained sets and the attention
+    output (over the C..C+T-1 older tokens held meanwhile) against the oracle, every step."""
+    name, kw = case
+    wl = inputs.small_workload(2000 + COARSE.index(case), **kw)
+    ls = _lockstep(wl, DEV).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report(name, rep)
+    assert rep.evictions > 0
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")
