@@ -31,9 +31,11 @@ def algorithmic_bytes_per_step(wl) -> int:
     the score state (one aggregate row read, the running aggregate read and written);
     q, k_new, v_new in, the new token's K/V written, fp32 output; one K/V row moved and one
     column of the R rows moved on compaction."""
-    n, d, s, G, C, R = wl.C + wl.R, wl.head_dim, wl.elem_bytes, wl.G, wl.C, wl.R
+    d, s, G, R = wl.head_dim, wl.elem_bytes, wl.G, wl.R
+    C = wl.C + (wl.evict_every - 1) / 2.0   # older tokens held, averaged over the T steps between selections
+    n = C + R
     per_unit = (2 * n * d * s) + 4 * n + 12 * (C + 1) + (G + 4) * d * s + 4 * G * d + 4 * d * s + 8 * R
-    return per_unit * wl.n_units
+    return int(per_unit * wl.n_units)
 
 
 def read_traffic(name: str):
@@ -84,6 +86,11 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=5, help="timed repetitions of --steps; the median is reported")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="one launch per layer and step (the order a model's layer chain imposes) instead of one "
+                         "launch over all layers")
+    ap.add_argument("--evict-every", type=int, default=1,
+                    help="T of the coarse schedule (Appendix A.5): selection at every T-th step")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -100,6 +107,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     wl = inputs.workload(args.workload)
+    if args.evict_every != 1:
+        import dataclasses
+        wl = dataclasses.replace(wl, evict_every=args.evict_every)
     K_steps, W = args.steps, args.warmup
 
     # ---- setup (untimed): prompts, prompt-time selection, run until every cache is full
@@ -125,7 +135,7 @@ def main():
         step_no += 1
     torch.cuda.synchronize()
     pos, n_snap = g.export_positions()
-    assert int(n_snap.min()) == wl.C, "not in steady state"
+    assert int(n_snap.min()) >= wl.C, "not in steady state"
 
     # ---- inputs of the timed region, resident in HBM (a pool that is cycled if K is large)
     pool = min(K_steps + W, 512)
@@ -143,7 +153,17 @@ def main():
     vptr = [ctypes.c_void_p(Vp.data_ptr() + i * vb) for i in range(pool)]
     optr = ctypes.c_void_p(out.data_ptr())
 
+    nl = wl.n_layers
+    ob = out[0].numel() * 4
+
     def run(nsteps, start):
+        if args.per_layer:
+            for i in range(nsteps):
+                j = (start + i) % pool
+                for l in range(nl):
+                    g.decode_step_layer_ptrs(l, qptr[j].value + l * (qb // nl), kptr[j].value + l * (kb // nl),
+                                             vptr[j].value + l * (vb // nl), optr.value + l * ob, sp)
+            return
         for i in range(nsteps):
             j = (start + i) % pool
             g.decode_step_ptrs(qptr[j], kptr[j], vptr[j], optr, sp)
@@ -173,6 +193,7 @@ def main():
     sec = max(dev_s, 0.0)                      # HIP events on the launch stream bracket exactly the K kernels
     ms_per_step = sec / K_steps * 1e3
     A = algorithmic_bytes_per_step(wl)
+    launches = K_steps * (nl if args.per_layer else 1)
     achieved = A / (sec / K_steps) / 1e9
     res = {
         "metric": "decode steps/s incl. KV selection (B=32, 8B shape) on 1 GPU; % HBM roofline",
@@ -180,14 +201,16 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: L={wl.n_layers} B={wl.batch} M={wl.n_q_heads} M'={wl.n_kv_heads} "
-                               f"d={wl.head_dim} C={wl.C} R={wl.R} fusion={wl.fusion} {wl.dtype}, steady state",
+                               f"d={wl.head_dim} C={wl.C} R={wl.R} fusion={wl.fusion} {wl.dtype}, steady state"
+                               + (f", selection every {wl.evict_every} steps" if wl.evict_every > 1 else "")
+                               + (f", {nl} launches per step (one per layer)" if args.per_layer else ""),
                    "units": wl.n_units, "fill_steps": fill_steps, "repeats": args.repeats,
                    "wall_ms_per_step": wall_s / K_steps * 1e3, "prefill_select_ms": prefill_ms,
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),
-                     "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A,
-                     "avg_launch_us": sec / K_steps * 1e6},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.per_layer or wl.evict_every > 1) else read_traffic(wl.name),
+                     "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A * K_steps // launches,
+                     "avg_launch_us": sec / launches * 1e6},
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, Qw, K, V, lambda t: dec_inputs(step_no + t))

@@ -90,6 +90,14 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
 int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
                         void *stream /* hipStream_t */);
 
+/* The same step for the units of ONE layer (Section 3.3: every layer's attention keeps its own cache; a
+ * model calls this from inside layer `layer`'s attention, one call per layer per token):
+ *  q      device [B][M][d],  k_new, v_new device [B][M'][d],  out device [B][M][d] fp32
+ * of that layer alone.  Calls for different layers are independent; per layer they must come in token
+ * order.  Whole-model and per-layer calls may be mixed as long as every layer sees every token once. */
+int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                              float *out, void *stream /* hipStream_t */);
+
 /* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
  *  pos    [U][Cs+R] int32, Cs = C+evict_every-1: slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
  *         window slot (position mod R)

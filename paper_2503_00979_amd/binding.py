@@ -20,6 +20,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
+           "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
            "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_last_error")
 
@@ -55,6 +56,7 @@ def load_library():
     L.morphkv_destroy.argtypes = [vp]
     L.morphkv_prefill_select.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.morphkv_decode_step_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp]
     L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
     L.morphkv_export_evicted.argtypes = [vp, vp, vp]
     L.morphkv_export_evicted_list.argtypes = [vp, vp, vp]
@@ -170,6 +172,23 @@ class MorphKV:
         _check(self.lib.morphkv_decode_step(self._h, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out),
                                             self._stream()))
         return out
+
+    def decode_step_layer(self, layer: int, q, k_new, v_new, out):
+        """One layer's units only; the tensors are that layer's [B, M, d] / [B, M', d] / [B, M, d] fp32."""
+        c = self.cfg
+        self._want(q, (c.batch, c.n_q_heads, c.head_dim))
+        self._want(k_new, (c.batch, c.n_kv_heads, c.head_dim))
+        self._want(v_new, (c.batch, c.n_kv_heads, c.head_dim))
+        if tuple(out.shape) != (c.batch, c.n_q_heads, c.head_dim) or out.dtype != torch.float32 or not out.is_contiguous():
+            raise ValueError("out must be a contiguous fp32 [B, M, d] tensor")
+        _check(self.lib.morphkv_decode_step_layer(self._h, int(layer), _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
+                                                  _dev_ptr(out), self._stream()))
+        return out
+
+    def decode_step_layer_ptrs(self, layer: int, q_ptr: int, k_ptr: int, v_ptr: int, out_ptr: int, stream_ptr: int):
+        rc = self.lib.morphkv_decode_step_layer(self._h, layer, q_ptr, k_ptr, v_ptr, out_ptr, stream_ptr)
+        if rc != OK:
+            _check(rc)
 
     def decode_step_ptrs(self, q_ptr: int, k_ptr: int, v_ptr: int, out_ptr: int, stream_ptr: int):
         """Same call with raw device addresses (no shape checks): for tight loops over pre-checked tensors."""

@@ -46,6 +46,8 @@ struct DecodeParams {
   int32_t C, T;            // older tokens kept by a selection; selection every T steps (Appendix A.5), Cs = C+T-1
   int32_t *evl;            // [U][T] positions evicted by the last step, -1 padded
   int32_t zig;             // parity of the step count: direction of the walk over the cache
+  int32_t u0;              // first unit of the launch (a launch may cover one layer's units only);
+                           // q, k_new, v_new and out are addressed by the unit's index within the whole model
   float scale_log2;        // softmax scale * log2(e)
 };
 
@@ -91,7 +93,9 @@ inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, 
   const size_t cpt = (size_t)turn_cols_padded(cps);
   size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
               16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
-  if (T > 1) fl += (size_t)CsP /*scores*/ + (size_t)(NT / 64) * R /*a column per wave*/ + 4 * (size_t)T /*lists*/;
+  if (T > 1)
+    fl += 2 * (size_t)CsP /*scores, positions*/ + (size_t)(NT / 64) * R /*a column per wave*/ + 2 * (size_t)T /*lists*/ +
+          2 * 3 * 16 /*per-wave minima, two sets*/;
   return fl * 4;
 }
 
@@ -151,28 +155,39 @@ __device__ inline void wave_argmin(float &f, int &p, int &c) {
 //   stage[i*cpt + cc] = f(rows of steps p-1-i .. p-1) of column c0+cc   (i = 0..R-2), to be stored to
 //                       sfx row (p-2-i) mod R by the whole workgroup later;
 //   turn[cc]          = f(all R-1 rows): the old part of this step's score for that column.
-// Lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc).  The first
-// batch of row loads is issued by begin() before the workgroup's first barrier, so that it is served
-// ahead of the K stream; finish() consumes it and loops over what is left.
+// The columns are dealt out in groups of gw to the rebuilding waves (group k to wave k mod nrw).  Within
+// a group lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc), which it
+// loads in batches of RB and scans one after the other.  gw is chosen so that a chunk is two batches at
+// most: the chain of dependent loads is what the rest of the workgroup waits for at the end of the K pass.
 constexpr int RB = 16;  // rows per lane and batch
+// columns per group: 64 lanes / gw columns = row chunks, each at most 2*RB rows
+__host__ __device__ inline int turn_group_width(int R) {
+  int gw = WAVE;
+  while (gw > 1 && (R - 1 + WAVE / gw - 1) / (WAVE / gw) > 2 * RB) gw >>= 1;
+  return gw;
+}
 struct TurnRebuild {
-  int lane, p, R, rs, cpt, fusion, c0, ncol, r_top;
+  int lane, p, R, rs, cpt, fusion, c0, ncol, r_top, gw, gstride, g0;
   const float *ringu;
   // current column group
   int cg, CP, lg2, Q, cc, q, c, Lc, i0, i1;
   bool colok;
 
+  // k-th of nrw rebuilding waves
   __device__ inline void init(int lane_, int p_, int wm1, int n_snap, int R_, int rs_, int cps, int cpt_,
-                              int fusion_, const float *ringu_) {
+                              int fusion_, const float *ringu_, int k, int nrw) {
     lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_;
     r_top = wm1;  // (p-1) mod R: ring row of row i = 0
     c0 = wm1 * cps;
     ncol = n_snap - c0;
     ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
+    gw = turn_group_width(R);
+    g0 = k * gw;
+    gstride = nrw * gw;
   }
   __device__ inline void group(int cg_) {
     cg = cg_;
-    const int nc = ncol - cg < WAVE ? ncol - cg : WAVE;
+    const int nc = ncol - cg < gw ? ncol - cg : gw;
     CP = 1; lg2 = 0;
     while (CP < nc) { CP <<= 1; ++lg2; }
     Q = WAVE >> lg2;
@@ -200,10 +215,10 @@ struct TurnRebuild {
 
   }
   __device__ inline void begin(float (&v)[RB]) {
-    if (ncol > 0) { group(0); load(0, v); }
+    if (ncol > g0) { group(g0); load(0, v); }
   }
   __device__ inline void finish(float (&v)[RB], float *stage, float *turn) {
-    if (ncol <= 0) return;
+    if (ncol <= g0) return;
     int b = 0;
     float acc = 0.f;
     while (true) {
@@ -231,8 +246,8 @@ struct TurnRebuild {
           for (int i = i0; i < i1; ++i) st[i * cpt] = fuse2(fusion, st[i * cpt], carry);
         }
         if (q == 0) turn[cg + cc] = total;
-        if (cg + WAVE >= ncol) break;
-        group(cg + WAVE);
+        if (cg + gstride >= ncol) break;
+        group(cg + gstride);
         b = 0;
         acc = 0.f;
       }
@@ -284,7 +299,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   constexpr int KBUF = 1, VBUF = 1;
   extern __shared__ __align__(16) float smem[];
 
-  const int u = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
+  const int u = blockIdx.x + P.u0, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
   const int wave = tid / WAVE, lane = tid % WAVE;
   const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps, cpt = P.cpt;
 
@@ -308,8 +323,10 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   // selection every T > 1 steps only:
   const int Tev = P.T;
   float *Fl = shf + 16;                   // [CsP] fused score per older-token slot
-  float *colw = Fl + (Tev > 1 ? CsP : 0);   // [NW][R] a column of the R rows per wave, oldest first
-  int *lists = (int *)(colw + (Tev > 1 ? NW * R : 0));  // [4][Tev]: evicted slot, hole, mover source, mover dest
+  int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP] its position
+  float *colw = (float *)(Pl + (Tev > 1 ? CsP : 0));      // [NW][R] a column of the R rows per wave, oldest first
+  int *lists = (int *)(colw + (Tev > 1 ? NW * R : 0));    // [2][Tev]: freed slot below C, slot that moves there
+  float *best2 = (float *)(lists + 2 * Tev);              // [2][3][16] per-wave minima of the selection rounds
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -397,11 +414,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       if (a < R - 1 && win_full) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
     }
   }
-  // ---- the last wave rebuilds the columns whose turn it is: its first loads go out ahead of the K stream
+  // ---- the last waves rebuild the columns whose turn it is (one wave per group of columns, at most half
+  // of the waves)
   TurnRebuild tr;
   float rbv[RB];
-  if (wave == NW - 1) {
-    tr.init(lane, p, wm1, n_snap, R, n_pad, cps, cpt, fusion, ringu);
+  const int tgw = turn_group_width(R);
+  int nrw = (cps + tgw - 1) / tgw;
+  nrw = nrw > NW / 2 ? NW / 2 : nrw;
+  if (wave >= NW - nrw) {
+    tr.init(lane, p, wm1, n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
   }
 
   // ---- self logit (every lane ends up with all G values)
@@ -466,8 +487,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   lds_barrier();  // the tile counter is initialised
   if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
 
-  // ---- the last wave first rebuilds the columns whose turn it is, then joins the K pass
-  if (wave == NW - 1) {
+  // ---- the last waves first rebuild the columns whose turn it is, then join the K pass
+  if (wave >= NW - nrw) {
     tr.begin(rbv);
     tr.finish(rbv, stage, turn);
   }
@@ -671,7 +692,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         if (j < n_snap) {
           const float F = fuse2(fusion, so, nwo[i]);
           if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-          if (Tev > 1) Fl[j] = F;
+          if (Tev > 1) { Fl[j] = F; Pl[j] = pj[i]; }
           if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         }
       }
@@ -893,58 +914,54 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     const int n_ev = sh[5] ? n_snap + 1 - P.C : 0;  // 1..T at a selection step
     if (tid >= n_ev && tid < Tev) evl[tid] = -1;
     if (n_ev > 0) {
-      int *ev_slot = lists, *hole = lists + Tev, *msrc = lists + 2 * Tev, *mdst = lists + 3 * Tev;
+      int *hole = lists, *msrc = lists + Tev;
       const int wsl = Cs + w;
+      // n_ev rounds, each taking out the candidate that goes first.  Every wave works the round's result out
+      // for itself from the per-wave minima (two sets, used in turn: one barrier per round); slot j is read
+      // and, once taken, struck out by thread j mod NT only.
+      float fd = shf[9];  // score of the token leaving the window; +inf once it has been taken
+      int nh = 0;         // slots below C freed so far
       for (int it = 0; it < n_ev; ++it) {
         float f = INFINITY;
         int bp = -1, bc = -1;
         for (int j = tid; j < n_snap; j += NT) {
           const float F = Fl[j];
-          const int pj = posu[j];
+          const int pj = Pl[j];
           if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
         }
         wave_argmin(f, bp, bc);
-        if (lane == 0) { bestF[wave] = f; bestP[wave] = bp; bestC[wave] = bc; }
+        float *bF = best2 + (it & 1) * 48;
+        int *bPp = (int *)bF + 16, *bCc = (int *)bF + 32;
+        if (lane == 0) { bF[wave] = f; bPp[wave] = bp; bCc[wave] = bc; }
         lds_barrier();
-        if (wave == 0) {
-          f = INFINITY; bp = -1; bc = -1;
-          if (lane < NW) { f = bestF[lane]; bp = bestP[lane]; bc = bestC[lane]; }
-          wave_argmin(f, bp, bc);
-          if (lane == 0) {
-            const float fd = shf[9];  // +inf once the token leaving the window has been taken
-            if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; shf[9] = INFINITY; }
-            else Fl[bc] = INFINITY;
-            ev_slot[it] = bc;
-            evl[it] = bp;
-            if (it == 0) sh[3] = bp;
-          }
+        f = INFINITY; bp = -1; bc = -1;
+        if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
+        wave_argmin(f, bp, bc);
+        if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; fd = INFINITY; }
+        else if (bc % NT == tid) Fl[bc] = INFINITY;
+        if (tid == 0) {
+          evl[it] = bp;
+          if (it == 0) sh[3] = bp;
+          if (bc < P.C) hole[nh] = bc;
         }
-        lds_barrier();
+        nh += bc < P.C;
       }
-      if (tid == 0) {
-        // holes: evicted slots below C; movers: survivors at or above C, then the window token.  There
-        // are as many of the one as of the other: n_ev minus the evicted at or above C.
-        int nh = 0, nm = 0;
-        bool w_gone = false;
-        for (int e = 0; e < n_ev; ++e) {
-          const int s = ev_slot[e];
-          if (s < P.C) hole[nh++] = s;
-          w_gone |= s == wsl;
-        }
-        for (int j = P.C; j < n_snap; ++j) {
-          bool gone = false;
-          for (int e = 0; e < n_ev; ++e) gone |= ev_slot[e] == j;
-          if (!gone && nm < nh) { msrc[nm] = j; mdst[nm] = hole[nm]; ++nm; }
-        }
-        if (!w_gone && nm < nh) { msrc[nm] = wsl; mdst[nm] = hole[nm]; ++nm; }
-        sh[6] = nm;
+      lds_barrier();  // the last round's strike-out is visible
+      // movers = survivors at or above C, then the token leaving the window: as many as slots freed below C,
+      // at most T, listed by one wave
+      if (wave == 0) {
+        const int j = P.C + lane;  // n_snap - C <= T - 1 <= 63 candidates above C, then the window token
+        const bool mover = j < n_snap ? Fl[j] != INFINITY : (j == n_snap && fd != INFINITY);
+        const unsigned long long m = __ballot(mover);
+        if (mover) msrc[__popcll(m & ((1ull << lane) - 1ull))] = j < n_snap ? j : wsl;
+        if (lane == 0) sh[6] = nh;
       }
       __syncthreads();
       const int nm = sh[6];
       T *Kx = (T *)P.K + (size_t)u * n_pad * D;
       T *Vx = (T *)P.V + (size_t)u * n_pad * D;
       for (int m = wave; m < nm; m += NW) {
-        const int src = msrc[m], dst = mdst[m];
+        const int src = msrc[m], dst = hole[m];
         float *cb = colw + (size_t)wave * R;
         for (int a = lane; a < R; a += WAVE) {
           int r = w + 1 + a;
@@ -963,7 +980,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         } else {
           if (lane < PCSx) *(uint4 *)(Vx + L::v_off(dst, lane * EPL)) = *(const uint4 *)(Vx + L::v_off(src, lane * EPL));
         }
-        if (lane == 0) posu[dst] = src == wsl ? p - R : posu[src];
+        if (lane == 0) posu[dst] = src == wsl ? p - R : Pl[src];
       }
       __syncthreads();  // movers have read their sources before slots are cleared / the window slot is rewritten
       for (int j = P.C + tid; j < Cs; j += NT) posu[j] = -1;

@@ -4,7 +4,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
+#include <vector>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -80,7 +82,21 @@ BufLayout make_layout(const morphkv_config *c) {
   L.n = L.Cs + c->R;
   L.n_pad = (L.n + 31) / 32 * 32;  // K/V slot arrays are padded to whole tiles
   L.CsP = (L.Cs + 31) / 32 * 32;   // row stride of the per-column state
-  L.cps = (L.Cs + c->R - 1) / c->R;
+  // Columns rebuilt per step: at least ceil(Cs/R), so that every column's turn comes once in R steps.  The
+  // rebuilt aggregates go out as one run of cps floats per sfx row: runs that are whole 128-byte lines (else
+  // 64, 32 .. bytes) keep partial-line writes away from HBM, which cost several us per step on c3-sized
+  // caches when the run was 17 floats.  Rounded up as far as the LDS staging area (R x cps floats) allows.
+  const int cps0 = (L.Cs + c->R - 1) / c->R;
+  L.cps = cps0;
+  for (int a = 32; a > 1; a >>= 1) {
+    const int cand = (cps0 + a - 1) / a * a;
+    const size_t stage = (size_t)c->R * turn_cols_padded(cand) * 4;
+    if (stage <= 32 * 1024 &&
+        decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, cand, (L.Cs + 31) / 32 * 32, c->evict_every) <= 160 * 1024) {
+      L.cps = cand;
+      break;
+    }
+  }
   L.cpt = turn_cols_padded(L.cps);
   L.esz = c->dtype == MORPHKV_DTYPE_F32 ? 4 : 2;
   const size_t U = (size_t)L.U, np = (size_t)L.n_pad, d = (size_t)c->head_dim, R = (size_t)c->R,
@@ -116,10 +132,12 @@ struct morphkv_handle {
   float *dbgF;
   long long *dbgT;
   bool prefilled;
-  unsigned steps;  // decode steps since the last prefill
+  unsigned steps;  // whole-model decode steps since the last prefill
+  std::vector<unsigned> layer_steps;  // decode steps of each layer taken by per-layer calls
   float scale_log2;
   int n_cu;
   int force_threads;  // MORPHKV_DECODE_THREADS (256/512/1024): tuning override, 0 = choose
+  size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
 };
 
 namespace {
@@ -169,26 +187,27 @@ PrefillParams prefill_params(const morphkv_handle *h) {
 
 // threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
 // over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
-int decode_threads(const morphkv_handle *h) {
+int decode_threads(const morphkv_handle *h, int U) {
   if (h->force_threads) return h->force_threads;
-  const int U = h->L.U, cu = h->n_cu > 0 ? h->n_cu : 256;
+  const int cu = h->n_cu > 0 ? h->n_cu : 256;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
   return 1024;
 }
 
 template <typename T, int D, int G>
-int launch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
-  const int NT = decode_threads(h);
-  const size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps, P.CsP, P.T);
+int launch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
+  const int NT = decode_threads(h, n_units);
+  size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps, P.CsP, P.T);
   if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
+  if (h->min_lds > lds && h->min_lds <= 160 * 1024) lds = h->min_lds;
   auto kern = decode_fused_kernel<T, D, G>;
   static size_t attr_set = 0;  // per instantiation
   if (lds > attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = lds;
   }
-  hipLaunchKernelGGL(kern, dim3(h->L.U), dim3(NT), lds, st, P);
+  hipLaunchKernelGGL(kern, dim3(n_units), dim3(NT), lds, st, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }
@@ -241,8 +260,8 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
     }                                                                         \
   } while (0)
 
-int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, hipStream_t st) {
-  MKV_DISPATCH(launch_decode, h, h, P, st);
+int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
+  MKV_DISPATCH(launch_decode, h, h, P, n_units, st);
 }
 int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
   MKV_DISPATCH(launch_prefill, h, h, P, st);
@@ -283,10 +302,18 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   h->dbgT = nullptr;
   h->prefilled = false;
   h->steps = 0;
+  try {
+    h->layer_steps.assign((size_t)cfg->n_layers, 0u);
+  } catch (...) {
+    delete h;
+    return fail(MORPHKV_EINVAL, "out of host memory");
+  }
   const double scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / std::sqrt((double)cfg->head_dim);
   h->scale_log2 = (float)(scale * 1.4426950408889634074);
   h->n_cu = 0;
   h->force_threads = 0;
+  h->min_lds = 0;
+  if (const char *e = std::getenv("MORPHKV_DECODE_MIN_LDS")) h->min_lds = (size_t)std::atol(e);
   if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
     const int v = std::atoi(e);
     if (v == 256 || v == 512 || v == 1024) h->force_threads = v;
@@ -324,6 +351,7 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
   if (rc) return rc;
   h->prefilled = true;
   h->steps = 0;
+  std::fill(h->layer_steps.begin(), h->layer_steps.end(), 0u);
   return MORPHKV_OK;
 }
 
@@ -334,8 +362,31 @@ int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, con
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step before prefill_select");
   DecodeParams P = decode_params(h);
   P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
-  const int rc = dispatch_decode(h, P, (hipStream_t)stream);
+  const int rc = dispatch_decode(h, P, h->L.U, (hipStream_t)stream);
   if (rc == MORPHKV_OK) ++h->steps;
+  return rc;
+}
+
+int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                              float *out, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!q || !k_new || !v_new || !out) return fail(MORPHKV_EINVAL, "null pointer");
+  if (layer < 0 || layer >= h->cfg.n_layers)
+    return fail(MORPHKV_EINVAL, "layer %d outside 0..%d", layer, h->cfg.n_layers - 1);
+  if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step_layer before prefill_select");
+  const int upl = h->cfg.batch * h->cfg.n_kv_heads;  // units per layer
+  DecodeParams P = decode_params(h);
+  P.u0 = layer * upl;
+  P.zig = (int32_t)(h->layer_steps[layer] & 1u);
+  // the kernel addresses the step's tensors by the unit's index in the whole model: shift the layer's
+  // own tensors back by the units that come before it
+  const size_t d = (size_t)h->cfg.head_dim, esz = (size_t)h->L.esz, G = (size_t)h->L.G, u0 = (size_t)P.u0;
+  P.q = (const void *)((uintptr_t)q - u0 * G * d * esz);
+  P.k_new = (const void *)((uintptr_t)k_new - u0 * d * esz);
+  P.v_new = (const void *)((uintptr_t)v_new - u0 * d * esz);
+  P.out = (float *)((uintptr_t)out - u0 * G * d * sizeof(float));
+  const int rc = dispatch_decode(h, P, upl, (hipStream_t)stream);
+  if (rc == MORPHKV_OK) ++h->layer_steps[layer];
   return rc;
 }
 

@@ -66,7 +66,7 @@ def _gpu_sets(gpu, wl, umap):
 
 class LockStep:
     def __init__(self, wl, device="cuda:0", batch_index: Optional[List[int]] = None, gen_device=None,
-                 capture_scores=False):
+                 capture_scores=False, per_layer=False):
         self.wl = wl
         self.device = device
         self.bidx = list(range(wl.batch)) if batch_index is None else list(batch_index)
@@ -79,6 +79,7 @@ class LockStep:
         self.tol = OUT_TOL[wl.dtype]
         self.scoreF = self.gpu.capture_scores(True) if capture_scores else None
         self.t = 0
+        self.per_layer = per_layer   # one call per layer (reverse order, to show the calls are independent)
 
     # ---- prefill --------------------------------------------------------
     def prefill(self):
@@ -128,7 +129,13 @@ class LockStep:
         pos_before = None
         if self.scoreF is not None:
             pos_before = self.gpu.export_positions()[0].cpu().numpy()[self.umap]
-        out = self.gpu.decode_step(q.to(self.device), k.to(self.device), v.to(self.device))
+        qd, kd, vd = q.to(self.device), k.to(self.device), v.to(self.device)
+        if self.per_layer:
+            out = torch.full(self.gpu.out_shape, float("nan"), dtype=torch.float32, device=self.device)
+            for l in reversed(range(wl.n_layers)):
+                self.gpu.decode_step_layer(l, qd[l], kd[l], vd[l], out[l])
+        else:
+            out = self.gpu.decode_step(qd, kd, vd)
         T = wl.evict_every
         if T > 1:
             return self._finish_step_multi(q, k, v, out, check_sets)

@@ -83,6 +83,17 @@ def test_coarse_eviction(case, oracle_lib):
     assert rep.evictions > 0
 
 
+@pytest.mark.parametrize("T", [1, 4])
+def test_per_layer_calls(T, oracle_lib):
+    """One call per layer, as a model's attention layers make them, gives what the whole-model call gives."""
+    wl = inputs.small_workload(3000 + T, L=3, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=40, R=8, fusion="sum",
+                               prompt_lens=(90, 30), steps=60, evict_every=T)
+    ls = _lockstep(wl, DEV, per_layer=True).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"per_layer_T{T}", rep)
+    assert rep.evictions > 0
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")
