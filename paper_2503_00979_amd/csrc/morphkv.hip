@@ -46,7 +46,7 @@ struct BufLayout {
   // scores_ring
   size_t offRing, offSfx, offNw, ring_bytes;
   // scratch
-  size_t offSrow, offF, offSel, offPlen, scratch_bytes;
+  size_t offSrow, offStat, offF, offSel, offPlen, scratch_bytes;
 };
 
 int validate(const morphkv_config *c) {
@@ -115,7 +115,11 @@ BufLayout make_layout(const morphkv_config *c) {
   L.ring_bytes = o;
   o = 0;
   const size_t Nm = (size_t)c->max_prompt_len;
-  L.offSrow = o; o = align_up(o + U * R * Nm * 4);
+  // prompt-time scratch: fp32 keeps whole rows of weights; bf16 only softmax statistics per block of keys
+  const size_t R16 = (R + 15) / 16 * 16, nblk = (Nm + PF_BLOCK - 1) / PF_BLOCK;
+  L.offSrow = o;
+  o = align_up(o + (c->dtype == MORPHKV_DTYPE_F32 ? U * R * Nm * 4 : U * nblk * (size_t)L.G * R16 * 8));
+  L.offStat = o; o = align_up(o + U * (size_t)L.G * R16 * 8);
   L.offF = o; o = align_up(o + U * Nm * 4);
   L.offSel = o; o = align_up(o + U * (size_t)L.Cs * 4);
   L.offPlen = o; o = align_up(o + (size_t)c->batch * 4);
@@ -170,6 +174,8 @@ PrefillParams prefill_params(const morphkv_handle *h) {
   const BufLayout &L = h->L;
   P.plen = (const int32_t *)(h->scratch + L.offPlen);
   P.Srow = (float *)(h->scratch + L.offSrow);
+  P.Spart = (float2 *)(h->scratch + L.offSrow);
+  P.Sfin = (float2 *)(h->scratch + L.offStat);
   P.F = (float *)(h->scratch + L.offF);
   P.sel = (int32_t *)(h->scratch + L.offSel);
   P.Kc = h->cache + L.offK;
@@ -215,19 +221,31 @@ int launch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, h
 template <typename T, int D, int G>
 int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
   const int U = h->L.U;
-  if constexpr (Layout<T, D>::tiled)
-    hipLaunchKernelGGL((prefill_rows_mfma_kernel<D, G>), dim3((P.R + 15) / 16, U), dim3(256), 0, st, P);
-  else
+  constexpr bool mfma = Layout<T, D>::tiled;
+  const int nblk = (P.Nmax + PF_BLOCK - 1) / PF_BLOCK;
+  if constexpr (mfma) {
+    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_STATS>), dim3(nblk, U), dim3(256), 0, st, P);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL((prefill_stats_merge_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P, nblk);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_FUSE>), dim3(nblk, U), dim3(256), 0, st, P);
+    HIP_TRY(hipGetLastError());
+  } else {
     hipLaunchKernelGGL((prefill_rows_kernel<T, D, G>), dim3(P.R, U), dim3(256), 0, st, P);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(prefill_fuse_kernel, dim3((P.Nmax + 255) / 256, U), dim3(256), 0, st, P);
-  HIP_TRY(hipGetLastError());
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(prefill_fuse_kernel, dim3((P.Nmax + 255) / 256, U), dim3(256), 0, st, P);
+    HIP_TRY(hipGetLastError());
+  }
   hipLaunchKernelGGL(prefill_select_kernel, dim3(U), dim3(1024), 0, st, P);
   HIP_TRY(hipGetLastError());
   constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
   hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n_pad + 255) / 256, U), dim3(256), 0, st, P);
+  if constexpr (mfma)
+    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_RING>), dim3((P.n_pad + PF_BLOCK - 1) / PF_BLOCK, U), dim3(256),
+                       0, st, P);
+  else
+    hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n_pad + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(prefill_state_kernel, dim3((P.CsP + 255) / 256, U), dim3(256), 0, st, P);
   HIP_TRY(hipGetLastError());

@@ -11,6 +11,7 @@ struct PrefillParams {
   const void *Qw, *K, *V;  // [L][B][M][R][D], [L][B][M'][Nmax][D] x2
   const int32_t *plen;     // device [B]
   float *Srow;             // scratch [U][R][Nmax]: group-summed weights of window query j on key k
+  float2 *Spart, *Sfin;    // scratch (bf16 passes): [U][nblk][G][R16] per-block and [U][G][R16] final softmax statistics
   float *F;                // scratch [U][Nmax]: fused score per older token
   int32_t *sel;            // scratch [U][Cs]: retained positions, ascending
   // state written
@@ -240,6 +241,363 @@ __global__ __launch_bounds__(256) void prefill_rows_mfma_kernel(PrefillParams P)
       if (k <= pj) Sr[k] = S[i];
     }
   }
+}
+
+// ---- bf16, key-major passes ---------------------------------------------------------------------------
+// The prompt-time selection needs the R window rows twice: once for their softmax statistics and once
+// for the weights themselves.  Both passes walk the prompt in blocks of keys: a workgroup keeps 256 keys
+// as MFMA A-operand fragments in registers (4 waves x 4 tiles of 16 keys) and streams every (query tile,
+// head) of its unit past them, B fragments straight from the row-major window queries (they stay in L2).
+// K is read from HBM once per pass and no row of weights is ever written out:
+//   PF_STATS  per-block (max, sum of exp2) of every (head, query)      -> Spart, merged by prefill_stats_merge
+//   PF_FUSE   weights -> sum over the group's heads -> fused over the R queries (Eq.4-6) -> F[key]
+//   PF_RING   the same weights for the slots of the cache after the gather, stored as the recorded rows
+// MFMA 16x16x32: D[key][query]; a lane owns one query (column) and 4 consecutive keys of each tile.
+enum { PF_STATS = 0, PF_FUSE = 1, PF_RING = 2 };
+constexpr int PF_KT = 4;                  // key tiles a wave holds                  // key tiles a wave holds                  // key tiles a wave holds                  // key tiles a wave holds
+constexpr int PF_BLOCK = 4 * PF_KT * 16;  // keys (slots) per workgroup
+
+template <int D, int G, int MODE>
+__global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
+  constexpr int KB = D / 32, KT = PF_KT;
+  constexpr int JC = 32 / G;  // query tiles whose statistics are collected in LDS before they are flushed
+  constexpr bool ST = MODE == PF_STATS;
+  // the window queries of one query tile (16 queries x G heads), in B-fragment order, two buffers: the next
+  // tile is fetched by the whole workgroup while the current one is worked on
+  // rows of 16 pieces (one 8-channel group of the 16 queries) are 17 apart: the writes of a staging thread
+  // row (one query, consecutive channel groups) then fall into different banks, as the reads do anyway
+  constexpr int QROW = 17;
+  __shared__ uint4 qs[2][G * KB * 4 * QROW];
+  __shared__ float2 sts[2][ST ? 1 : G * 16];           // (max, 1/sum) of (head, query) for the weights
+  __shared__ float2 wst[ST ? 4 : 1][ST ? G : 1][ST ? JC * 16 : 1];
+  const int blk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x;
+  const int wave = tid / WAVE, lane = tid % WAVE, col = lane & 15, kq = lane >> 4;
+  const int b = (u / P.Mkv) % P.B;
+  const int N = P.plen[b], R = P.R, Rw = N < R ? N : R, n_old = N - Rw, R16 = (R + 15) & ~15;
+  const int nkeys = MODE == PF_STATS ? N : MODE == PF_FUSE ? n_old : P.n_pad;
+  if (blk * PF_BLOCK >= nkeys) return;
+  const int kbase = blk * PF_BLOCK + wave * (KT * 16);
+  const int njt = (Rw + 15) >> 4;
+  const float scale = P.scale_log2;
+  // keys below the window are seen by every window query: only a wave that reaches into the window masks
+  [[maybe_unused]] const bool need_mask = kbase + KT * 16 > n_old;
+
+  // ---- this wave's keys: A fragments (and, for cache slots, the positions behind them)
+  uint4 ka[KT][KB];
+  [[maybe_unused]] int4 kp[KT];
+  if constexpr (MODE == PF_RING) {
+    const bf16_t *Kc = (const bf16_t *)P.Kc + (size_t)u * P.n_pad * D;
+    const int32_t *posu = P.pos + (size_t)u * P.n_pad;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      int tile = (kbase >> 4) + t;
+      const bool tok = tile * 16 < P.n_pad;
+      tile = tok ? tile : 0;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) ka[t][kb] = *(const uint4 *)(Kc + ((size_t)tile * KB + kb) * 512 + lane * 8);
+      kp[t] = tok ? *(const int4 *)(posu + tile * 16 + 4 * kq) : make_int4(-1, -1, -1, -1);
+    }
+  } else {
+    const bf16_t *Kb = (const bf16_t *)P.K + (size_t)u * P.Nmax * D;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const int key = min(kbase + t * 16 + col, N - 1);  // rows past the prompt are masked or never stored
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) ka[t][kb] = *(const uint4 *)(Kb + (size_t)key * D + kb * 32 + kq * 8);
+    }
+  }
+  // rows of the recorded-row array that no window query maps to (prompt shorter than R) are zero
+  if constexpr (MODE == PF_RING) {
+    if (N < R) {
+      const int s0 = blk * PF_BLOCK + lane * 4;
+      if (s0 < P.n_pad)
+        for (int r = N + wave; r < R; r += 4)
+          *(float4 *)(P.ring + ((size_t)u * R + r) * P.n_pad + s0) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+
+  // ---- staging of a query tile: thread -> (query jq, 8 channels c8) of every head; a row of 16 threads
+  // reads one 256-byte query row, and the piece lands where lane (kq, jq) of k-block kb will look for it
+  const bf16_t *Qu = (const bf16_t *)P.Qw + (size_t)u * G * R * D;
+  const float2 *stu = P.Sfin + (size_t)u * G * R16;
+  constexpr int C8 = D / 8;                      // 16-byte pieces per query row
+  constexpr int QPT = (16 * C8 + 255) / 256;     // query rows a thread fetches per head (1 for d <= 128)
+  uint4 sq[G][QPT];
+  [[maybe_unused]] float2 sst = make_float2(0.f, 0.f);
+  // head g of query tile jt: global -> registers, and later registers -> LDS buffer.  The two halves are
+  // called a few steps apart so that only a few heads are in registers at a time.
+  auto fetch = [&](int jt, int g) {
+#pragma unroll
+    for (int qi = 0; qi < QPT; ++qi) {
+      const int e = tid + qi * 256, jq = e / C8, c8 = e % C8, j = jt * 16 + jq;
+      sq[g][qi] = make_uint4(0u, 0u, 0u, 0u);
+      if (jq < 16 && j < Rw) sq[g][qi] = *(const uint4 *)(Qu + ((size_t)g * R + j) * D + c8 * 8);
+    }
+  };
+  auto stash = [&](int buf, int g) {
+#pragma unroll
+    for (int qi = 0; qi < QPT; ++qi) {
+      const int e = tid + qi * 256, jq = e / C8, c8 = e % C8;
+      if (jq < 16) qs[buf][(g * C8 + c8) * QROW + jq] = sq[g][qi];
+    }
+  };
+  auto fetch_stats = [&](int jt) {
+    if constexpr (!ST) {
+      if (tid < G * 16) {
+        const int g = tid >> 4, j = jt * 16 + (tid & 15);
+        sst = j < Rw ? stu[g * R16 + j] : make_float2(0.f, 0.f);
+      }
+    }
+  };
+  auto stash_stats = [&](int buf) {
+    if constexpr (!ST) {
+      if (tid < G * 16) sts[buf][tid] = sst;
+    }
+  };
+
+  [[maybe_unused]] float S[KT][4], Facc[KT][4];
+#pragma unroll
+  for (int t = 0; t < KT; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { S[t][i] = 0.f; Facc[t][i] = 0.f; }
+
+  // One step = (query tile jt, head g) against this wave's keys: 16 matrix instructions, then the arithmetic
+  // on their 16 results per lane.  The two are software-pipelined: the matrix instructions of the next step
+  // are issued before the arithmetic of the current one, so the matrix pipe works under it.
+  auto ldq = [&](int buf, int g, uint4 (&q)[KB]) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) q[kb] = qs[buf][((g * KB + kb) * 4 + kq) * QROW + col];
+  };
+  // k-block outermost: consecutive matrix instructions belong to different key tiles and do not wait for
+  // one another's result
+  auto mfma16 = [&](const uint4 (&q)[KB], f32x4_t (&acc)[KT]) {
+#pragma unroll
+    for (int t = 0; t < KT; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t][kb]),
+                                                         __builtin_bit_cast(bf16x8_t, q[kb]), acc[t], 0, 0, 0);
+  };
+  // asks the instruction scheduler to lay the region before it out as: one matrix instruction, then three
+  // vector instructions (the fma / exp2 / fma of one result), and so on
+  auto interleave = [&]() {
+    if constexpr (!ST) {
+      // the running sums are pinned here, so that the arithmetic above is not sunk past the next step's
+      // matrix instructions
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(S[t][i]));
+    }
+#pragma unroll
+    for (int i = 0; i < KT * KB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+    }
+  };
+  // st = (max, 1/sum) of (head g, query j) for the weights; (0, 0): no such query
+  auto valu = [&](int jt, int g, float2 st, f32x4_t (&acc)[KT]) {
+    const int j = jt * 16 + col;
+    const int pj = j < Rw ? N - Rw + j : -1;  // causal: query j sees keys 0..pj
+    if constexpr (ST) {
+      // maximum on the raw products (the scale is positive), then one fma and one exp2 per logit
+      float m = -INFINITY;
+      if (need_mask) {
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int k = kbase + t * 16 + 4 * kq + i;
+            acc[t][i] = k <= pj ? acc[t][i] : -INFINITY;
+          }
+      }
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m = fmaxf(m, acc[t][i]);
+      m *= scale;
+      const float mr = m == -INFINITY ? 0.f : m;
+      float z = 0.f;
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z += __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -mr));
+#pragma unroll
+      for (int sft = 16; sft < WAVE; sft <<= 1) {
+        const float om = __shfl_xor(m, sft), oz = __shfl_xor(z, sft);
+        const float mn = fmaxf(m, om), mnr = mn == -INFINITY ? 0.f : mn;
+        z = z * __builtin_amdgcn_exp2f(m - mnr) + oz * __builtin_amdgcn_exp2f(om - mnr);
+        m = mn;
+      }
+      if (kq == 0) wst[wave][g][(jt % JC) * 16 + col] = make_float2(m, z);
+    } else {
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        [[maybe_unused]] const int kpp[4] = {kp[t].x, kp[t].y, kp[t].z, kp[t].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float e = __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -st.x)) * st.y;
+          if constexpr (MODE == PF_RING) e = (kpp[i] >= 0 && kpp[i] <= pj) ? e : 0.f;
+          S[t][i] += e;
+        }
+      }
+      if (g == G - 1) {
+        if constexpr (MODE == PF_FUSE) {
+#pragma unroll
+          for (int t = 0; t < KT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { Facc[t][i] = fuse2(P.fusion, Facc[t][i], S[t][i]); S[t][i] = 0.f; }
+        } else {
+          const int r = pj >= 0 ? pj % R : 0;
+          float *row = P.ring + ((size_t)u * R + r) * P.n_pad;
+#pragma unroll
+          for (int t = 0; t < KT; ++t) {
+            const int s0 = kbase + t * 16 + 4 * kq;
+            if (pj >= 0 && s0 < P.n_pad) *(float4 *)(row + s0) = make_float4(S[t][0], S[t][1], S[t][2], S[t][3]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[t][i] = 0.f;
+          }
+        }
+      }
+    }
+  };
+  // statistics of query tiles [jt0, jt_end) (one chunk of JC at most): the 4 waves' shares merged, out to
+  // the block's partials.  The caller's barrier has made the waves' shares visible.
+  [[maybe_unused]] auto flush = [&](int jt_end) {
+    const int jt0 = (jt_end - 1) / JC * JC, nj = (jt_end - jt0) * 16;
+    float2 *part = P.Spart + ((size_t)u * gridDim.x + blk) * G * R16;
+    for (int idx = tid; idx < G * nj; idx += 256) {
+      const int g = idx / nj, jj = idx - g * nj;
+      float m = -INFINITY, z = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) {
+        const float2 o = wst[wv][g][jj];
+        const float mn = fmaxf(m, o.x), mnr = mn == -INFINITY ? 0.f : mn;
+        z = z * __builtin_amdgcn_exp2f(m - mnr) + o.y * __builtin_amdgcn_exp2f(o.x - mnr);
+        m = mn;
+      }
+      part[g * R16 + jt0 * 16 + jj] = make_float2(m, z);
+    }
+  };
+
+#pragma unroll
+  for (int g = 0; g < G; ++g) fetch(0, g);
+  fetch_stats(0);
+#pragma unroll
+  for (int g = 0; g < G; ++g) stash(0, g);
+  stash_stats(0);
+  __syncthreads();
+  // accumulators and query fragments of the step in flight and the one after it, used in turn
+  f32x4_t aA[KT], aB[KT];
+  uint4 qA[KB], qB[KB];
+  ldq(0, 0, qA);
+  mfma16(qA, aA);
+  for (int jt = 0; jt < njt; ++jt) {
+    const int buf = jt & 1;
+    const bool more = jt + 1 < njt;
+    // staging of the next tile: fetched now, written to its LDS buffer (not read since the last barrier) at
+    // the end of this tile
+    if (more) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) fetch(jt + 1, g);
+      fetch_stats(jt + 1);
+    }
+    if constexpr (G > 1) ldq(buf, 1, qB);
+    // heads 0 .. G-2, two per trip: results of head g are in aA for even g, in aB for odd g
+    constexpr int NP = (G - 1) / 2;
+#pragma unroll 1
+    for (int gp = 0; gp < NP; ++gp) {
+      const int g = 2 * gp;
+      {
+        const float2 st = ST ? make_float2(0.f, 0.f) : sts[buf][g * 16 + col];
+        mfma16(qB, aB);
+        ldq(buf, g + 2, qA);  // g + 2 <= G - 1
+        valu(jt, g, st, aA);
+        interleave();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const float2 st = ST ? make_float2(0.f, 0.f) : sts[buf][(g + 1) * 16 + col];
+        mfma16(qA, aA);
+        ldq(buf, g + 3 < G ? g + 3 : G - 1, qB);  // unconditional: the step stays one block of straight code
+        valu(jt, g + 1, st, aB);
+        interleave();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (((G - 1) & 1) != 0) {  // one more head before the last: G - 2 (even), results in aA
+      const float2 st = ST ? make_float2(0.f, 0.f) : sts[buf][(G - 2) * 16 + col];
+      mfma16(qB, aB);
+      valu(jt, G - 2, st, aA);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // last head: the next tile is staged first, so that its first step can be issued under this arithmetic
+    const float2 st_last = ST ? make_float2(0.f, 0.f) : sts[buf][(G - 1) * 16 + col];
+    if (more) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) stash(buf ^ 1, g);
+      stash_stats(buf ^ 1);
+    }
+    __syncthreads();  // next tile in place; every read of this one has been issued
+    constexpr bool lastB = ((G - 1) & 1) != 0;  // where the results of head G-1 are
+    if constexpr (lastB) {
+      if (more) { ldq(buf ^ 1, 0, qA); mfma16(qA, aA); }
+      valu(jt, G - 1, st_last, aB);
+    } else {
+      if (more) { ldq(buf ^ 1, 0, qB); mfma16(qB, aB); }
+      valu(jt, G - 1, st_last, aA);
+      if (more) {
+#pragma unroll
+        for (int t = 0; t < KT; ++t) aA[t] = aB[t];
+      }
+    }
+    if constexpr (ST) {
+      if ((jt + 1) % JC == 0 || !more) {
+        __syncthreads();  // this chunk's shares are complete
+        flush(jt + 1);
+        __syncthreads();  // before the next chunk overwrites them
+      }
+    }
+  }
+
+  if constexpr (MODE == PF_FUSE) {
+    // fuse over the 16 queries of a tile column: lanes of one row of 16 hold the same keys
+    float *Fu = P.F + (size_t)u * P.Nmax;
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float f = Facc[t][i];
+#pragma unroll
+        for (int sft = 1; sft < 16; sft <<= 1) f = fuse2(P.fusion, f, __shfl_xor(f, sft));
+        const int k = kbase + t * 16 + 4 * kq + i;
+        if (col == 0 && k < n_old) Fu[k] = f;
+      }
+  }
+}
+
+// merges the per-block statistics of a unit: Sfin[g][j] = (max, 1 / sum of exp2(logit - max)) over the
+// whole causal row of query j, (0, 0) for queries that do not exist
+template <int G>
+__global__ __launch_bounds__(64) void prefill_stats_merge_kernel(PrefillParams P, int nblk) {
+  const int u = blockIdx.x, g = blockIdx.y, j = blockIdx.z * 64 + threadIdx.x;
+  const int b = (u / P.Mkv) % P.B;
+  const int N = P.plen[b], R = P.R, Rw = N < R ? N : R, R16 = (R + 15) & ~15;
+  if (j >= R16) return;
+  const int nb = (N + PF_BLOCK - 1) / PF_BLOCK, idx = g * R16 + j;
+  float m = -INFINITY, z = 0.f;
+  if (j < Rw) {
+    for (int bk = 0; bk < nb; ++bk) {
+      const float2 o = P.Spart[((size_t)u * nblk + bk) * G * R16 + idx];
+      const float mn = fmaxf(m, o.x), mnr = mn == -INFINITY ? 0.f : mn;
+      z = z * exp2f(m - mnr) + o.y * exp2f(o.x - mnr);
+      m = mn;
+    }
+  }
+  P.Sfin[(size_t)u * G * R16 + idx] = z > 0.f ? make_float2(m, 1.0f / z) : make_float2(0.f, 0.f);
 }
 
 // ---- P2: fused score of every older token (Eq.5 / Eq.6 over the window rows)
