@@ -134,115 +134,6 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
   }
 }
 
-// ---- P1 (bf16): the same rows on the matrix core.  One workgroup per (tile of 16 window queries, unit);
-// its 4 waves split the prompt keys.  MFMA 16x16x32: A = 16 keys x 32 channels straight from the row-major
-// prompt K, B = 32 channels x 16 queries of one head (fragments stay in registers), D[key][query]: a lane
-// owns one query (its softmax statistics are per-lane scalars) and 4 consecutive keys.
-template <int D, int G>
-__global__ __launch_bounds__(256) void prefill_rows_mfma_kernel(PrefillParams P) {
-  constexpr int KB = D / 32;
-  __shared__ float sm[4][G][16], sz[4][G][16];
-  const int jt = blockIdx.x, u = blockIdx.y, tid = threadIdx.x;
-  const int wave = tid / WAVE, lane = tid % WAVE, col = lane & 15, kq = lane >> 4;
-  const int b = (u / P.Mkv) % P.B;
-  const int N = P.plen[b], R = P.R, Rw = N < R ? N : R;
-  if (jt * 16 >= Rw) return;
-  const int j = jt * 16 + col;
-  const bool jok = j < Rw;
-  const int pj = jok ? N - Rw + j : -1;                  // causal: keys 0..pj
-  const int jlast = min(jt * 16 + 15, Rw - 1);
-  const int nkmax = N - Rw + jlast + 1;                  // keys any query of the tile looks at
-  const bf16_t *Kb = (const bf16_t *)P.K + (size_t)u * P.Nmax * D;
-
-  bf16x8_t qfr[G][KB];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-      uint4 r = {0u, 0u, 0u, 0u};
-      if (jok) r = *(const uint4 *)((const bf16_t *)P.Qw + (((size_t)u * G + g) * R + j) * D + kb * 32 + kq * 8);
-      qfr[g][kb] = __builtin_bit_cast(bf16x8_t, r);
-    }
-  auto load_keys = [&](int t, uint4 (&a)[KB]) {
-    const int key = min(t * 16 + col, N - 1);  // clamped rows are masked by the causal test
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) a[kb] = *(const uint4 *)(Kb + (size_t)key * D + kb * 32 + kq * 8);
-  };
-  auto logits4 = [&](const uint4 (&a)[KB], int g) {
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kb]), qfr[g][kb], acc, 0, 0, 0);
-    return acc;  // acc[i]: key t*16 + 4*kq + i, query col
-  };
-
-  // pass A: running (max, sum of exp2) per head for this lane's query over this lane's keys
-  float m[G], z[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) { m[g] = -INFINITY; z[g] = 0.f; }
-  for (int t = wave; t * 16 < nkmax; t += 4) {
-    uint4 a[KB];
-    load_keys(t, a);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const f32x4_t acc = logits4(a, g);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int k = t * 16 + 4 * kq + i;
-        if (k <= pj) {
-          const float l = acc[i] * P.scale_log2;
-          const float mn = fmaxf(m[g], l);
-          z[g] = z[g] * exp2f(m[g] - mn) + exp2f(l - mn);
-          m[g] = mn;
-        }
-      }
-    }
-  }
-  // merge the 4 key groups of the wave, then the waves
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int s = 16; s < WAVE; s <<= 1) {
-      const float om = __shfl_xor(m[g], s), oz = __shfl_xor(z[g], s);
-      const float mn = fmaxf(m[g], om);
-      const float x = m[g] == -INFINITY ? 0.f : z[g] * exp2f(m[g] - mn);
-      const float y = om == -INFINITY ? 0.f : oz * exp2f(om - mn);
-      z[g] = x + y;
-      m[g] = mn;
-    }
-    if (kq == 0) { sm[wave][g][col] = m[g]; sz[wave][g][col] = z[g]; }
-  }
-  __syncthreads();
-  float Mx[G], inv[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float mm = -INFINITY;
-    for (int x = 0; x < 4; ++x) mm = fmaxf(mm, sm[x][g][col]);
-    float zz = 0.f;
-    for (int x = 0; x < 4; ++x) zz += sm[x][g][col] == -INFINITY ? 0.f : sz[x][g][col] * exp2f(sm[x][g][col] - mm);
-    Mx[g] = mm;
-    inv[g] = 1.0f / zz;
-  }
-  // pass B: weights, summed over the group's heads
-  float *Sr = P.Srow + ((size_t)u * R + (jok ? j : 0)) * P.Nmax;
-  for (int t = wave; t * 16 < nkmax; t += 4) {
-    uint4 a[KB];
-    load_keys(t, a);
-    float S[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const f32x4_t acc = logits4(a, g);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) S[i] += exp2f(acc[i] * P.scale_log2 - Mx[g]) * inv[g];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int k = t * 16 + 4 * kq + i;
-      if (k <= pj) Sr[k] = S[i];
-    }
-  }
-}
-
 // ---- bf16, key-major passes ---------------------------------------------------------------------------
 // The prompt-time selection needs the R window rows twice: once for their softmax statistics and once
 // for the weights themselves.  Both passes walk the prompt in blocks of keys: a workgroup keeps 256 keys
@@ -417,6 +308,10 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
       for (int t = 0; t < KT; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) m = fmaxf(m, acc[t][i]);
+      // one reference for the wave's 64 keys of this query (the 4 lanes that share the column), so that their
+      // sums add up without rescaling
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
       m *= scale;
       const float mr = m == -INFINITY ? 0.f : m;
       float z = 0.f;
@@ -424,13 +319,8 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
       for (int t = 0; t < KT; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) z += __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -mr));
-#pragma unroll
-      for (int sft = 16; sft < WAVE; sft <<= 1) {
-        const float om = __shfl_xor(m, sft), oz = __shfl_xor(z, sft);
-        const float mn = fmaxf(m, om), mnr = mn == -INFINITY ? 0.f : mn;
-        z = z * __builtin_amdgcn_exp2f(m - mnr) + oz * __builtin_amdgcn_exp2f(om - mnr);
-        m = mn;
-      }
+      z += __shfl_xor(z, 16);
+      z += __shfl_xor(z, 32);
       if (kq == 0) wst[wave][g][(jt % JC) * 16 + col] = make_float2(m, z);
     } else {
 #pragma unroll
