@@ -2,6 +2,7 @@
 
   python -m paper_2503_00979_amd.rocprof_summary trace  <results.db> <n_last>   # --kernel-trace runs
   python -m paper_2503_00979_amd.rocprof_summary pmc    <results.db> <n_last>   # --pmc runs
+  python -m paper_2503_00979_amd.rocprof_summary kernels <results.db> <n_last>  # every kernel of the library
 
 Only the library's kernels are looked at; <n_last> = how many of the last decode dispatches form the
 steady-state sample (the timed region of bench.py).
@@ -45,5 +46,20 @@ def pmc(db, nlast):
               f"max={max(vals):.1f} mean_dur_us={st.mean(durs):.2f}")
 
 
+def kernels(db, nlast):
+    """Every kernel of the library: calls, and duration over the last <n_last> calls of each (the first
+    call of a process pays code loading and cold caches)."""
+    c = sqlite3.connect(db)
+    d = defaultdict(list)
+    for name, start, dur in c.execute("select name, start, duration from kernels where name like '%mkv::%' order by start"):
+        d[name.split('(')[0][-70:]].append(dur / 1e3)
+    tot = 0.0
+    for name, v in sorted(d.items(), key=lambda kv: -st.mean(kv[1][-nlast:])):
+        w = v[-nlast:]
+        tot += st.mean(w)
+        print(f"{name:70s} calls={len(v):5d} last{len(w)}: mean_us={st.mean(w):9.1f} min_us={min(w):9.1f}")
+    print(f"sum of the means: {tot:.1f} us")
+
+
 if __name__ == "__main__":
-    {"trace": trace, "pmc": pmc}[sys.argv[1]](sys.argv[2], int(sys.argv[3]))
+    {"trace": trace, "pmc": pmc, "kernels": kernels}[sys.argv[1]](sys.argv[2], int(sys.argv[3]))
