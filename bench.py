@@ -89,6 +89,10 @@ def main():
     ap.add_argument("--per-layer", action="store_true",
                     help="one launch per layer and step (the order a model's layer chain imposes) instead of one "
                          "launch over all layers")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --per-layer: the launches of two consecutive steps are captured in a HIP graph once "
+                         "and replayed (inputs copied into static buffers before each replay), as serving stacks "
+                         "run their decode loops; takes the host out of the measurement")
     ap.add_argument("--evict-every", type=int, default=1,
                     help="T of the coarse schedule (Appendix A.5): selection at every T-th step")
     ap.add_argument("--prefill-repeats", type=int, default=3,
@@ -162,7 +166,33 @@ def main():
     nl = wl.n_layers
     ob = out[0].numel() * 4
 
+    graph = None
+    if args.graph:
+        assert args.per_layer and K_steps % 2 == 0 and W % 2 == 0 and pool % 2 == 0, "--graph: --per-layer, even step counts"
+        sQ, sK, sV = torch.empty_like(Qp[:2]), torch.empty_like(Kp[:2]), torch.empty_like(Vp[:2])
+        cs = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        spc = ctypes.c_void_p(cs.cuda_stream)
+        for i in range(2):  # two eager steps first: kernel attributes are set outside the capture
+            for l in range(nl):
+                g.decode_step_layer_ptrs(l, qptr[i].value + l * (qb // nl), kptr[i].value + l * (kb // nl),
+                                         vptr[i].value + l * (vb // nl), optr.value + l * ob, sp)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(cs):
+            with torch.cuda.graph(graph, stream=cs):
+                for i in range(2):
+                    for l in range(nl):
+                        g.decode_step_layer_ptrs(l, sQ[i].data_ptr() + l * (qb // nl), sK[i].data_ptr() + l * (kb // nl),
+                                                 sV[i].data_ptr() + l * (vb // nl), optr.value + l * ob, spc)
+        torch.cuda.synchronize()
+
     def run(nsteps, start):
+        if graph is not None:
+            for i in range(0, nsteps, 2):
+                j = (start + i) % pool
+                sQ.copy_(Qp[j:j + 2]); sK.copy_(Kp[j:j + 2]); sV.copy_(Vp[j:j + 2])
+                graph.replay()
+            return
         if args.per_layer:
             for i in range(nsteps):
                 j = (start + i) % pool
@@ -209,7 +239,8 @@ def main():
         "config": {"workload": f"{wl.name}: L={wl.n_layers} B={wl.batch} M={wl.n_q_heads} M'={wl.n_kv_heads} "
                                f"d={wl.head_dim} C={wl.C} R={wl.R} fusion={wl.fusion} {wl.dtype}, steady state"
                                + (f", selection every {wl.evict_every} steps" if wl.evict_every > 1 else "")
-                               + (f", {nl} launches per step (one per layer)" if args.per_layer else ""),
+                               + (f", {nl} launches per step (one per layer)" if args.per_layer else "")
+                               + (", two steps per HIP graph replay" if args.graph else ""),
                    "units": wl.n_units, "fill_steps": fill_steps, "repeats": args.repeats,
                    "wall_ms_per_step": wall_s / K_steps * 1e3, "prefill_select_ms": prefill_ms,
                    "prefill_select_first_call_ms": pf[0],

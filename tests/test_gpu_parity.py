@@ -142,6 +142,101 @@ def test_c5_sampled_units_full_size(oracle_lib):
     _report("c5", rep)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_full_attention_when_nothing_is_evicted(dtype):
+    """A layer that keeps everything (C + R covers the whole sequence; layer-aware retention of Appendix A.6):
+    the step's output is plain dense attention of the new token over every token so far and itself (Eq.1),
+    computed here with torch in fp64 -- a check of the GPU path that does not go through the oracle."""
+    from paper_2503_00979_amd import binding
+    N, steps, R = 37, 50, 8
+    wl = inputs.small_workload(5150, L=2, B=2, M=6, Mkv=2, d=64, dtype=dtype, C=N + steps, R=R, fusion="max",
+                               prompt_lens=(N, 19), steps=steps)
+    g = binding.MorphKV.from_workload(wl, DEV)
+    Qw, K, V = wl.prompt()
+    g.prefill_select(Qw.to(DEV), K.to(DEV), V.to(DEV), wl.prompt_len_tensor().numpy())
+    G = wl.n_q_heads // wl.n_kv_heads
+    # history per (layer, sequence): [M', n, d] fp64
+    Kh = [[K[l, b, :, :wl.prompt_lens[b]].double() for b in range(wl.batch)] for l in range(wl.n_layers)]
+    Vh = [[V[l, b, :, :wl.prompt_lens[b]].double() for b in range(wl.batch)] for l in range(wl.n_layers)]
+    tol = 2e-3 if dtype == "bf16" else 1e-5
+    worst = 0.0
+    for t in range(steps):
+        q, k, v = wl.decode_inputs(t)
+        out = g.decode_step(q.to(DEV), k.to(DEV), v.to(DEV)).cpu().double()
+        for l in range(wl.n_layers):
+            for b in range(wl.batch):
+                Kh[l][b] = torch.cat([Kh[l][b], k[l, b].double()[:, None, :]], 1)
+                Vh[l][b] = torch.cat([Vh[l][b], v[l, b].double()[:, None, :]], 1)
+                qq = q[l, b].double().view(wl.n_kv_heads, G, wl.head_dim)
+                logits = torch.einsum("hgd,hnd->hgn", qq, Kh[l][b]) / wl.head_dim ** 0.5
+                ref = torch.einsum("hgn,hnd->hgd", torch.softmax(logits, -1), Vh[l][b]).reshape(wl.n_q_heads, wl.head_dim)
+                worst = max(worst, float((out[l, b] - ref).abs().max()))
+    print(f"[full_attention_{dtype}] max abs error {worst:.3e}", flush=True)
+    assert worst <= tol
+    _, n_snap = g.export_positions()
+    assert int(n_snap.min()) == min(wl.prompt_lens) + steps - R  # nothing was ever evicted
+
+
+def test_graph_replay_matches_eager():
+    """The per-layer calls of two decode steps captured in a HIP graph (no allocation, no memset, launches on the
+    capture stream only) and replayed several times, with eager work and synchronisations in between, give
+    bit for bit what the same calls give eagerly."""
+    from paper_2503_00979_amd import binding
+    wl = inputs.small_workload(6161, L=3, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=48, R=8, fusion="sum",
+                               prompt_lens=(120, 33), steps=24)
+    Qw, K, V = (t.to(DEV) for t in wl.prompt())
+    ins = [tuple(x.to(DEV) for x in wl.decode_inputs(t)) for t in range(wl.steps)]
+
+    def fresh():
+        g = binding.MorphKV.from_workload(wl, DEV)
+        g.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())
+        return g
+
+    def layer_calls(g, q, k, v, out):
+        for l in range(wl.n_layers):
+            g.decode_step_layer(l, q[l], k[l], v[l], out[l])
+
+    # eager
+    g = fresh()
+    eager = []
+    for t in range(wl.steps):
+        out = torch.empty(g.out_shape, dtype=torch.float32, device=DEV)
+        layer_calls(g, *ins[t], out)
+        eager.append(out)
+    pos_e, ns_e = g.export_positions()
+    # graph: two steps per replay (the walk direction alternates with the step parity), static input buffers
+    g = fresh()
+    sq = [torch.empty_like(ins[0][0]) for _ in range(2)]
+    sk = [torch.empty_like(ins[0][1]) for _ in range(2)]
+    sv = [torch.empty_like(ins[0][2]) for _ in range(2)]
+    so = [torch.empty(g.out_shape, dtype=torch.float32, device=DEV) for _ in range(2)]
+    for i in range(2):   # the first two steps run eagerly (they also set the kernels' attributes)
+        layer_calls(g, *ins[i], so[i])
+        assert torch.equal(so[i], eager[i])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    for i in range(2):
+        sq[i].copy_(ins[2 + i][0]); sk[i].copy_(ins[2 + i][1]); sv[i].copy_(ins[2 + i][2])
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(2):
+                layer_calls(g, sq[i], sk[i], sv[i], so[i])
+    # capture enqueues nothing: steps 2,3 happen on the first replay
+    for t in range(2, wl.steps, 2):
+        for i in range(2):
+            sq[i].copy_(ins[t + i][0]); sk[i].copy_(ins[t + i][1]); sv[i].copy_(ins[t + i][2])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(so[i], eager[t + i]), f"replayed step {t + i} differs from the eager run"
+        _ = (so[0] * 2).sum().item()   # eager work between replays
+    pos_g, ns_g = g.export_positions()
+    assert torch.equal(pos_g, pos_e) and torch.equal(ns_g, ns_e)
+
+
 def test_rerun_is_bit_identical(oracle_lib):
     """The in-place compaction is the only write-after-read hazard: two runs must agree bit for bit."""
     from paper_2503_00979_amd import binding
