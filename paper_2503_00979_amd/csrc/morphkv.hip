@@ -140,7 +140,7 @@ struct morphkv_handle {
   std::vector<unsigned> layer_steps;  // decode steps of each layer taken by per-layer calls
   float scale_log2;
   int n_cu;
-  int force_threads;  // MORPHKV_DECODE_THREADS (256/512/1024): tuning override, 0 = choose
+  int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 256..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
 };
 
@@ -334,7 +334,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   if (const char *e = std::getenv("MORPHKV_DECODE_MIN_LDS")) h->min_lds = (size_t)std::atol(e);
   if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
     const int v = std::atoi(e);
-    if (v == 256 || v == 512 || v == 1024) h->force_threads = v;
+    if (v >= 256 && v <= 1024 && v % 64 == 0) h->force_threads = v;
   }
   int dev = 0;
   hipDeviceProp_t prop;
@@ -342,6 +342,17 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
     h->n_cu = prop.multiProcessorCount;
   else
     (void)hipGetLastError();
+  // the decode kernel keeps one weight per (head, slot) in LDS: say so now if C + R is too large for that
+  const int upl = cfg->batch * cfg->n_kv_heads;
+  for (int units : {h->L.U, upl}) {
+    const size_t lds = decode_lds_bytes(h->L.n_pad, h->L.G, cfg->head_dim, decode_threads(h, units), cfg->R, h->L.cps,
+                                        h->L.CsP, cfg->evict_every);
+    if (lds > 160 * 1024) {
+      const int n = h->L.n;
+      delete h;
+      return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS in the decode kernel (limit 163840)", n, lds);
+    }
+  }
   *out = h;
   return MORPHKV_OK;
 }

@@ -151,7 +151,7 @@ constexpr int PF_BLOCK = 4 * PF_KT * 16;  // keys (slots) per workgroup
 template <int D, int G, int MODE>
 __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
   constexpr int KB = D / 32, KT = PF_KT;
-  constexpr int JC = 32 / G;  // query tiles whose statistics are collected in LDS before they are flushed
+  constexpr int JC = 16 / G;  // query tiles whose statistics are collected in LDS before they are flushed
   constexpr bool ST = MODE == PF_STATS;
   // the window queries of one query tile (16 queries x G heads), in B-fragment order, two buffers: the next
   // tile is fetched by the whole workgroup while the current one is worked on

@@ -94,6 +94,27 @@ def test_per_layer_calls(T, oracle_lib):
     assert rep.evictions > 0
 
 
+LARGE = [
+    # shapes at the edges of what the kernels are built for, a few dozen steps each, every unit followed
+    ("mha_g1", dict(L=1, B=2, M=8, Mkv=8, d=128, dtype="bf16", C=1024, R=64, fusion="sum", prompt_lens=(2000, 1500), steps=40)),
+    ("r_1024", dict(L=1, B=1, M=4, Mkv=2, d=128, dtype="bf16", C=512, R=1024, fusion="max", prompt_lens=(3000,), steps=40)),
+    ("c_7680_lds", dict(L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=7680, R=128, fusion="sum", prompt_lens=(9000,), steps=24)),
+    ("g8_d64", dict(L=1, B=2, M=16, Mkv=2, d=64, dtype="bf16", C=3000, R=100, fusion="max", prompt_lens=(5000, 3050), steps=32)),
+    ("f32_large", dict(L=1, B=1, M=4, Mkv=2, d=128, dtype="f32", C=1500, R=96, fusion="sum", prompt_lens=(2500,), steps=32)),
+    ("coarse_large", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=2048, R=128, fusion="sum", prompt_lens=(3000, 2500), steps=40, evict_every=8)),
+]
+
+
+@pytest.mark.parametrize("case", LARGE, ids=[c[0] for c in LARGE])
+def test_large_shapes(case, oracle_lib):
+    name, kw = case
+    wl = inputs.small_workload(7000 + LARGE.index(case), **kw)
+    ls = _lockstep(wl, DEV, gen_device=DEV).prefill()
+    rep = ls.run(wl.steps, check_every=8)
+    _report(name, rep)
+    assert rep.evictions > 0
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")
@@ -272,4 +293,12 @@ def test_error_paths(oracle_lib):
     Qw, K, V = (t.to(DEV) for t in wl.prompt())
     with pytest.raises(binding.MorphKVError) as e:
         g.prefill_select(Qw, K, V, [9])
+    assert e.value.code == binding.EINVAL
+    # a cache too large for the LDS-resident weights is refused when the handle is made, with the reason
+    big = inputs.small_workload(8, L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=12000, R=128, prompt_lens=(100,), steps=1)
+    with pytest.raises(binding.MorphKVError) as e:
+        binding.MorphKV.from_workload(big, DEV)
+    assert e.value.code == binding.EINVAL and "LDS" in str(e.value)
+    with pytest.raises(binding.MorphKVError) as e:
+        g.decode_step_layer(1, q[0], k[0], v[0], torch.empty(g.out_shape[1:], dtype=torch.float32, device=DEV))
     assert e.value.code == binding.EINVAL
