@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--prefill-repeats", type=int, default=3,
                     help="prefill_select is run this many times on the same prompts (it rewrites all state); the "
                          "median is reported as prefill_select_ms")
+    ap.add_argument("--prefill-lse", action="store_true",
+                    help="also time prefill_select_lse (window rows' log-sum-exp supplied by the caller)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -132,6 +134,33 @@ def main():
         torch.cuda.synchronize()
         pf.append(e0.elapsed_time(e1))
     prefill_ms = sorted(pf)[len(pf) // 2]
+    prefill_lse_ms = None
+    if args.prefill_lse:
+        # what the caller's own attention pass over the prompt would hand over: log-sum-exp of the window rows
+        # (computed here with torch, untimed), then the variant that skips the statistics pass
+        G, R = wl.G, wl.R
+        lse = torch.zeros(wl.n_layers, wl.batch, wl.n_q_heads, R, dtype=torch.float32, device=dev)
+        for l in range(wl.n_layers):
+            for b in range(wl.batch):
+                N = wl.prompt_lens[b]
+                Rw = min(R, N)
+                lg = torch.einsum("mjd,mnd->mjn", Qw[l, b, :, :Rw].float(),
+                                  K[l, b, :, :N].float().repeat_interleave(G, dim=0)) / wl.head_dim ** 0.5
+                pj = torch.arange(N - Rw, N, device=dev)[:, None]
+                lg.masked_fill_(torch.arange(N, device=dev)[None, :] > pj, float("-inf"))
+                lse[l, b, :, :Rw] = torch.logsumexp(lg, -1)
+                del lg
+        pfl = []
+        for _ in range(max(1, args.prefill_repeats)):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy(), lse_window=lse)
+            e1.record()
+            torch.cuda.synchronize()
+            pfl.append(e0.elapsed_time(e1))
+        prefill_lse_ms = sorted(pfl)[len(pfl) // 2]
+        del lse
     fill_steps = max(0, max(wl.C + wl.R - n for n in wl.prompt_lens))
     step_no = 0
     out = torch.empty(g.out_shape, dtype=torch.float32, device=dev)
@@ -244,6 +273,7 @@ def main():
                    "units": wl.n_units, "fill_steps": fill_steps, "repeats": args.repeats,
                    "wall_ms_per_step": wall_s / K_steps * 1e3, "prefill_select_ms": prefill_ms,
                    "prefill_select_first_call_ms": pf[0],
+                   **({"prefill_select_lse_ms": prefill_lse_ms} if prefill_lse_ms is not None else {}),
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.per_layer or wl.evict_every > 1) else read_traffic(wl.name),

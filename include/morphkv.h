@@ -81,6 +81,17 @@ int morphkv_destroy(morphkv_handle *h);
 int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                            const int32_t *prompt_len, int32_t Nmax, void *stream /* hipStream_t */);
 
+/* The same when the prompt's own attention pass has already been run by the caller (Section 8 names fusing the
+ * selection into that pass as future work): attention kernels return, per query row, the natural logarithm of the
+ * sum of exp over its causal logits.
+ *  lse_window device [L][B][M][R] fp32: that value for the window queries (row j as in Q_window, rows >= min(R,N_b)
+ *             ignored), or NULL for the behaviour of morphkv_prefill_select.
+ * The pass over the prompt that finds the rows' softmax statistics is then skipped; weights are
+ * exp(logit - lse).  Everything else as morphkv_prefill_select. */
+int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                               const float *lse_window, const int32_t *prompt_len, int32_t Nmax,
+                               void *stream /* hipStream_t */);
+
 /* One decode step for all units (Eq.1, Algorithm 1, Eq.7).
  *  q      device [L][B][M][d]    query of the new token
  *  k_new  device [L][B][M'][d]   its key   (enters the window after the step)

@@ -19,7 +19,7 @@ FUSION = {"sum": 0, "max": 1}
 DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
-EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_decode_step",
+EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_prefill_select_lse", "morphkv_decode_step",
            "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
            "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_last_error")
@@ -55,6 +55,7 @@ def load_library():
     L.morphkv_create.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, vp, vp]
     L.morphkv_destroy.argtypes = [vp]
     L.morphkv_prefill_select.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
+    L.morphkv_prefill_select_lse.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.morphkv_decode_step_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp]
     L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
@@ -152,13 +153,20 @@ class MorphKV:
         if t.dtype != self.dtype or tuple(t.shape) != tuple(shape):
             raise ValueError(f"expected {self.dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
 
-    def prefill_select(self, Q_window, K, V, prompt_len):
+    def prefill_select(self, Q_window, K, V, prompt_len, lse_window=None):
+        """lse_window: optional fp32 [L, B, M, R] log-sum-exp of the window rows from the caller's attention pass."""
         c = self.cfg
         Nmax = K.shape[3]
         self._want(Q_window, (c.n_layers, c.batch, c.n_q_heads, c.R, c.head_dim))
         self._want(K, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
         self._want(V, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
         pl = (C.c_int32 * c.batch)(*[int(x) for x in prompt_len])
+        if lse_window is not None:
+            if lse_window.dtype != torch.float32 or tuple(lse_window.shape) != (c.n_layers, c.batch, c.n_q_heads, c.R):
+                raise ValueError("lse_window must be fp32 [L, B, M, R]")
+            _check(self.lib.morphkv_prefill_select_lse(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V),
+                                                       _dev_ptr(lse_window), pl, Nmax, self._stream()))
+            return
         _check(self.lib.morphkv_prefill_select(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V), pl, Nmax,
                                                self._stream()))
 

@@ -224,10 +224,15 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
   constexpr bool mfma = Layout<T, D>::tiled;
   const int nblk = (P.Nmax + PF_BLOCK - 1) / PF_BLOCK;
   if constexpr (mfma) {
-    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_STATS>), dim3(nblk, U), dim3(256), 0, st, P);
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL((prefill_stats_merge_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P, nblk);
-    HIP_TRY(hipGetLastError());
+    if (P.lse) {
+      hipLaunchKernelGGL((prefill_stats_from_lse_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P);
+      HIP_TRY(hipGetLastError());
+    } else {
+      hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_STATS>), dim3(nblk, U), dim3(256), 0, st, P);
+      HIP_TRY(hipGetLastError());
+      hipLaunchKernelGGL((prefill_stats_merge_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P, nblk);
+      HIP_TRY(hipGetLastError());
+    }
     hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_FUSE>), dim3(nblk, U), dim3(256), 0, st, P);
     HIP_TRY(hipGetLastError());
   } else {
@@ -365,6 +370,11 @@ int morphkv_destroy(morphkv_handle *h) {
 
 int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                            const int32_t *prompt_len, int32_t Nmax, void *stream) {
+  return morphkv_prefill_select_lse(h, Q_window, K, V, nullptr, prompt_len, Nmax, stream);
+}
+
+int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                               const float *lse_window, const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!Q_window || !K || !V || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
   if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
@@ -374,7 +384,7 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
       return fail(MORPHKV_EINVAL, "prompt_len[%d] = %d outside 1..Nmax (%d)", b, prompt_len[b], Nmax);
   hipStream_t st = (hipStream_t)stream;
   PrefillParams P = prefill_params(h);
-  P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax;
+  P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax; P.lse = lse_window;
   HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
   int rc = dispatch_prefill(h, P, st);
   if (rc) return rc;

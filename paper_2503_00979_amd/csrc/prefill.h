@@ -11,6 +11,7 @@ struct PrefillParams {
   const void *Qw, *K, *V;  // [L][B][M][R][D], [L][B][M'][Nmax][D] x2
   const int32_t *plen;     // device [B]
   float *Srow;             // scratch [U][R][Nmax]: group-summed weights of window query j on key k
+  const float *lse;        // nullable, [L][B][M][R]: natural-log sum of exp of the window rows' causal logits, from the caller
   float2 *Spart, *Sfin;    // scratch (bf16 passes): [U][nblk][G][R16] per-block and [U][G][R16] final softmax statistics
   float *F;                // scratch [U][Nmax]: fused score per older token
   int32_t *sel;            // scratch [U][Cs]: retained positions, ascending
@@ -71,11 +72,11 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
     }
   };
 
-  // pass A: running (max, sum of exp2) per head
+  // pass A: running (max, sum of exp2) per head -- skipped when the caller brought the rows' log-sum-exp
   float m[G], z[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) { m[g] = -INFINITY; z[g] = 0.f; }
-  for (int tile = wave; tile * RPT < nk; tile += NW) {
+  for (int tile = wave; !P.lse && tile * RPT < nk; tile += NW) {
     float l[UNR][G];
     bool ok[UNR];
     logits(tile, l, ok);
@@ -114,6 +115,10 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
     for (int x = 0; x < NW; ++x) zz += sm[x][g] == -INFINITY ? 0.f : sz[x][g] * exp2f(sm[x][g] - mm);
     Mx[g] = mm;
     inv[g] = 1.0f / zz;
+    if (P.lse) {
+      Mx[g] = P.lse[((size_t)(lb * P.Mq + kh * G + g)) * R + j] * 1.4426950408889634f;
+      inv[g] = 1.0f;
+    }
   }
   // pass B: weights, summed over the group's heads
   float *Sr = P.Srow + ((size_t)u * R + j) * P.Nmax;
@@ -488,6 +493,19 @@ __global__ __launch_bounds__(64) void prefill_stats_merge_kernel(PrefillParams P
     }
   }
   P.Sfin[(size_t)u * G * R16 + idx] = z > 0.f ? make_float2(m, 1.0f / z) : make_float2(0.f, 0.f);
+}
+
+// the same from the caller's log-sum-exp of the window rows (natural log, as attention kernels return it):
+// weight = exp2(logit * scale_log2 - lse * log2(e))
+template <int G>
+__global__ __launch_bounds__(64) void prefill_stats_from_lse_kernel(PrefillParams P) {
+  const int u = blockIdx.x, g = blockIdx.y, j = blockIdx.z * 64 + threadIdx.x;
+  const int b = (u / P.Mkv) % P.B;
+  const int N = P.plen[b], R = P.R, Rw = N < R ? N : R, R16 = (R + 15) & ~15;
+  if (j >= R16) return;
+  float2 st = make_float2(0.f, 0.f);
+  if (j < Rw) st = make_float2(P.lse[((size_t)u * G + g) * R + j] * 1.4426950408889634f, 1.0f);
+  P.Sfin[((size_t)u * G + g) * R16 + j] = st;
 }
 
 // ---- P2: fused score of every older token (Eq.5 / Eq.6 over the window rows)

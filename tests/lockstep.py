@@ -64,9 +64,27 @@ def _gpu_sets(gpu, wl, umap):
     return snaps, wins, pos
 
 
+def window_lse(wl, Qw, K):
+    """Natural-log sum of exp of the window rows' causal logits, [L, B, M, R] fp32, with torch in fp64: what the
+    caller's own attention pass over the prompt would hand over."""
+    L, B, M, R, d = Qw.shape
+    G = wl.n_q_heads // wl.n_kv_heads
+    out = torch.zeros(L, B, M, R, dtype=torch.float64)
+    for b in range(B):
+        N = wl.prompt_lens[b]
+        Rw = min(R, N)
+        q = Qw[:, b, :, :Rw].double().cpu()                               # [L, M, Rw, d]
+        k = K[:, b, :, :N].double().cpu().repeat_interleave(G, dim=1)     # [L, M, N, d]
+        logits = torch.einsum("lmjd,lmnd->lmjn", q, k) / d ** 0.5
+        pj = torch.arange(N - Rw, N)[:, None]
+        logits = logits.masked_fill(torch.arange(N)[None, :] > pj, float("-inf"))
+        out[:, b, :, :Rw] = torch.logsumexp(logits, -1)
+    return out.float()
+
+
 class LockStep:
     def __init__(self, wl, device="cuda:0", batch_index: Optional[List[int]] = None, gen_device=None,
-                 capture_scores=False, per_layer=False):
+                 capture_scores=False, per_layer=False, use_lse=False):
         self.wl = wl
         self.device = device
         self.bidx = list(range(wl.batch)) if batch_index is None else list(batch_index)
@@ -79,6 +97,7 @@ class LockStep:
         self.tol = OUT_TOL[wl.dtype]
         self.scoreF = self.gpu.capture_scores(True) if capture_scores else None
         self.t = 0
+        self.use_lse = use_lse       # prefill through the variant that takes the rows' log-sum-exp from the caller
         self.per_layer = per_layer   # one call per layer (reverse order, to show the calls are independent)
 
     # ---- prefill --------------------------------------------------------
@@ -86,7 +105,8 @@ class LockStep:
         wl, rep = self.wl, self.rep
         Qw, K, V = wl.prompt(self.gen_device)
         plen = wl.prompt_len_tensor().numpy()
-        self.gpu.prefill_select(Qw.to(self.device), K.to(self.device), V.to(self.device), plen)
+        lse = window_lse(wl, Qw, K).to(self.device) if self.use_lse else None
+        self.gpu.prefill_select(Qw.to(self.device), K.to(self.device), V.to(self.device), plen, lse_window=lse)
         ix = torch.tensor(self.bidx, device=Qw.device)
         Qo, Ko, Vo = (t.index_select(1, ix).cpu().contiguous() for t in (Qw, K, V))
         del Qw, K, V

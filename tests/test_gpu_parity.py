@@ -115,6 +115,25 @@ def test_large_shapes(case, oracle_lib):
     assert rep.evictions > 0
 
 
+LSE = [
+    ("bf16", dict(L=2, B=3, M=8, Mkv=2, d=128, dtype="bf16", C=64, R=24, fusion="sum", prompt_lens=(700, 20, 300), steps=30)),
+    ("bf16_g7_max", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(600, 150), steps=30)),
+    ("f32", dict(L=1, B=2, M=8, Mkv=2, d=64, dtype="f32", C=40, R=16, fusion="sum", prompt_lens=(100, 9), steps=30)),
+]
+
+
+@pytest.mark.parametrize("case", LSE, ids=[c[0] for c in LSE])
+def test_prefill_with_callers_lse(case, oracle_lib):
+    """prefill_select_lse: the window rows' log-sum-exp comes from outside (torch, fp64 -> fp32) instead of the
+    library's own statistics pass; selection, recorded rows and the decode steps after it against the oracle."""
+    name, kw = case
+    wl = inputs.small_workload(9000 + LSE.index(case), **kw)
+    ls = _lockstep(wl, DEV, use_lse=True, capture_scores=True).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report("lse_" + name, rep)
+    assert rep.max_score_rel_err <= 1e-5
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")
