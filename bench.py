@@ -93,6 +93,8 @@ def main():
                     help="with --per-layer: the launches of two consecutive steps are captured in a HIP graph once "
                          "and replayed (inputs copied into static buffers before each replay), as serving stacks "
                          "run their decode loops; takes the host out of the measurement")
+    ap.add_argument("--fusion", default=None, choices=["sum", "max", "cumsum"],
+                    help="override the workload's fusion; cumsum = the running-sum comparison policy (H2O's score)")
     ap.add_argument("--evict-every", type=int, default=1,
                     help="T of the coarse schedule (Appendix A.5): selection at every T-th step")
     ap.add_argument("--prefill-repeats", type=int, default=3,
@@ -116,9 +118,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     wl = inputs.workload(args.workload)
-    if args.evict_every != 1:
+    if args.evict_every != 1 or args.fusion:
         import dataclasses
-        wl = dataclasses.replace(wl, evict_every=args.evict_every)
+        wl = dataclasses.replace(wl, evict_every=args.evict_every, fusion=args.fusion or wl.fusion)
     K_steps, W = args.steps, args.warmup
 
     # ---- setup (untimed): prompts, prompt-time selection, run until every cache is full

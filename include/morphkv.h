@@ -40,6 +40,10 @@ extern "C" {
 
 #define MORPHKV_FUSION_SUM 0 /* Eq.5 */
 #define MORPHKV_FUSION_MAX 1 /* Eq.6 */
+/* Comparison policy, not MorphKV: the score of an older token is the running sum of every weight later queries
+ * gave it since it entered the cache, with no window (the accumulated attention score of H2O, Section 5
+ * "Baselines"); the R most recent tokens are still always kept.  For run-time comparison on the same kernel. */
+#define MORPHKV_FUSION_CUMSUM 2
 #define MORPHKV_DTYPE_F32 0
 #define MORPHKV_DTYPE_BF16 1
 
@@ -53,9 +57,13 @@ typedef struct morphkv_config {
   int32_t fusion;         /* MORPHKV_FUSION_* */
   int32_t dtype;          /* element type of q/K/V: MORPHKV_DTYPE_* */
   int32_t evict_every;    /* T of Appendix A.5, 1..64: selection runs at steps whose token position is a
-                             multiple of T; in between up to C+T-1 older tokens are held */
+                             multiple of T; in between up to C+T-1 older tokens are held.
+                             0 = comparison policy, not MorphKV: selection at the prompt only, every later token
+                             is kept (SnapKV, Section 5 "Baselines"); needs max_new_tokens */
   int32_t max_prompt_len; /* largest Nmax that will be passed to prefill_select */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */
+  int32_t max_new_tokens; /* only with evict_every == 0: decode steps the cache has room for (the step after
+                             that returns MORPHKV_ESTATE); otherwise ignored */
 } morphkv_config;
 
 typedef struct morphkv_handle morphkv_handle;
@@ -110,7 +118,7 @@ int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, c
                               float *out, void *stream /* hipStream_t */);
 
 /* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
- *  pos    [U][Cs+R] int32, Cs = C+evict_every-1: slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
+ *  pos    [U][Cs+R] int32, Cs = C+evict_every-1 (C+max_new_tokens when evict_every == 0): slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
  *         window slot (position mod R)
  *  n_snap [U]      int32: older tokens currently held */
 int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream);

@@ -46,6 +46,9 @@ typedef struct {
   int32_t *cand_pos, *cand_col; /* [Cs+1] */
   double *cand_F;               /* [Cs+1] */
   int32_t *choice;              /* [T] */
+  /* running-sum policy (fusion 2) */
+  double *cum;                  /* [Cs] sum of every weight recorded for the older token in the slot */
+  double *S_last;               /* [Cs] what the query in flight adds to it */
   double *k_new, *v_new;        /* [d] staged new token */
   /* prefill scores kept for inspection */
   double *pf_F;
@@ -67,7 +70,7 @@ static double ld(const void *base, size_t i, int dtype) {
   return (double)f;
 }
 
-static double fuse2(int fusion, double a, double b) { return fusion == 0 ? a + b : (a > b ? a : b); }
+static double fuse2(int fusion, double a, double b) { return fusion == 1 ? (a > b ? a : b) : a + b; }
 
 int morphkv_ref_num_threads(void) {
 #ifdef _OPENMP
@@ -81,13 +84,14 @@ int morphkv_ref_create(morphkv_ref **out, const morphkv_ref_config *cfg) {
   if (!out || !cfg) return MORPHKV_REF_EINVAL;
   if (cfg->n_layers < 1 || cfg->batch < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads < 1) return MORPHKV_REF_EINVAL;
   if (cfg->n_q_heads % cfg->n_kv_heads) return MORPHKV_REF_EINVAL;
-  if (cfg->head_dim < 1 || cfg->C < 1 || cfg->R < 1 || cfg->evict_every < 1) return MORPHKV_REF_EINVAL;
-  if (cfg->fusion < 0 || cfg->fusion > 1 || cfg->dtype < 0 || cfg->dtype > 1) return MORPHKV_REF_EINVAL;
+  if (cfg->head_dim < 1 || cfg->C < 1 || cfg->R < 1 || cfg->evict_every < 0) return MORPHKV_REF_EINVAL;
+  if (cfg->evict_every == 0 && cfg->max_new_tokens < 1) return MORPHKV_REF_EINVAL;
+  if (cfg->fusion < 0 || cfg->fusion > 2 || cfg->dtype < 0 || cfg->dtype > 1) return MORPHKV_REF_EINVAL;
   morphkv_ref *h = (morphkv_ref *)calloc(1, sizeof(*h));
   h->c = *cfg;
   h->G = cfg->n_q_heads / cfg->n_kv_heads;
   h->U = cfg->n_layers * cfg->batch * cfg->n_kv_heads;
-  h->Cs = cfg->C + cfg->evict_every - 1;
+  h->Cs = cfg->C + (cfg->evict_every >= 1 ? cfg->evict_every - 1 : cfg->max_new_tokens);
   h->W = h->Cs + cfg->R;
   h->scale = cfg->softmax_scale != 0.0f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)cfg->head_dim);
   h->u = (unit_t *)calloc((size_t)h->U, sizeof(unit_t));
@@ -106,7 +110,9 @@ int morphkv_ref_create(morphkv_ref **out, const morphkv_ref_config *cfg) {
     s->cand_pos = (int32_t *)calloc((size_t)Cs + 1, sizeof(int32_t));
     s->cand_col = (int32_t *)calloc((size_t)Cs + 1, sizeof(int32_t));
     s->cand_F = (double *)calloc((size_t)Cs + 1, sizeof(double));
-    s->choice = (int32_t *)calloc((size_t)cfg->evict_every, sizeof(int32_t));
+    s->choice = (int32_t *)calloc((size_t)(cfg->evict_every > 0 ? cfg->evict_every : 1), sizeof(int32_t));
+    s->cum = (double *)calloc((size_t)Cs, sizeof(double));
+    s->S_last = (double *)calloc((size_t)Cs, sizeof(double));
     s->k_new = (double *)calloc((size_t)d, sizeof(double));
     s->v_new = (double *)calloc((size_t)d, sizeof(double));
   }
@@ -120,7 +126,7 @@ int morphkv_ref_destroy(morphkv_ref *h) {
     unit_t *s = &h->u[i];
     free(s->Ks); free(s->Vs); free(s->pos_s); free(s->Kw); free(s->Vw); free(s->pos_w);
     free(s->row); free(s->row_q); free(s->cand_pos); free(s->cand_col); free(s->cand_F);
-    free(s->choice); free(s->k_new); free(s->v_new); free(s->pf_F);
+    free(s->choice); free(s->k_new); free(s->v_new); free(s->pf_F); free(s->cum); free(s->S_last);
   }
   free(h->u);
   free(h);
@@ -203,6 +209,7 @@ static int prefill_unit(morphkv_ref *h, int l, int b, int kh, const void *Qw, co
   for (int i = 0; i < Cs; ++i) s->pos_s[i] = -1;
   for (int i = 0; i < keep; ++i) {
     s->pos_s[i] = kept[i];
+    s->cum[i] = s->pf_F[kept[i]]; /* used by the running-sum policy only: there F is the sum over the rows */
     for (int e = 0; e < d; ++e) {
       s->Ks[(size_t)i * d + e] = ld(K, kbase + (size_t)kept[i] * d + e, dt);
       s->Vs[(size_t)i * d + e] = ld(V, kbase + (size_t)kept[i] * d + e, dt);
@@ -314,13 +321,15 @@ static void decode_begin_unit(morphkv_ref *h, int l, int b, int kh, const void *
   memset(rw, 0, sizeof(double) * (size_t)W);
   for (int j = 0; j < nr; ++j) rw[col[j]] = S[j];
   s->row_q[w] = p;
+  for (int j = 0; j < nr; ++j)
+    if (col[j] < Cs) s->S_last[col[j]] = S[j]; /* what this query adds to the running sums */
 
   /* the window slides: token p-R (slot w) becomes an older token.  Fuse and decide. */
   s->n_cand = 0;
   s->n_evict = 0;
   for (int i = 0; i < T; ++i) s->choice[i] = -1;
   const int demote = s->pos_w[w] >= 0; /* slot w holds token p-R */
-  if (demote && (p % T) == 0 && s->n_snap + 1 > C) {
+  if (demote && T >= 1 && (p % T) == 0 && s->n_snap + 1 > C) {
     int nc = 0;
     for (int i = 0; i < s->n_snap; ++i) { s->cand_pos[nc] = s->pos_s[i]; s->cand_col[nc] = i; ++nc; }
     s->cand_pos[nc] = s->pos_w[w]; s->cand_col[nc] = Cs + w; ++nc;
@@ -333,6 +342,9 @@ static void decode_begin_unit(morphkv_ref *h, int l, int b, int kh, const void *
         F = first ? v : fuse2(c->fusion, F, v);
         first = 0;
       }
+      /* running-sum policy: an older token's score is everything recorded for it so far; the token leaving
+         the window has been seen by exactly the window's queries, whose rows were just summed */
+      if (c->fusion == 2 && i < s->n_snap) F = s->cum[i] + s->S_last[i];
       s->cand_F[i] = F;
     }
     s->n_cand = nc;
@@ -384,6 +396,7 @@ static int decode_commit_unit(morphkv_ref *h, int u, const int32_t *ev /* [T] or
   const int p = s->next_pos, w = p % R;
   const int32_t *E = ev ? ev : s->choice;
   const int demote = s->pos_w[w] >= 0;
+  for (int j = 0; j < s->n_snap; ++j) s->cum[j] += s->S_last[j];
   if (demote) {
     /* mark what goes */
     int drop_demoted = 0, n_marked = 0;
@@ -404,6 +417,7 @@ static int decode_commit_unit(morphkv_ref *h, int u, const int32_t *ev /* [T] or
       if (gone[j]) continue;
       if (n != j) {
         s->pos_s[n] = s->pos_s[j];
+        s->cum[n] = s->cum[j];
         memcpy(s->Ks + (size_t)n * d, s->Ks + (size_t)j * d, sizeof(double) * (size_t)d);
         memcpy(s->Vs + (size_t)n * d, s->Vs + (size_t)j * d, sizeof(double) * (size_t)d);
         for (int r = 0; r < R; ++r) s->row[(size_t)r * W + n] = s->row[(size_t)r * W + j];
@@ -416,7 +430,11 @@ static int decode_commit_unit(morphkv_ref *h, int u, const int32_t *ev /* [T] or
       s->pos_s[n] = s->pos_w[w];
       memcpy(s->Ks + (size_t)n * d, s->Kw + (size_t)w * d, sizeof(double) * (size_t)d);
       memcpy(s->Vs + (size_t)n * d, s->Vw + (size_t)w * d, sizeof(double) * (size_t)d);
-      for (int r = 0; r < R; ++r) s->row[(size_t)r * W + n] = s->row[(size_t)r * W + Cs + w];
+      s->cum[n] = 0.0;
+      for (int r = 0; r < R; ++r) {
+        s->row[(size_t)r * W + n] = s->row[(size_t)r * W + Cs + w];
+        if (s->row_q[r] >= 0 && s->row_q[r] > p - R) s->cum[n] += s->row[(size_t)r * W + n];
+      }
       ++n;
     }
     for (int j = n; j < Cs; ++j) s->pos_s[j] = -1;

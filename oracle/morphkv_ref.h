@@ -25,11 +25,15 @@ extern "C" {
 
 typedef struct morphkv_ref_config {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim, C, R;
-  int32_t fusion;         /* 0 = sum (Eq.5), 1 = max (Eq.6) */
+  int32_t fusion;         /* 0 = sum (Eq.5), 1 = max (Eq.6); 2 = comparison policy: running sum of every
+                             recorded weight since the token entered the cache, no window (the accumulated
+                             attention score of H2O, Section 2 / Section 5 "Baselines") */
   int32_t dtype;          /* element type of q/K/V inputs: 0 = fp32, 1 = bf16 bits */
-  int32_t evict_every;    /* T of Appendix A.5; 1 = evict at every step */
+  int32_t evict_every;    /* T of Appendix A.5; 1 = evict at every step; 0 = comparison policy: selection at
+                             the prompt only, every later token is kept (SnapKV, Section 5 "Baselines") */
   int32_t max_prompt_len; /* unused by the oracle; kept so one harness fills both structs */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */
+  int32_t max_new_tokens; /* with evict_every == 0: room for this many decode steps; else unused */
 } morphkv_ref_config;
 
 typedef struct morphkv_ref morphkv_ref;
@@ -77,7 +81,7 @@ int morphkv_ref_decode_commit_multi(morphkv_ref *h, const int32_t *evict_pos);
 /* Retained positions: pos [U][C+T-1+R], ascending snapshot positions then ascending
  * window positions, -1 padded at the end; n_snap [U]; n_win [U] (may be NULL). */
 int morphkv_ref_export_positions(morphkv_ref *h, int32_t *pos, int32_t *n_snap, int32_t *n_win);
-int morphkv_ref_row_stride(morphkv_ref *h); /* = C+T-1+R, the pos row length above */
+int morphkv_ref_row_stride(morphkv_ref *h); /* = C+T-1+R (C+max_new_tokens+R when evict_every == 0), the pos row length */
 
 int morphkv_ref_num_threads(void);
 

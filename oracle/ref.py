@@ -32,7 +32,8 @@ def build(force: bool = True) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "C", "R",
-                 "fusion", "dtype", "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float)]
+                 "fusion", "dtype", "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float),
+                                                                         ("max_new_tokens", C.c_int32)]
 
 
 _lib = None
@@ -77,7 +78,7 @@ def _host_ptr(t):
     return C.c_void_p(t.ctypes.data)
 
 
-_FUSION = {"sum": 0, "max": 1}
+_FUSION = {"sum": 0, "max": 1, "cumsum": 2}
 _DTYPE = {"f32": 0, "bf16": 1}
 
 
@@ -85,13 +86,13 @@ class RefMorphKV:
     """The oracle, one instance per configuration (state lives in the C handle)."""
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, fusion, dtype,
-                 evict_every=1, softmax_scale=0.0):
+                 evict_every=1, softmax_scale=0.0, max_new_tokens=0):
         self.cfg = _Cfg(n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R,
-                        _FUSION[fusion], _DTYPE[dtype], evict_every, 0, softmax_scale)
+                        _FUSION[fusion], _DTYPE[dtype], evict_every, 0, softmax_scale, max_new_tokens)
         self.dtype = dtype
         self.U = n_layers * batch * n_kv_heads
         self.C, self.R, self.T = C_, R, evict_every
-        self.Cs = C_ + evict_every - 1
+        self.Cs = C_ + (evict_every - 1 if evict_every >= 1 else max_new_tokens)
         self.out_shape = (n_layers, batch, n_q_heads, head_dim)
         self._h = C.c_void_p()
         rc = lib().morphkv_ref_create(C.byref(self._h), C.byref(self.cfg))
@@ -102,7 +103,7 @@ class RefMorphKV:
     def from_workload(cls, wl, **kw):
         return cls(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                    head_dim=wl.head_dim, C_=wl.C, R=wl.R, fusion=wl.fusion, dtype=wl.dtype,
-                   evict_every=wl.evict_every, **kw)
+                   evict_every=wl.evict_every, max_new_tokens=wl.max_new_tokens, **kw)
 
     def close(self):
         if self._h:
@@ -156,7 +157,7 @@ class RefMorphKV:
         n_evict = np.zeros(self.U, np.int32)
         cand_pos = np.full((self.U, self.Cs + 1), -1, np.int32)
         cand_F = np.zeros((self.U, self.Cs + 1), np.float64)
-        choice = np.full((self.U, self.T), -1, np.int32)
+        choice = np.full((self.U, max(self.T, 1)), -1, np.int32)
         rc = lib().morphkv_ref_candidates(self._h, _host_ptr(n_cand), _host_ptr(cand_pos), _host_ptr(cand_F),
                                           _host_ptr(n_evict), _host_ptr(choice))
         if rc != 0:
@@ -166,7 +167,7 @@ class RefMorphKV:
     def decode_commit(self, evict_pos: Optional[np.ndarray] = None) -> None:
         ep = None
         if evict_pos is not None:
-            ep = np.ascontiguousarray(evict_pos, dtype=np.int32).reshape(self.U, self.T)
+            ep = np.ascontiguousarray(evict_pos, dtype=np.int32).reshape(self.U, max(self.T, 1))
         rc = lib().morphkv_ref_decode_commit_multi(self._h, _host_ptr(ep) if ep is not None else None)
         if rc != 0:
             raise RuntimeError(f"morphkv_ref_decode_commit failed: {rc}")

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MORPHKV_LIB") or os.path.join(_HERE, "libmorphkv.so")  # MORPHKV_LIB: another build
 
 OK, EINVAL, ESTATE, EHIP = 0, -1, -2, -3
-FUSION = {"sum": 0, "max": 1}
+FUSION = {"sum": 0, "max": 1, "cumsum": 2}
 DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
@@ -34,7 +34,7 @@ class MorphKVError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "C", "R", "fusion", "dtype",
-                 "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float)]
+                 "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float), ("max_new_tokens", C.c_int32)]
 
 
 _lib = None
@@ -86,9 +86,9 @@ def _dev_ptr(t: torch.Tensor):
 
 
 def make_config(*, n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, fusion, dtype, max_prompt_len,
-                evict_every=1, softmax_scale=0.0) -> Config:
+                evict_every=1, softmax_scale=0.0, max_new_tokens=0) -> Config:
     return Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, FUSION[fusion], DTYPE[dtype],
-                  evict_every, max_prompt_len, softmax_scale)
+                  evict_every, max_prompt_len, softmax_scale, max_new_tokens)
 
 
 def morphkv_sizes(cfg: Config):
@@ -115,7 +115,7 @@ class MorphKV:
         if self.device.type != "cuda":
             raise ValueError("libmorphkv needs a GPU device")
         self.U = cfg.n_layers * cfg.batch * cfg.n_kv_heads
-        self.n = cfg.C + cfg.evict_every - 1 + cfg.R
+        self.n = cfg.C + (cfg.evict_every - 1 if cfg.evict_every >= 1 else cfg.max_new_tokens) + cfg.R
         self.dtype = _TORCH_DTYPE["f32" if cfg.dtype == 0 else "bf16"]
         cb, rb, sb = morphkv_sizes(cfg)
         self.bytes = (cb, rb, sb)
@@ -132,7 +132,8 @@ class MorphKV:
     def from_workload(cls, wl, device="cuda:0", **kw):
         cfg = make_config(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                           head_dim=wl.head_dim, C_=wl.C, R=wl.R, fusion=wl.fusion, dtype=wl.dtype,
-                          max_prompt_len=wl.Nmax, evict_every=wl.evict_every, **kw)
+                          max_prompt_len=wl.Nmax, evict_every=wl.evict_every,
+                          max_new_tokens=wl.max_new_tokens, **kw)
         return cls(cfg, device)
 
     def close(self):
@@ -218,7 +219,7 @@ class MorphKV:
 
     def export_evicted_list(self):
         """[U, evict_every] int32: every position the last step evicted, -1 padded."""
-        ev = torch.empty(self.U, self.cfg.evict_every, dtype=torch.int32, device=self.device)
+        ev = torch.empty(self.U, max(self.cfg.evict_every, 1), dtype=torch.int32, device=self.device)
         _check(self.lib.morphkv_export_evicted_list(self._h, _dev_ptr(ev), self._stream()))
         return ev
 

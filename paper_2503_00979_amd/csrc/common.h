@@ -31,8 +31,9 @@ template <> struct Elem<bf16_t> {
 // non-negative remainder
 __device__ __host__ inline int pmod(int a, int m) { int r = a % m; return r < 0 ? r + m : r; }
 
-// fusion of two recorded weights: sum (Eq.5) or max (Eq.6); identity is 0 for both (weights >= 0)
-__device__ inline float fuse2(int fusion, float a, float b) { return fusion == 0 ? a + b : fmaxf(a, b); }
+// fusion of two recorded weights: sum (Eq.5; also the running-sum comparison policy, fusion 2) or max (Eq.6);
+// identity is 0 for both (weights >= 0)
+__device__ inline float fuse2(int fusion, float a, float b) { return fusion == 1 ? fmaxf(a, b) : a + b; }
 
 __device__ inline float wave_sum(float v) {
 #pragma unroll

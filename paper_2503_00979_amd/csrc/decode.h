@@ -301,7 +301,12 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 
   const int u = blockIdx.x + P.u0, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
   const int wave = tid / WAVE, lane = tid % WAVE;
-  const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, fusion = P.fusion, cps = P.cps, cpt = P.cpt;
+  const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, cps = P.cps, cpt = P.cpt;
+  // Running-sum policy (fusion 2, the accumulated score of H2O): a column's score is the sum of everything recorded
+  // for it since it entered the cache.  That is the sum fusion with a rebuild point that never comes: the new-part
+  // aggregate is all there is, no column ever takes a turn, the old part is not read.
+  const bool cum = P.fusion == 2;
+  const int fusion = cum ? 0 : P.fusion;
 
   // ---- LDS carve-up
   // rows of the weight array are n_pad + 4 floats apart: the heads then start 4 banks apart and the 16-byte
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   const bool win_full = p >= R;
   const int turn0 = wm1 * cps;             // first column rebuilt this step
   int turn_n = n_snap - turn0;             // how many of them exist
-  turn_n = turn_n < 0 ? 0 : (turn_n > cps ? cps : turn_n);
+  turn_n = turn_n < 0 || cum ? 0 : (turn_n > cps ? cps : turn_n);
 
   float *ringu = P.ring + (size_t)u * R * n_pad;
   float *sfxu = P.sfx + (size_t)u * R * CsP;
@@ -422,7 +427,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   int nrw = (cps + tgw - 1) / tgw;
   nrw = nrw > NW / 2 ? NW / 2 : nrw;
   if (wave >= NW - nrw) {
-    tr.init(lane, p, wm1, n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
+    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
   }
 
   // ---- self logit (every lane ends up with all G values)
@@ -686,7 +691,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = j0 + i;
-        float so = sfo[i];
+        float so = cum ? 0.f : sfo[i];
         if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
         nwo[i] = fuse2(fusion, nwo[i], S[i]);
         if (j < n_snap) {
@@ -972,7 +977,14 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_wave_barrier();
-        move_scan_wave(lane, p, last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP, nwu + dst);
+        if (cum && src != wsl) {
+          // a running sum reaches further back than the R rows: it moves with the token (the record phase's
+          // store of nw[src] is visible since the barrier after the V pass)
+          if (lane == 0) nwu[dst] = nwu[src];
+        } else {
+          move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP,
+                         nwu + dst);
+        }
         constexpr int PCSx = D / EPL;
         if (lane < PCSx) *(uint4 *)(Kx + L::k_off(dst, lane * EPL)) = *(const uint4 *)(Kx + L::k_off(src, lane * EPL));
         if constexpr (L::tiled) {
@@ -1017,7 +1029,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   if (dest >= 0) {
     if (wave == NW - 1) {
       if (lane == 0) posu[dest] = p - R;
-      move_scan_wave(lane, p, last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP, nwu + dest);
+      move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP,
+                     nwu + dest);
     } else {
       const int stride = NT - WAVE;
       int r = (w + 1 + tid) % R;

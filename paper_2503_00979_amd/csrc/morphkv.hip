@@ -60,17 +60,19 @@ int validate(const morphkv_config *c) {
   if (c->head_dim != 64 && c->head_dim != 128) return fail(MORPHKV_EINVAL, "head_dim must be 64 or 128");
   if (c->C < 1) return fail(MORPHKV_EINVAL, "C must be >= 1");
   if (c->R < 1 || c->R > 1024) return fail(MORPHKV_EINVAL, "R must be in 1..1024");
-  if (c->fusion != MORPHKV_FUSION_SUM && c->fusion != MORPHKV_FUSION_MAX)
-    return fail(MORPHKV_EINVAL, "fusion must be 0 (sum) or 1 (max)");
+  if (c->fusion != MORPHKV_FUSION_SUM && c->fusion != MORPHKV_FUSION_MAX && c->fusion != MORPHKV_FUSION_CUMSUM)
+    return fail(MORPHKV_EINVAL, "fusion must be 0 (sum), 1 (max) or 2 (running sum)");
   if (c->dtype != MORPHKV_DTYPE_F32 && c->dtype != MORPHKV_DTYPE_BF16)
     return fail(MORPHKV_EINVAL, "dtype must be 0 (f32) or 1 (bf16)");
-  if (c->evict_every < 1 || c->evict_every > 64) return fail(MORPHKV_EINVAL, "evict_every must be in 1..64");
+  if (c->evict_every < 0 || c->evict_every > 64) return fail(MORPHKV_EINVAL, "evict_every must be in 0..64");
+  if (c->evict_every == 0 && (c->max_new_tokens < 1 || c->max_new_tokens > (1 << 20)))
+    return fail(MORPHKV_EINVAL, "evict_every == 0 (selection at the prompt only) needs max_new_tokens >= 1");
   if (c->max_prompt_len < 1) return fail(MORPHKV_EINVAL, "max_prompt_len must be >= 1");
   if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale))
     return fail(MORPHKV_EINVAL, "softmax_scale must be finite and >= 0");
   const long long U = (long long)c->n_layers * c->batch * c->n_kv_heads;
   if (U > 65535) return fail(MORPHKV_EINVAL, "too many units (layers*batch*kv_heads must be <= 65535)");
-  if ((long long)c->C + c->R > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
+  if ((long long)c->C + c->R + (c->evict_every == 0 ? c->max_new_tokens : 0) > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
   return MORPHKV_OK;
 }
 
@@ -78,7 +80,7 @@ BufLayout make_layout(const morphkv_config *c) {
   BufLayout L{};
   L.U = c->n_layers * c->batch * c->n_kv_heads;
   L.G = c->n_q_heads / c->n_kv_heads;
-  L.Cs = c->C + c->evict_every - 1;
+  L.Cs = c->C + (c->evict_every >= 1 ? c->evict_every - 1 : c->max_new_tokens);
   L.n = L.Cs + c->R;
   L.n_pad = (L.n + 31) / 32 * 32;  // K/V slot arrays are padded to whole tiles
   L.CsP = (L.Cs + 31) / 32 * 32;   // row stride of the per-column state
@@ -106,7 +108,7 @@ BufLayout make_layout(const morphkv_config *c) {
   L.offV = o; o = align_up(o + U * np * d * L.esz);
   L.offPos = o; o = align_up(o + U * np * 4);
   L.offMeta = o; o = align_up(o + U * META * 4);
-  L.offEvl = o; o = align_up(o + U * (size_t)c->evict_every * 4);
+  L.offEvl = o; o = align_up(o + U * (size_t)(c->evict_every > 0 ? c->evict_every : 1) * 4);
   L.cache_bytes = o;
   o = 0;
   L.offRing = o; o = align_up(o + U * R * np * 4);
@@ -158,7 +160,8 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.nw = (float *)(h->ring + L.offNw);
   P.dbgF = h->dbgF;
   P.dbgT = h->dbgT;
-  P.C = h->cfg.C; P.T = h->cfg.evict_every;
+  // selection at the prompt only: the kernel runs its every-step schedule on a cache that never fills up
+  P.C = h->cfg.C; P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.evl = (int32_t *)(h->cache + L.offEvl);
   P.zig = (int32_t)(h->steps & 1u);
   P.cpt_shift = -1;
@@ -399,6 +402,8 @@ int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, con
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!q || !k_new || !v_new || !out) return fail(MORPHKV_EINVAL, "null pointer");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step before prefill_select");
+  if (h->cfg.evict_every == 0 && h->steps >= (unsigned)h->cfg.max_new_tokens)
+    return fail(MORPHKV_ESTATE, "the cache has room for max_new_tokens = %d decode steps only", h->cfg.max_new_tokens);
   DecodeParams P = decode_params(h);
   P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
   const int rc = dispatch_decode(h, P, h->L.U, (hipStream_t)stream);
@@ -413,6 +418,8 @@ int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, c
   if (layer < 0 || layer >= h->cfg.n_layers)
     return fail(MORPHKV_EINVAL, "layer %d outside 0..%d", layer, h->cfg.n_layers - 1);
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step_layer before prefill_select");
+  if (h->cfg.evict_every == 0 && h->layer_steps[layer] + h->steps >= (unsigned)h->cfg.max_new_tokens)
+    return fail(MORPHKV_ESTATE, "the cache has room for max_new_tokens = %d decode steps only", h->cfg.max_new_tokens);
   const int upl = h->cfg.batch * h->cfg.n_kv_heads;  // units per layer
   DecodeParams P = decode_params(h);
   P.u0 = layer * upl;
@@ -458,7 +465,7 @@ int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *strea
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
   const BufLayout &L = h->L;
   const int T = h->cfg.evict_every;
-  if (T == 1) return morphkv_export_evicted(h, evicted, stream);
+  if (T <= 1) return morphkv_export_evicted(h, evicted, stream);
   HIP_TRY(hipMemcpyAsync(evicted, h->cache + L.offEvl, (size_t)L.U * T * 4, hipMemcpyDeviceToDevice,
                          (hipStream_t)stream));
   return MORPHKV_OK;

@@ -673,7 +673,7 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(PrefillParams P) {
   float nwv = 0.f;
   if (c < n_snap) {
     const int p_end = N - 1;
-    const int p0 = last_rebuild_before(p_end, c / P.cps, R);
+    const int p0 = P.fusion == 2 ? p_end - R : last_rebuild_before(p_end, c / P.cps, R);  // running sum: no old part
     nwv = column_scan(
         p_end, p0, R, P.fusion, [&](int t) { return t >= 0 ? ringu[(size_t)pmod(t, R) * P.n_pad + c] : 0.f; },
         [&](int r, float x) { sfxu[(size_t)r * P.CsP + c] = x; });

@@ -112,6 +112,7 @@ class Workload:
     n_outlier_channels: int = 0     # per KV head, key channels scaled by outlier_scale
     outlier_scale: float = 5.0
     evict_every: int = 1
+    max_new_tokens: int = 0   # only with evict_every == 0 (selection at the prompt only): room for decode steps
 
     # ---- derived sizes -------------------------------------------------
     @property
@@ -218,7 +219,7 @@ def workload(name: str) -> Workload:
 
 
 def small_workload(seed: int, *, L=1, B=1, M=4, Mkv=2, d=64, dtype="f32", C=6, R=4, fusion="sum",
-                   prompt_lens=(20,), steps=30, n_outlier_channels=0, evict_every=1) -> Workload:
+                   prompt_lens=(20,), steps=30, n_outlier_channels=0, evict_every=1, max_new_tokens=0) -> Workload:
     """Free-form small case for tests."""
     return Workload(f"small{seed}", L, B, M, Mkv, d, dtype, C, R, fusion, tuple(prompt_lens), steps, seed,
-                    n_outlier_channels=n_outlier_channels, evict_every=evict_every)
+                    n_outlier_channels=n_outlier_channels, evict_every=evict_every, max_new_tokens=max_new_tokens)

@@ -30,10 +30,13 @@ class BruteForceUnit:
         self.last_scores = {}  # candidate position -> fused score, of the last selection
 
     def _fuse(self, vals):
-        return float(sum(vals)) if self.fusion == "sum" else float(max(vals))
+        return float(max(vals)) if self.fusion == "max" else float(sum(vals))
 
     def _select(self, cands, queries):
-        F = {k: self._fuse([self.W[(t, k)] for t in queries]) for k in cands}
+        if self.fusion == "cumsum":  # comparison policy: every weight later queries gave the token, no window
+            queries = None
+        F = {k: (self._fuse([self.W[(t, k)] for t in queries]) if queries is not None else
+                 float(sum(w for (t, kk), w in self.W.items() if kk == k and t > k))) for k in cands}
         self.last_scores = F
         order = sorted(cands, key=lambda k: (-F[k], k))
         return set(order[: self.C])
@@ -72,7 +75,7 @@ class BruteForceUnit:
         self.V.append(v_new.astype(np.float64))
         if p - self.R >= 0:
             cands = sorted(self.old | {p - self.R})
-            if p % self.T == 0 and len(cands) > self.C:
+            if self.T >= 1 and p % self.T == 0 and len(cands) > self.C:   # T == 0: selection at the prompt only
                 self.old = self._select(cands, list(range(p - self.R + 1, p + 1)))
             else:
                 self.old = set(cands)

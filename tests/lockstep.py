@@ -50,7 +50,8 @@ def _gpu_sets(gpu, wl, umap):
     pos, n_snap = gpu.export_positions()
     pos = pos.cpu().numpy()[umap]
     n_snap = n_snap.cpu().numpy()[umap]
-    C = wl.C + wl.evict_every - 1   # older-token slots (more than C are held between coarse selections)
+    # older-token slots: more than C are held between coarse selections, or for good when selection is at the prompt only
+    C = wl.C + (wl.evict_every - 1 if wl.evict_every >= 1 else wl.max_new_tokens)
     snaps, wins = [], []
     for i in range(len(umap)):
         s = pos[i, :C]

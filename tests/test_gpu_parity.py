@@ -134,6 +134,35 @@ def test_prefill_with_callers_lse(case, oracle_lib):
     assert rep.max_score_rel_err <= 1e-5
 
 
+POLICIES = [
+    # comparison policies on the same kernel (Section 5 "Baselines"): running sum without a window (H2O's accumulated
+    # score), selection at the prompt only (SnapKV)
+    ("cumsum_f32", dict(L=1, B=2, M=8, Mkv=2, d=64, dtype="f32", C=40, R=16, fusion="cumsum", prompt_lens=(100, 30), steps=90)),
+    ("cumsum_bf16", dict(L=2, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=96, R=12, fusion="cumsum", prompt_lens=(300, 61), steps=80)),
+    ("cumsum_T4", dict(L=1, B=2, M=4, Mkv=2, d=128, dtype="bf16", C=50, R=9, fusion="cumsum", prompt_lens=(90, 61), steps=80, evict_every=4)),
+    ("prompt_only_sum", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=64, R=16, fusion="sum", prompt_lens=(200, 40), steps=70, evict_every=0, max_new_tokens=70)),
+    ("prompt_only_max_f32", dict(L=1, B=1, M=4, Mkv=2, d=64, dtype="f32", C=20, R=5, fusion="max", prompt_lens=(64,), steps=40, evict_every=0, max_new_tokens=40)),
+]
+
+
+@pytest.mark.parametrize("case", POLICIES, ids=[c[0] for c in POLICIES])
+def test_comparison_policies(case, oracle_lib):
+    name, kw = case
+    wl = inputs.small_workload(8000 + POLICIES.index(case), **kw)
+    ls = _lockstep(wl, DEV, capture_scores=wl.evict_every == 1).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report(name, rep)
+    if wl.evict_every == 0:
+        from paper_2503_00979_amd import binding
+        assert rep.evictions == 0
+        q, k, v = (x.to(DEV) for x in wl.decode_inputs(wl.steps))
+        with pytest.raises(binding.MorphKVError) as e:   # the cache is full: refused, not overrun
+            ls.gpu.decode_step(q, k, v)
+        assert e.value.code == binding.ESTATE
+    else:
+        assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")

@@ -78,6 +78,11 @@ CASES = [
     (7, 4, 1, 1, 5, "max", (8,), 30, 1),        # C = 1
     (8, 4, 2, 6, 4, "sum", (25, 11), 50, 3),    # coarse eviction every 3 steps
     (9, 2, 1, 5, 3, "max", (20,), 50, 8),       # coarse eviction every 8 steps
+    # comparison policies (Section 5 "Baselines"): running sum without a window; selection at the prompt only
+    (10, 4, 2, 5, 3, "cumsum", (22, 7), 50, 1),
+    (11, 2, 1, 4, 4, "cumsum", (30,), 45, 3),
+    (12, 4, 1, 6, 4, "sum", (40, 5), 30, 0),
+    (13, 2, 2, 3, 2, "cumsum", (12,), 25, 0),
 ]
 
 
@@ -85,7 +90,8 @@ CASES = [
 def test_bookkeeping_matches_bruteforce(oracle_lib, case):
     seed, M, Mkv, C, R, fusion, plens, steps, T = case
     wl = inputs.small_workload(100 + seed, L=2, B=len(plens), M=M, Mkv=Mkv, d=8, dtype="f32", C=C, R=R,
-                               fusion=fusion, prompt_lens=plens, steps=steps, evict_every=T)
+                               fusion=fusion, prompt_lens=plens, steps=steps, evict_every=T,
+                               max_new_tokens=steps if T == 0 else 0)
     G = wl.G
     o = _mk(oracle_lib, wl)
     Qw, K, V = wl.prompt()
@@ -125,7 +131,7 @@ def test_bookkeeping_matches_bruteforce(oracle_lib, case):
                     np.testing.assert_allclose(out[l, b, h * G:(h + 1) * G], ob, rtol=0, atol=1e-12)
                     if n_cand[u]:
                         for i in range(n_cand[u]):
-                            assert abs(cand_F[u, i] - bf[u].last_scores[int(cand_pos[u, i])]) <= 1e-13
+                            assert abs(cand_F[u, i] - bf[u].last_scores[int(cand_pos[u, i])]) <= 1e-12
         compare()
 
 
@@ -375,6 +381,9 @@ def test_validation(oracle_lib):
     with pytest.raises(ValueError):
         oracle_lib.RefMorphKV(n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, head_dim=8, C_=0, R=2,
                               fusion="sum", dtype="f32")
+    with pytest.raises(ValueError):       # selection at the prompt only needs room for the decode steps
+        oracle_lib.RefMorphKV(n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, head_dim=8, C_=4, R=2,
+                              fusion="sum", dtype="f32", evict_every=0, max_new_tokens=0)
     o = oracle_lib.RefMorphKV(n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, head_dim=8, C_=4, R=2,
                               fusion="sum", dtype="f32")
     z = torch.zeros(1, 1, 2, 8)
