@@ -10,6 +10,8 @@
  * Parity status: attention/softmax, bookkeeping, fusion arithmetic, tie-break
  * and GQA aggregation are pinned by the CPU tests (dense attention, a
  * dict-based brute force, the paper's worked fusion numbers, closed forms).
+ * The two comparison policies (running-sum score, selection at the prompt
+ * only) are pinned by the same brute force.
  * End-task accuracy (the paper's tables) is "parity unpinned": it needs the
  * paper's models and datasets.
  *
