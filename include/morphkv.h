@@ -56,8 +56,8 @@ typedef struct morphkv_config {
   int32_t R;              /* recent window (H1), 1..1024 */
   int32_t fusion;         /* MORPHKV_FUSION_* */
   int32_t dtype;          /* element type of q/K/V: MORPHKV_DTYPE_* */
-  int32_t evict_every;    /* T of Appendix A.5, 1..64: selection runs at steps whose token position is a
-                             multiple of T; in between up to C+T-1 older tokens are held.
+  int32_t evict_every;    /* T of Appendix A.5, 1..64: selection runs at every T-th generation step of a sequence
+                             (its T-th, 2T-th .. generated token); in between up to C+T-1 older tokens are held.
                              0 = comparison policy, not MorphKV: selection at the prompt only, every later token
                              is kept (SnapKV, Section 5 "Baselines"); needs max_new_tokens */
   int32_t max_prompt_len; /* largest Nmax that will be passed to prefill_select */

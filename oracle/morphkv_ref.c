@@ -46,6 +46,7 @@ typedef struct {
   int32_t *cand_pos, *cand_col; /* [Cs+1] */
   double *cand_F;               /* [Cs+1] */
   int32_t *choice;              /* [T] */
+  int32_t prompt_len;           /* N: generation steps are counted from here */
   /* running-sum policy (fusion 2) */
   double *cum;                  /* [Cs] sum of every weight recorded for the older token in the slot */
   double *S_last;               /* [Cs] what the query in flight adds to it */
@@ -234,6 +235,7 @@ static int prefill_unit(morphkv_ref *h, int l, int b, int kh, const void *Qw, co
     for (int k = n_old; k <= pj; ++k) s->row[(size_t)r * W + Cs + (k % R)] = S[(size_t)j * N + k];
   }
   s->next_pos = N;
+  s->prompt_len = N;
   s->pending = 0;
   free(kept);
   free(S);
@@ -329,7 +331,8 @@ static void decode_begin_unit(morphkv_ref *h, int l, int b, int kh, const void *
   s->n_evict = 0;
   for (int i = 0; i < T; ++i) s->choice[i] = -1;
   const int demote = s->pos_w[w] >= 0; /* slot w holds token p-R */
-  if (demote && T >= 1 && (p % T) == 0 && s->n_snap + 1 > C) {
+  /* selection at every T-th generation step (Appendix A.5): token p is number p - N + 1 of the response */
+  if (demote && T >= 1 && ((p - s->prompt_len + 1) % T) == 0 && s->n_snap + 1 > C) {
     int nc = 0;
     for (int i = 0; i < s->n_snap; ++i) { s->cand_pos[nc] = s->pos_s[i]; s->cand_col[nc] = i; ++nc; }
     s->cand_pos[nc] = s->pos_w[w]; s->cand_col[nc] = Cs + w; ++nc;

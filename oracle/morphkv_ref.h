@@ -31,7 +31,7 @@ typedef struct morphkv_ref_config {
                              recorded weight since the token entered the cache, no window (the accumulated
                              attention score of H2O, Section 2 / Section 5 "Baselines") */
   int32_t dtype;          /* element type of q/K/V inputs: 0 = fp32, 1 = bf16 bits */
-  int32_t evict_every;    /* T of Appendix A.5; 1 = evict at every step; 0 = comparison policy: selection at
+  int32_t evict_every;    /* T of Appendix A.5: selection at every T-th generation step; 1 = at every step; 0 = comparison policy: selection at
                              the prompt only, every later token is kept (SnapKV, Section 5 "Baselines") */
   int32_t max_prompt_len; /* unused by the oracle; kept so one harness fills both structs */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */

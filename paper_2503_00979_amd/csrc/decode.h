@@ -25,7 +25,7 @@
 
 namespace mkv {
 
-constexpr int META = 4;  // per unit: n_snap, next_pos, last_evicted, next_pos mod R
+constexpr int META = 8;  // per unit: n_snap, next_pos, last_evicted, next_pos mod R, prompt length, 3 unused
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -344,6 +344,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
   // the unit's state is asked for first and looked at only after the first K loads are on their way
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
+  const int gen_step = p - meta[4] + 1;                  // the new token is this sequence's gen_step-th generated one
 
   // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
   // depends on the unit's state (the addresses do not)
@@ -760,9 +761,9 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
       colv[R - 1] = shf[0];
       int dest = -1, evicted = -1, ns = n_snap, multi = 0;
       if (win_full) {
-        // a selection is due when the step's position is a multiple of T and more than C older tokens
+        // a selection is due at every T-th generation step, if more than C older tokens
         // would be held; otherwise the token leaving the window is simply kept
-        const bool due = Tev > 1 ? (p % Tev == 0 && n_snap + 1 > P.C) : n_snap >= Cs;
+        const bool due = Tev > 1 ? (gen_step % Tev == 0 && n_snap + 1 > P.C) : n_snap >= Cs;
         if (!due) {
           dest = n_snap;
           ns = n_snap + 1;

@@ -535,7 +535,7 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(PrefillParams P) {
   const int keep = n_old < P.C ? n_old : P.C;
   if (tid == 0) {
     int32_t *m = P.meta + (size_t)u * META;
-    m[0] = keep; m[1] = N; m[2] = -1; m[3] = N % R;
+    m[0] = keep; m[1] = N; m[2] = -1; m[3] = N % R; m[4] = N;
   }
   if (n_old <= P.C) {
     for (int k = tid; k < n_old; k += NT) sel[k] = k;

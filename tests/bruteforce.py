@@ -44,6 +44,7 @@ class BruteForceUnit:
     def prefill(self, Qw: np.ndarray, K: np.ndarray, V: np.ndarray):
         """Qw [G,R,d] (row j = query of position N-min(R,N)+j), K,V [N,d]."""
         N = K.shape[0]
+        self.N = N
         self.K = [K[i].astype(np.float64) for i in range(N)]
         self.V = [V[i].astype(np.float64) for i in range(N)]
         Rw = min(self.R, N)
@@ -75,7 +76,7 @@ class BruteForceUnit:
         self.V.append(v_new.astype(np.float64))
         if p - self.R >= 0:
             cands = sorted(self.old | {p - self.R})
-            if self.T >= 1 and p % self.T == 0 and len(cands) > self.C:   # T == 0: selection at the prompt only
+            if self.T >= 1 and (p - self.N + 1) % self.T == 0 and len(cands) > self.C:   # T == 0: selection at the prompt only
                 self.old = self._select(cands, list(range(p - self.R + 1, p + 1)))
             else:
                 self.old = set(cands)
