@@ -185,6 +185,8 @@ PrefillParams prefill_params(const morphkv_handle *h) {
   P.Vc = h->cache + L.offV;
   P.pos = (int32_t *)(h->cache + L.offPos);
   P.meta = (int32_t *)(h->cache + L.offMeta);
+  P.evl = (int32_t *)(h->cache + L.offEvl);
+  P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.ring = (float *)(h->ring + L.offRing);
   P.sfx = (float *)(h->ring + L.offSfx);
   P.nw = (float *)(h->ring + L.offNw);

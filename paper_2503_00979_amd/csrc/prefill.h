@@ -18,8 +18,9 @@ struct PrefillParams {
   // state written
   void *Kc, *Vc;
   int32_t *pos, *meta;
+  int32_t *evl;            // [U][T] positions evicted by the last step: none yet
   float *ring, *sfx, *nw;
-  int32_t B, Mq, Mkv, C, Cs, CsP, R, n, n_pad, Nmax, fusion, cps;
+  int32_t B, Mq, Mkv, C, Cs, CsP, R, n, n_pad, Nmax, fusion, cps, T;
   float scale_log2;
 };
 
@@ -537,6 +538,7 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(PrefillParams P) {
     int32_t *m = P.meta + (size_t)u * META;
     m[0] = keep; m[1] = N; m[2] = -1; m[3] = N % R; m[4] = N;
   }
+  if (tid < P.T) P.evl[(size_t)u * P.T + tid] = -1;
   if (n_old <= P.C) {
     for (int k = tid; k < n_old; k += NT) sel[k] = k;
     return;

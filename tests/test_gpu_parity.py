@@ -78,6 +78,7 @@ def test_coarse_eviction(case, oracle_lib):
     name, kw = case
     wl = inputs.small_workload(2000 + COARSE.index(case), **kw)
     ls = _lockstep(wl, DEV).prefill()
+    assert bool((ls.gpu.export_evicted_list() == -1).all()), "nothing has been evicted before the first step"
     rep = ls.run(wl.steps, check_every=1)
     _report(name, rep)
     assert rep.evictions > 0
