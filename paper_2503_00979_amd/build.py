@@ -32,11 +32,31 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not needs_build():
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + sources()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", LIB_PATH] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, cwd=CSRC)
+    r = subprocess.run(cmd, cwd=CSRC, stderr=subprocess.PIPE, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr[-4000:])
+    spilling = scratch_users(r.stderr)
+    if spilling:
+        os.remove(LIB_PATH)
+        raise RuntimeError("kernels that spill vector registers to scratch (not allowed, see csrc/decode.h): "
+                           + ", ".join(f"{k} ({b} B/lane)" for k, b in spilling))
     return LIB_PATH
+
+
+def scratch_users(remarks: str):
+    """(kernel, scratch bytes per lane) of every kernel the compiler's resource remarks report scratch for."""
+    out, name = [], None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            b = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if b:
+                out.append((name, b))
+    return out
 
 
 if __name__ == "__main__":

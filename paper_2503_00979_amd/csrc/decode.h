@@ -79,7 +79,7 @@ template <int D> struct Layout<bf16_t, D> {
   }
 };
 
-constexpr int MAXQ = 2;  // groups of 4 columns per thread whose state is prefetched before the K pass
+constexpr int MAXQ = 1;  // groups of 4 columns per thread whose state is prefetched before the K pass
 
 // columns rebuilt per step, padded the way the staging area lays them out
 __host__ __device__ inline int turn_cols_padded(int cps) {
@@ -290,7 +290,7 @@ __device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion
 }
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
+__device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
   // tile groups (K) and tiles (V) a wave keeps in flight.  Two of each (which needs groups of at most 512
@@ -1051,6 +1051,20 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
     m[3] = w + 1 == R ? 0 : w + 1;
     if (P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
   }
+}
+
+// Register budgets.  The compiler version this is built with places spill stores at the top of the block
+// where the lanes of a skipped branch join again, BEFORE it restores their execution mask: a value spilled
+// there is lost for waves that skipped the branch (seen: the fp32 d=64 G=8 build moved only 16 of a key's 256
+// bytes at compaction).  So no build may spill vector registers: the bf16 builds fit 128 registers (1024-thread
+// groups); the fp32 builds, which keep G x 4 products per lane in flight, get 256 (groups of at most 512).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
+  decode_fused_body<T, D, G>(P);
+}
+template <typename T, int D, int G>
+__global__ __launch_bounds__(512) void decode_fused_kernel_512(DecodeParams P) {
+  decode_fused_body<T, D, G>(P);
 }
 
 }  // namespace mkv

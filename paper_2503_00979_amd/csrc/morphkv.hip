@@ -208,11 +208,15 @@ int decode_threads(const morphkv_handle *h, int U) {
 
 template <typename T, int D, int G>
 int launch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
-  const int NT = decode_threads(h, n_units);
+  constexpr bool wide = !Layout<T, D>::tiled;  // fp32 builds: 256 registers a lane, groups of at most 512 threads
+  int NT = decode_threads(h, n_units);
+  if (wide && NT > 512) NT = 512;
   size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps, P.CsP, P.T);
   if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
   if (h->min_lds > lds && h->min_lds <= 160 * 1024) lds = h->min_lds;
-  auto kern = decode_fused_kernel<T, D, G>;
+  void (*kern)(DecodeParams);
+  if constexpr (wide) kern = decode_fused_kernel_512<T, D, G>;
+  else kern = decode_fused_kernel<T, D, G>;
   static size_t attr_set = 0;  // per instantiation
   if (lds > attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -355,7 +359,10 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   // the decode kernel keeps one weight per (head, slot) in LDS: say so now if C + R is too large for that
   const int upl = cfg->batch * cfg->n_kv_heads;
   for (int units : {h->L.U, upl}) {
-    const size_t lds = decode_lds_bytes(h->L.n_pad, h->L.G, cfg->head_dim, decode_threads(h, units), cfg->R, h->L.cps,
+    const size_t lds = decode_lds_bytes(h->L.n_pad, h->L.G, cfg->head_dim,
+                                        cfg->dtype == MORPHKV_DTYPE_F32 ? std::min(decode_threads(h, units), 512)
+                                                                        : decode_threads(h, units),
+                                        cfg->R, h->L.cps,
                                         h->L.CsP, cfg->evict_every);
     if (lds > 160 * 1024) {
       const int n = h->L.n;

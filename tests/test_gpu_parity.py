@@ -164,6 +164,46 @@ def test_comparison_policies(case, oracle_lib):
         assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("G", range(1, 9))
+def test_every_kernel_instantiation(dtype, d, G, oracle_lib):
+    """One short lock-step run per (element type, head dimension, group size): each is a kernel build of its own,
+    with its own register allocation (a build that spilled registers once moved only part of a key)."""
+    wl = inputs.small_workload(555, L=1, B=2, M=G, Mkv=1, d=d, dtype=dtype, C=20, R=6, fusion="sum",
+                               prompt_lens=(50, 9), steps=30)
+    rep = _lockstep(wl, DEV).prefill().run(wl.steps, check_every=1)
+    assert rep.evictions > 0
+
+
+def _random_case(i):
+    """Seeded random small configuration: every knob of the configuration drawn independently."""
+    rng = np.random.default_rng(0xC0FFEE + i)
+    Mkv = int(rng.integers(1, 4))
+    G = int(rng.integers(1, 9))
+    d = int(rng.choice([64, 128]))
+    R = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 64]))
+    C = int(rng.choice([1, 2, 7, 16, 33, 64, 100, 257]))
+    T = int(rng.choice([1, 1, 1, 2, 3, 8, 17, 0]))
+    fusion = str(rng.choice(["sum", "max", "cumsum"]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    B = int(rng.integers(1, 4))
+    lens = tuple(int(x) for x in rng.integers(1, 2 * (C + R) + 8, size=B))
+    steps = int(rng.integers(20, 70))
+    L = int(rng.integers(1, 3))
+    return dict(L=L, B=B, M=Mkv * G, Mkv=Mkv, d=d, dtype=dtype, C=C, R=R, fusion=fusion, prompt_lens=lens, steps=steps,
+                evict_every=T, max_new_tokens=steps if T == 0 else 0)
+
+
+@pytest.mark.parametrize("i", range(48))
+def test_random_small_configs(i, oracle_lib):
+    kw = _random_case(i)
+    wl = inputs.small_workload(10000 + i, **kw)
+    ls = _lockstep(wl, DEV, per_layer=bool(i & 1), use_lse=bool(i & 2)).prefill()
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"random{i} {kw}", rep)
+
+
 def test_c1_full(oracle_lib):
     """c1: toy single layer, fp32, all 64 steps, every unit."""
     wl = inputs.workload("c1")
