@@ -217,13 +217,24 @@ int launch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, h
   void (*kern)(DecodeParams);
   if constexpr (wide) kern = decode_fused_kernel_512<T, D, G>;
   else kern = decode_fused_kernel<T, D, G>;
-  static size_t attr_set = 0;  // per instantiation
-  if (lds > attr_set) {
-    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = lds;
-  }
+  // (the kernel's dynamic-LDS limit was raised when the handle was made, on the device current then)
   hipLaunchKernelGGL(kern, dim3(n_units), dim3(NT), lds, st, P);
   HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+// raises the decode kernel's dynamic-LDS limit for this handle's configuration (once, at creation: not inside a
+// launch, which may be under stream capture)
+template <typename T, int D, int G>
+int set_decode_lds_limit(size_t lds) {
+  void (*kern)(DecodeParams);
+  if constexpr (!Layout<T, D>::tiled) kern = decode_fused_kernel_512<T, D, G>;
+  else kern = decode_fused_kernel<T, D, G>;
+  static size_t limit = 0;  // per kernel build; only ever raised (another handle may need the larger value)
+  if (lds > limit) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    limit = lds;
+  }
   return MORPHKV_OK;
 }
 
@@ -295,6 +306,7 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
 int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
   MKV_DISPATCH(launch_decode, h, h, P, n_units, st);
 }
+int dispatch_lds_limit(const morphkv_handle *h, size_t lds) { MKV_DISPATCH(set_decode_lds_limit, h, lds); }
 int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
   MKV_DISPATCH(launch_prefill, h, h, P, st);
 }
@@ -358,6 +370,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
     (void)hipGetLastError();
   // the decode kernel keeps one weight per (head, slot) in LDS: say so now if C + R is too large for that
   const int upl = cfg->batch * cfg->n_kv_heads;
+  size_t lds_max = 0;
   for (int units : {h->L.U, upl}) {
     const size_t lds = decode_lds_bytes(h->L.n_pad, h->L.G, cfg->head_dim,
                                         cfg->dtype == MORPHKV_DTYPE_F32 ? std::min(decode_threads(h, units), 512)
@@ -369,6 +382,12 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
       delete h;
       return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS in the decode kernel (limit 163840)", n, lds);
     }
+    lds_max = lds > lds_max ? lds : lds_max;
+  }
+  if (h->min_lds > lds_max && h->min_lds <= 160 * 1024) lds_max = h->min_lds;
+  if (const int rc = dispatch_lds_limit(h, lds_max)) {
+    delete h;
+    return rc;
   }
   *out = h;
   return MORPHKV_OK;
