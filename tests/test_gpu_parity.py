@@ -226,13 +226,14 @@ def test_c2_full(oracle_lib):
 def test_c3_sampled_units_full_size(oracle_lib):
     """c3 at full size on the GPU (batch 32, ragged prompts 1k-8k, C=2048, R=128, sum fusion) in the launch
     configuration the benchmark times; the oracle follows a sample of sequences (shortest prompt, whose
-    cache is still filling, and the longest) step by step."""
+    cache fills up during the run, and the longest) step by step."""
     wl = inputs.workload("c3")
     lens = list(wl.prompt_lens)
     sample = sorted({lens.index(min(lens)), lens.index(max(lens))})
     ls = _lockstep(wl, DEV, batch_index=sample, gen_device=DEV).prefill()
-    rep = ls.run(256, check_every=32)
+    rep = ls.run(1280, check_every=64)   # the shortest sequence's cache fills up after ~1150 steps and starts evicting
     _report("c3", rep)
+    assert rep.evictions > 1280 * 8
 
 
 def test_c4_sampled_units_full_size(oracle_lib):
