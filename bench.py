@@ -102,6 +102,8 @@ def main():
                          "median is reported as prefill_select_ms")
     ap.add_argument("--prefill-lse", action="store_true",
                     help="also time prefill_select_lse (window rows' log-sum-exp supplied by the caller)")
+    ap.add_argument("--no-stream-ref", action="store_true",
+                    help="skip the plain streaming-read measurement reported as roofline.stream_read_GBs")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -255,6 +257,24 @@ def main():
             binding.calib_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+    # what this device sustains when a kernel only streams (the practical ceiling next to the data-sheet peak):
+    # a plain read of a buffer as large as the step's K+V, 50 launches back to back
+    stream_gbs = None
+    if not args.no_stream_ref:
+        nbytes = (2 * (wl.C + wl.R) * wl.head_dim * wl.elem_bytes * wl.n_units + 15) // 16 * 16
+        src = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(256, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            binding.calib_read(src, sink)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(50):           # back to back, like the decode steps
+            binding.calib_read(src, sink)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        stream_gbs = nbytes / (ev0.elapsed_time(ev1) / 1e3 / 50) / 1e9
+        del src, sink
     times.sort()
     dev_s, wall_s = times[len(times) // 2]
     sec = max(dev_s, 0.0)                      # HIP events on the launch stream bracket exactly the K kernels
@@ -279,6 +299,8 @@ def main():
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.per_layer or wl.evict_every > 1) else read_traffic(wl.name),
+                     "stream_read_GBs": stream_gbs,
+                     "frac_of_stream_read": (achieved / stream_gbs) if stream_gbs else None,
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A * K_steps // launches,
                      "avg_launch_us": sec / launches * 1e6},
     }

@@ -144,6 +144,11 @@ int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks);
  * profiler's HBM counters are scaled by. */
 int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* Diagnostics: a plain read of `bytes` (multiple of 16) of device memory; every 16-byte piece is loaded once and
+ * folded into sink[256] (device, uint32, xor-accumulated: zero it first if the value matters).  Times what the
+ * device sustains when a kernel only streams: the practical ceiling next to the 8 TB/s of the data sheet. */
+int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream);
+
 const char *morphkv_last_error(void);
 
 #ifdef __cplusplus

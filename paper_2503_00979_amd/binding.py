@@ -22,7 +22,7 @@ _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_prefill_select_lse", "morphkv_decode_step",
            "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
-           "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_last_error")
+           "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_calib_read", "morphkv_last_error")
 
 
 class MorphKVError(RuntimeError):
@@ -64,6 +64,7 @@ def load_library():
     L.morphkv_capture_scores.argtypes = [vp, vp]
     L.morphkv_capture_phase_clocks.argtypes = [vp, vp]
     L.morphkv_calib_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    L.morphkv_calib_read.argtypes = [vp, vp, C.c_size_t, vp]
     L.morphkv_last_error.argtypes = []
     L.morphkv_last_error.restype = C.c_char_p
     for f in EXPORTS[:-1]:
@@ -103,6 +104,13 @@ def calib_copy(dst: torch.Tensor, src: torch.Tensor):
     assert dst.numel() * dst.element_size() == nbytes
     stream = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream)
     _check(load_library().morphkv_calib_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, stream))
+
+
+def calib_read(src: torch.Tensor, sink: torch.Tensor):
+    """Plain streaming read of `src` through the library's yardstick kernel; sink: uint32/int32 [256] device tensor."""
+    assert sink.numel() >= 256 and sink.element_size() == 4
+    stream = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream)
+    _check(load_library().morphkv_calib_read(_dev_ptr(sink), _dev_ptr(src), src.numel() * src.element_size(), stream))
 
 
 class MorphKV:

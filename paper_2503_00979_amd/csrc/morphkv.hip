@@ -516,6 +516,22 @@ int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream) {
   return MORPHKV_OK;
 }
 
+int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream) {
+  if (!sink || !src || (bytes & 15)) return fail(MORPHKV_EINVAL, "calib_read needs non-null pointers and a multiple of 16 bytes");
+  const size_t nvec = bytes / 16;
+  if (nvec == 0) return MORPHKV_OK;
+  // one 1024-thread group per CU (as the decode kernel runs c3), each on its own contiguous share
+  int dev = 0, n_cu = 256;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+  else (void)hipGetLastError();
+  const size_t per_block = (nvec + (size_t)n_cu - 1) / (size_t)n_cu;
+  hipLaunchKernelGGL(calib_read_kernel, dim3(n_cu), dim3(1024), 0, (hipStream_t)stream, sink, (const uint4 *)src, nvec,
+                     per_block);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
 int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   h->dbgT = clocks;
