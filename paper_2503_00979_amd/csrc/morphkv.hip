@@ -263,8 +263,12 @@ int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t 
   }
   hipLaunchKernelGGL(prefill_select_kernel, dim3(U), dim3(1024), 0, st, P);
   HIP_TRY(hipGetLastError());
-  constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
-  hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
+  if constexpr (mfma) {
+    hipLaunchKernelGGL((prefill_gather_tiled_kernel<D>), dim3(P.n_pad / 32, U), dim3(256), 0, st, P);
+  } else {
+    constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
+    hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
+  }
   HIP_TRY(hipGetLastError());
   if constexpr (mfma)
     hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_RING>), dim3((P.n_pad + PF_BLOCK - 1) / PF_BLOCK, U), dim3(256),

@@ -641,6 +641,59 @@ __global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
   }
 }
 
+// ---- P4a (bf16): the same through LDS, one workgroup per 32 slots: the rows come in as whole 2*D-byte reads,
+// the tiles go out as what they are in memory -- two K tiles and one V tile, each contiguous -- in 16-byte stores
+template <int D>
+__global__ __launch_bounds__(256) void prefill_gather_tiled_kernel(PrefillParams P) {
+  constexpr int C8 = D / 8;               // 16-byte pieces per row
+  constexpr int KB = D / 32, CB = D / 16;
+  constexpr int ROW = C8 + 1;             // LDS row stride in pieces (+1: the column reads below spread over the banks)
+  __shared__ uint4 kr[32 * ROW], vr[32 * ROW];
+  __shared__ int srcs[32];
+  const int u = blockIdx.y, tid = threadIdx.x, slot0 = blockIdx.x * 32;
+  const int b = (u / P.Mkv) % P.B, N = P.plen[b];
+  const int n_snap = P.meta[(size_t)u * META];
+  if (tid < 32) {
+    const int slot = slot0 + tid;
+    const int src = slot < P.n ? prefill_slot_source(P, u, slot, N, n_snap) : -1;
+    srcs[tid] = src;
+    P.pos[(size_t)u * P.n_pad + slot] = src;   // n_pad is a multiple of 32: the slot exists
+  }
+  __syncthreads();
+  const bf16_t *Ku = (const bf16_t *)P.K + (size_t)u * P.Nmax * D;
+  const bf16_t *Vu = (const bf16_t *)P.V + (size_t)u * P.Nmax * D;
+  for (int e = tid; e < 32 * C8; e += 256) {
+    const int row = e / C8, c8 = e % C8, src = srcs[row];
+    uint4 k = {0u, 0u, 0u, 0u}, v = k;
+    if (src >= 0) {
+      k = *(const uint4 *)(Ku + (size_t)src * D + c8 * 8);
+      v = *(const uint4 *)(Vu + (size_t)src * D + c8 * 8);
+    }
+    kr[row * ROW + c8] = k;
+    vr[row * ROW + c8] = v;
+  }
+  __syncthreads();
+  // K: tile t (16 slots), k-block kb: lane l = kq*16 + m holds channels kb*32 + kq*8 .. +8 of slot m
+  bf16_t *Kc = (bf16_t *)P.Kc + (size_t)u * P.n_pad * D + (size_t)(slot0 / 16) * 16 * D;
+  for (int e = tid; e < 2 * KB * 64; e += 256) {
+    const int t = e / (KB * 64), kb = (e / 64) % KB, l = e % 64, kq = l >> 4, m = l & 15;
+    *(uint4 *)(Kc + ((size_t)(t * KB + kb) * 64 + l) * 8) = kr[(t * 16 + m) * ROW + kb * 4 + kq];
+  }
+  // V: channel block cb: lane l = kq*16 + nn holds slots kq*8 .. +8 of channel cb*16 + nn
+  bf16_t *Vc = (bf16_t *)P.Vc + (size_t)u * P.n_pad * D + (size_t)(slot0 / 32) * 32 * D;
+  const uint16_t *vr16 = (const uint16_t *)vr;
+  for (int e = tid; e < CB * 64; e += 256) {
+    const int cb = e / 64, l = e % 64, kq = l >> 4, ch = cb * 16 + (l & 15);
+    uint16_t x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = vr16[(size_t)((kq * 8 + i) * ROW) * 8 + ch];
+    uint4 o;
+    o.x = x[0] | ((uint32_t)x[1] << 16); o.y = x[2] | ((uint32_t)x[3] << 16);
+    o.z = x[4] | ((uint32_t)x[5] << 16); o.w = x[6] | ((uint32_t)x[7] << 16);
+    *(uint4 *)(Vc + ((size_t)cb * 64 + l) * 8) = o;
+  }
+}
+
 // ---- P4b: recorded rows restricted to the resident columns
 __global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
   const int u = blockIdx.y, col = blockIdx.x * blockDim.x + threadIdx.x;
