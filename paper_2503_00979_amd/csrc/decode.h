@@ -345,6 +345,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
   const int gen_step = p - meta[4] + 1;                  // the new token is this sequence's gen_step-th generated one
+  const bool sel_step = P.T > 1 && gen_step % P.T == 0;  // coarse schedule: a step at which a selection may run
 
   // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
   // depends on the unit's state (the addresses do not)
@@ -698,7 +699,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
         if (j < n_snap) {
           const float F = fuse2(fusion, so, nwo[i]);
           if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-          if (Tev > 1) { Fl[j] = F; Pl[j] = pj[i]; }
+          if (sel_step) { Fl[j] = F; Pl[j] = pj[i]; }
           if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         }
       }
@@ -763,7 +764,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       if (win_full) {
         // a selection is due at every T-th generation step, if more than C older tokens
         // would be held; otherwise the token leaving the window is simply kept
-        const bool due = Tev > 1 ? (gen_step % Tev == 0 && n_snap + 1 > P.C) : n_snap >= Cs;
+        const bool due = Tev > 1 ? (sel_step && n_snap + 1 > P.C) : n_snap >= Cs;
         if (!due) {
           dest = n_snap;
           ns = n_snap + 1;
