@@ -409,7 +409,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 
   // ---- column of the token leaving the window (rows of steps p-R+1 .. p-1, oldest first): into registers
   // now, into LDS after the K pass
-  constexpr int CVB = 4;  // R - 1 <= 1023 values over >= 256 threads
+  constexpr int CVB = 4;  // R - 1 <= 1023 values over >= 256 threads (groups of 128: R <= 512, the host sees to it)
   float cvr[CVB];
   {
 #pragma unroll
@@ -1014,8 +1014,8 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     *src = ((const uint4 *)knew)[tid];
   }
   if constexpr (L::tiled) {
-    // V: one element per (slot, channel) in tile order.  Uses the threads after the K pieces.
-    for (int ch = tid - 64; ch >= 0 && ch < D; ch += NT) {
+    // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
+    for (int ch = NT - 1 - tid; ch < D; ch += NT) {
       uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
       if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = *src;
       *src = ((const uint16_t *)vnew)[ch];

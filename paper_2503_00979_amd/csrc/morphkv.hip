@@ -142,7 +142,7 @@ struct morphkv_handle {
   std::vector<unsigned> layer_steps;  // decode steps of each layer taken by per-layer calls
   float scale_log2;
   int n_cu;
-  int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 256..1024): tuning override, 0 = choose
+  int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
 };
 
@@ -199,8 +199,10 @@ PrefillParams prefill_params(const morphkv_handle *h) {
 // threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
 // over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
 int decode_threads(const morphkv_handle *h, int U) {
-  if (h->force_threads) return h->force_threads;
+  if (h->force_threads) return h->force_threads == 128 && h->cfg.R > 512 ? 256 : h->force_threads;
   const int cu = h->n_cu > 0 ? h->n_cu : 256;
+  // (a thread keeps at most 4 of the R-1 rows of the leaving token's column: groups of 128 need R <= 512)
+  if (U >= 8 * cu && h->cfg.R <= 512) return 128;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
   return 1024;
@@ -364,7 +366,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   if (const char *e = std::getenv("MORPHKV_DECODE_MIN_LDS")) h->min_lds = (size_t)std::atol(e);
   if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
     const int v = std::atoi(e);
-    if (v >= 256 && v <= 1024 && v % 64 == 0) h->force_threads = v;
+    if (v >= 128 && v <= 1024 && v % 64 == 0) h->force_threads = v;
   }
   int dev = 0;
   hipDeviceProp_t prop;
