@@ -392,3 +392,77 @@ def test_validation(oracle_lib):
     with pytest.raises(RuntimeError):
         o.prefill_select(torch.zeros(1, 1, 2, 2, 8), torch.zeros(1, 1, 2, 5, 8), torch.zeros(1, 1, 2, 5, 8),
                          np.array([6], np.int32))   # prompt_len > Nmax
+
+
+# ---- dense causal attention over the prompt (the pass that selection over the prompt can share)
+def _rand_qkv(seed, M, Mk, N, d):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((M, N, d)), rng.standard_normal((Mk, N, d)), rng.standard_normal((Mk, N, d))
+
+
+@pytest.mark.parametrize("M,Mk,N,d", [(4, 2, 37, 16), (7, 1, 50, 8), (2, 2, 1, 4)])
+def test_prompt_attention_matches_library_sdpa(M, Mk, N, d):
+    """Against torch's scaled_dot_product_attention (an independent library routine) in fp64."""
+    from oracle.prompt_attn_ref import prompt_attention
+    Q, K, V = _rand_qkv(11 + N, M, Mk, N, d)
+    O, lse = prompt_attention(Q, K, V, N)
+    G = M // Mk
+    q, k, v = (torch.from_numpy(x) for x in (Q, K, V))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q[None], k.repeat_interleave(G, 0)[None], v.repeat_interleave(G, 0)[None], is_causal=True)[0].numpy()
+    assert np.abs(O - ref).max() < 1e-12
+    # lse against scipy's logsumexp row by row
+    from scipy.special import logsumexp
+    for h in range(M):
+        for i in (0, N // 2, N - 1):
+            l = (K[h // G, :i + 1] @ Q[h, i]) / np.sqrt(d)
+            assert abs(lse[h, i] - logsumexp(l)) < 1e-12
+
+
+def test_prompt_attention_closed_forms():
+    """Identical keys: every causal row is uniform, so O[i] is the running mean of V and lse[i] = q.k/sqrt(d) +
+    log(i+1); the first row returns V[0] whatever the logits; rows beyond N are ignored."""
+    from oracle.prompt_attn_ref import prompt_attention
+    rng = np.random.default_rng(5)
+    M, Mk, N, d = 4, 2, 23, 8
+    Q = rng.standard_normal((M, N + 3, d))
+    k0 = rng.standard_normal((Mk, 1, d))
+    K = np.repeat(k0, N + 3, axis=1)
+    K[:, N:] = 1e9                      # padding rows must not matter
+    V = rng.standard_normal((Mk, N + 3, d))
+    O, lse = prompt_attention(Q, K, V, N)
+    G = M // Mk
+    for h in range(M):
+        run = np.cumsum(V[h // G, :N], axis=0) / np.arange(1, N + 1)[:, None]
+        assert np.abs(O[h] - run).max() < 1e-12
+        want = (Q[h, :N] @ k0[h // G, 0]) / np.sqrt(d) + np.log(np.arange(1, N + 1))
+        assert np.abs(lse[h] - want).max() < 1e-12
+    Q2, K2, V2 = _rand_qkv(3, M, Mk, N, d)
+    O2, _ = prompt_attention(Q2, K2, V2, N)
+    for h in range(M):
+        assert np.abs(O2[h, 0] - V2[h // G, 0]).max() < 1e-14
+
+
+def test_prompt_attention_window_rows_give_selection_scores(oracle_lib):
+    """The window rows' weights recovered from lse (exp(logit - lse), summed over the group) are the rows the
+    selection oracle fuses (Eq.4): the fused scores it reports for a prompt equal the ones built from this pass."""
+    from oracle.prompt_attn_ref import prompt_attention
+    wl = inputs.small_workload(77, M=4, Mkv=2, d=16, C=5, R=4, prompt_lens=(19,), fusion="sum")
+    Qw, K, V = wl.prompt()
+    N, R, G, d = 19, 4, 2, 16
+    o = oracle_lib.RefMorphKV.from_workload(wl)
+    o.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())
+    rng = np.random.default_rng(1)
+    for u in range(wl.n_units):
+        Qfull = rng.standard_normal((G, N, d))
+        Qfull[:, N - R:] = Qw[0, 0, u * G:(u + 1) * G].double().numpy()
+        _, lse = prompt_attention(Qfull, K[0, 0, u:u + 1].double().numpy(), V[0, 0, u:u + 1].double().numpy(), N)
+        Ku = K[0, 0, u, :N].double().numpy()
+        F = np.zeros(N - R)
+        for j in range(N - R, N):
+            for g in range(G):
+                w = np.exp((Ku[:j + 1] @ Qfull[g, j]) / np.sqrt(d) - lse[g, j])
+                F += w[:N - R]
+        got = o.prefill_scores(u)[:N - R]
+        assert np.abs(got - F).max() < 1e-12
+    o.close()
