@@ -100,6 +100,23 @@ int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const vo
                                const float *lse_window, const int32_t *prompt_len, int32_t Nmax,
                                void *stream /* hipStream_t */);
 
+/* The prompt's attention pass and the selection over the prompt in one call (Section 8 "future work": selection
+ * fused with the attention kernel; Eq.1 at every prompt position with the token attending to itself, then Eq.4-7).
+ * bf16 configurations only (MORPHKV_EINVAL otherwise).
+ *  Q        device [L][B][M][Nmax][d]   queries of every prompt position (rows >= N_b are ignored padding)
+ *  K, V     device [L][B][M'][Nmax][d]  as in morphkv_prefill_select
+ *  O        device [L][B][M][Nmax][d]   bf16, written: O[i] = sum_{k<=i} softmax_k(scale q_i.k_k) v_k for i < N_b;
+ *                                       rows >= N_b are left untouched
+ *  lse      device [L][B][M][Nmax] fp32 or NULL: natural log of the sum of exp over each row's causal logits
+ *  prompt_len HOST [B]
+ * The weights that multiply V are rounded to bf16 (as the matrix cores take them), their sum is kept in fp32.
+ * The window rows' normalisers go from the attention pass straight to the selection, whose own statistics pass
+ * over the prompt is skipped, and the window queries are read in place from Q.  The state left behind is that
+ * of morphkv_prefill_select on (the last R rows of Q, K, V).  Q, K, V, O 16-byte aligned; all caller-owned. */
+int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O,
+                                  float *lse, const int32_t *prompt_len, int32_t Nmax,
+                                  void *stream /* hipStream_t */);
+
 /* One decode step for all units (Eq.1, Algorithm 1, Eq.7).
  *  q      device [L][B][M][d]    query of the new token
  *  k_new  device [L][B][M'][d]   its key   (enters the window after the step)

@@ -19,7 +19,8 @@ FUSION = {"sum": 0, "max": 1, "cumsum": 2}
 DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
-EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_prefill_select_lse", "morphkv_decode_step",
+EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_prefill_select_lse",
+           "morphkv_prefill_attend_select", "morphkv_decode_step",
            "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
            "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_calib_read", "morphkv_last_error")
@@ -56,6 +57,7 @@ def load_library():
     L.morphkv_destroy.argtypes = [vp]
     L.morphkv_prefill_select.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_prefill_select_lse.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
+    L.morphkv_prefill_attend_select.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.morphkv_decode_step_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp]
     L.morphkv_export_positions.argtypes = [vp, vp, vp, vp]
@@ -178,6 +180,27 @@ class MorphKV:
             return
         _check(self.lib.morphkv_prefill_select(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V), pl, Nmax,
                                                self._stream()))
+
+    def prefill_attend_select(self, Q, K, V, prompt_len, O=None, lse=None):
+        """Causal attention over the whole prompt (O, optionally lse, are written) and the selection over it.
+
+        Q [L, B, M, Nmax, d], K/V [L, B, M', Nmax, d] bf16; O like Q (allocated if None); lse fp32 [L, B, M, Nmax] or None.
+        """
+        c = self.cfg
+        Nmax = K.shape[3]
+        self._want(Q, (c.n_layers, c.batch, c.n_q_heads, Nmax, c.head_dim))
+        self._want(K, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        self._want(V, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        if O is None:
+            O = torch.zeros_like(Q)
+        self._want(O, Q.shape)
+        if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:-1])):
+            raise ValueError("lse must be fp32 [L, B, M, Nmax]")
+        pl = (C.c_int32 * c.batch)(*[int(x) for x in prompt_len])
+        _check(self.lib.morphkv_prefill_attend_select(self._h, _dev_ptr(Q), _dev_ptr(K), _dev_ptr(V), _dev_ptr(O),
+                                                      _dev_ptr(lse) if lse is not None else None, pl, Nmax,
+                                                      self._stream()))
+        return O
 
     def decode_step(self, q, k_new, v_new, out=None):
         c = self.cfg

@@ -16,6 +16,7 @@
 #include "common.h"
 #include "decode.h"
 #include "prefill.h"
+#include "prompt_attn.h"
 
 using namespace mkv;
 
@@ -46,7 +47,7 @@ struct BufLayout {
   // scores_ring
   size_t offRing, offSfx, offNw, ring_bytes;
   // scratch
-  size_t offSrow, offStat, offF, offSel, offPlen, scratch_bytes;
+  size_t offSrow, offStat, offF, offSel, offPlen, offLseW, scratch_bytes;
 };
 
 int validate(const morphkv_config *c) {
@@ -125,6 +126,7 @@ BufLayout make_layout(const morphkv_config *c) {
   L.offF = o; o = align_up(o + U * Nm * 4);
   L.offSel = o; o = align_up(o + U * (size_t)L.Cs * 4);
   L.offPlen = o; o = align_up(o + (size_t)c->batch * 4);
+  L.offLseW = o; o = align_up(o + U * (size_t)L.G * R * 4);  // window rows' log-sum-exp from the prompt's attention pass
   L.scratch_bytes = o;
   return L;
 }
@@ -193,6 +195,8 @@ PrefillParams prefill_params(const morphkv_handle *h) {
   P.B = h->cfg.batch; P.Mq = h->cfg.n_q_heads; P.Mkv = h->cfg.n_kv_heads; P.C = h->cfg.C; P.Cs = L.Cs; P.CsP = L.CsP;
   P.R = h->cfg.R; P.n = L.n; P.n_pad = L.n_pad; P.fusion = h->cfg.fusion; P.cps = L.cps;
   P.scale_log2 = h->scale_log2;
+  P.q_rows = h->cfg.R;
+  P.q_prompt = 0;
   return P;
 }
 
@@ -317,6 +321,36 @@ int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_
   MKV_DISPATCH(launch_prefill, h, h, P, st);
 }
 
+// causal attention over the prompt, bf16 only
+template <int D, int G>
+int launch_prompt_attn(const PromptAttnParams &P, int U, hipStream_t st) {
+  using Cf = PromptAttnCfg<D, G>;
+  static bool raised = false;  // the kernel's LDS need is a constant of the build: ask once per process
+  if (!raised) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&prompt_attn_kernel<D, G>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::lds_bytes));
+    raised = true;
+  }
+  hipLaunchKernelGGL((prompt_attn_kernel<D, G>), dim3((P.Nmax + Cf::BM - 1) / Cf::BM, U), dim3(Cf::NT), Cf::lds_bytes,
+                     st, P);
+  HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+template <int D>
+int dispatch_prompt_attn_g(int G, const PromptAttnParams &P, int U, hipStream_t st) {
+  switch (G) {
+    case 1: return launch_prompt_attn<D, 1>(P, U, st);
+    case 2: return launch_prompt_attn<D, 2>(P, U, st);
+    case 3: return launch_prompt_attn<D, 3>(P, U, st);
+    case 4: return launch_prompt_attn<D, 4>(P, U, st);
+    case 5: return launch_prompt_attn<D, 5>(P, U, st);
+    case 6: return launch_prompt_attn<D, 6>(P, U, st);
+    case 7: return launch_prompt_attn<D, 7>(P, U, st);
+    case 8: return launch_prompt_attn<D, 8>(P, U, st);
+    default: return fail(MORPHKV_EINVAL, "group size %d not supported", G);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -424,6 +458,43 @@ int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const vo
   P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax; P.lse = lse_window;
   HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
   int rc = dispatch_prefill(h, P, st);
+  if (rc) return rc;
+  h->prefilled = true;
+  h->steps = 0;
+  std::fill(h->layer_steps.begin(), h->layer_steps.end(), 0u);
+  return MORPHKV_OK;
+}
+
+int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O, float *lse,
+                                  const int32_t *prompt_len, int32_t Nmax, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (!Q || !K || !V || !O || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
+  if (h->cfg.dtype != MORPHKV_DTYPE_BF16)
+    return fail(MORPHKV_EINVAL, "prefill_attend_select is built for bf16 only");
+  if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
+    return fail(MORPHKV_EINVAL, "Nmax %d outside 1..max_prompt_len (%d)", Nmax, h->cfg.max_prompt_len);
+  for (int b = 0; b < h->cfg.batch; ++b)
+    if (prompt_len[b] < 1 || prompt_len[b] > Nmax)
+      return fail(MORPHKV_EINVAL, "prompt_len[%d] = %d outside 1..Nmax (%d)", b, prompt_len[b], Nmax);
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
+    return fail(MORPHKV_EINVAL, "Q, K, V and O must be 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  PrefillParams P = prefill_params(h);
+  HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
+  PromptAttnParams A{};
+  A.Q = (const bf16_t *)Q; A.K = (const bf16_t *)K; A.V = (const bf16_t *)V; A.O = (bf16_t *)O;
+  A.lse = lse;
+  A.lse_w = (float *)(h->scratch + h->L.offLseW);
+  A.plen = P.plen;
+  A.B = h->cfg.batch; A.Mq = h->cfg.n_q_heads; A.Mkv = h->cfg.n_kv_heads; A.R = h->cfg.R; A.Nmax = Nmax;
+  A.scale_log2 = h->scale_log2;
+  int rc = h->cfg.head_dim == 128 ? dispatch_prompt_attn_g<128>(h->L.G, A, h->L.U, st)
+                                  : dispatch_prompt_attn_g<64>(h->L.G, A, h->L.U, st);
+  if (rc) return rc;
+  // selection over the prompt, with the window queries read in place and their normalisers from the pass above
+  P.Qw = Q; P.q_rows = Nmax; P.q_prompt = 1;
+  P.K = K; P.V = V; P.Nmax = Nmax; P.lse = A.lse_w;
+  rc = dispatch_prefill(h, P, st);
   if (rc) return rc;
   h->prefilled = true;
   h->steps = 0;

@@ -8,7 +8,9 @@
 namespace mkv {
 
 struct PrefillParams {
-  const void *Qw, *K, *V;  // [L][B][M][R][D], [L][B][M'][Nmax][D] x2
+  const void *Qw, *K, *V;  // [L][B][M][q_rows][D], [L][B][M'][Nmax][D] x2
+  int32_t q_rows, q_prompt;  // rows per head in Qw; 0: row j is window query j (q_rows = R), 1: Qw holds every
+                             // prompt position's query (q_rows = Nmax) and window query j is row N - min(R,N) + j
   const int32_t *plen;     // device [B]
   float *Srow;             // scratch [U][R][Nmax]: group-summed weights of window query j on key k
   const float *lse;        // nullable, [L][B][M][R]: natural-log sum of exp of the window rows' causal logits, from the caller
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
   float qf[G][EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const T *qp = (const T *)P.Qw + (((size_t)(lb * P.Mq + kh * G + g)) * R + j) * D;
+    const T *qp = (const T *)P.Qw + (((size_t)(lb * P.Mq + kh * G + g)) * P.q_rows + (P.q_prompt ? N - Rw : 0) + j) * D;
     uint4 r = ((const uint4 *)qp)[chunk];
     Elem<T>::unpack(r, qf[g]);
 #pragma unroll
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams P) {
 //   PF_RING   the same weights for the slots of the cache after the gather, stored as the recorded rows
 // MFMA 16x16x32: D[key][query]; a lane owns one query (column) and 4 consecutive keys of each tile.
 enum { PF_STATS = 0, PF_FUSE = 1, PF_RING = 2 };
-constexpr int PF_KT = 4;                  // key tiles a wave holds                  // key tiles a wave holds                  // key tiles a wave holds                  // key tiles a wave holds
+constexpr int PF_KT = 4;                  // key tiles a wave holds
 constexpr int PF_BLOCK = 4 * PF_KT * 16;  // keys (slots) per workgroup
 
 template <int D, int G, int MODE>
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
 
   // ---- staging of a query tile: thread -> (query jq, 8 channels c8) of every head; a row of 16 threads
   // reads one 256-byte query row, and the piece lands where lane (kq, jq) of k-block kb will look for it
-  const bf16_t *Qu = (const bf16_t *)P.Qw + (size_t)u * G * R * D;
+  const bf16_t *Qu = (const bf16_t *)P.Qw + ((size_t)u * G * P.q_rows + (P.q_prompt ? N - Rw : 0)) * D;
   const float2 *stu = P.Sfin + (size_t)u * G * R16;
   constexpr int C8 = D / 8;                      // 16-byte pieces per query row
   constexpr int QPT = (16 * C8 + 255) / 256;     // query rows a thread fetches per head (1 for d <= 128)
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
     for (int qi = 0; qi < QPT; ++qi) {
       const int e = tid + qi * 256, jq = e / C8, c8 = e % C8, j = jt * 16 + jq;
       sq[g][qi] = make_uint4(0u, 0u, 0u, 0u);
-      if (jq < 16 && j < Rw) sq[g][qi] = *(const uint4 *)(Qu + ((size_t)g * R + j) * D + c8 * 8);
+      if (jq < 16 && j < Rw) sq[g][qi] = *(const uint4 *)(Qu + ((size_t)g * P.q_rows + j) * D + c8 * 8);
     }
   };
   auto stash = [&](int buf, int g) {

@@ -1,0 +1,243 @@
+// Causal attention over the whole prompt (Eq.1 at every prompt position, a token attends to itself) that also
+// hands the window rows' softmax normalisers to the selection over the prompt (Eq.4-7): the statistics pass of
+// that selection disappears, the prompt's keys are scored with the normalisers this pass has already made
+// (the fusion of selection with the prompt's attention pass that the paper's closing section leaves as future work).
+//
+// bf16 in, fp32 accumulate, bf16 out, v_mfma_f32_32x32x16_bf16.  One workgroup = 32*QB query rows of the G
+// query heads that share one KV head: every K/V tile staged in LDS is used by all of them.  A wave owns 32
+// rows of one head and keeps, per lane, ONE query column of the transposed problem
+//     S^T[key][query] = K Q^T          (A = keys from LDS, B = the wave's query fragments, in registers)
+//     O^T[dv][query] += V^T P^T        (A = transposed values from LDS, B = the exponentials just computed)
+// so the results of the first product are, as they lie in registers, the B operand of the second, and the row
+// statistics (running maximum, running sum) are per-lane scalars shared by the two lanes l and l+32.
+#pragma once
+#include "common.h"
+
+namespace mkv {
+
+typedef __bf16 pa_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 pa_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float pa_f32x16 __attribute__((ext_vector_type(16)));
+typedef float pa_f32x2 __attribute__((ext_vector_type(2)));
+
+struct PromptAttnParams {
+  const bf16_t *Q, *K, *V;  // [L][B][M][Nmax][D], [L][B][M'][Nmax][D] x2
+  bf16_t *O;                // [L][B][M][Nmax][D]; rows at or beyond a sequence's prompt length are not written
+  float *lse;               // nullable, [L][B][M][Nmax]: natural-log sum of exp of each row's causal logits
+  float *lse_w;             // [L][B][M][R]: the same for the last min(R, N) rows (row j = position N - min(R,N) + j)
+  const int32_t *plen;      // device [B]
+  int32_t B, Mq, Mkv, R, Nmax;
+  float scale_log2;         // softmax scale * log2(e), > 0
+};
+
+template <int D, int G>
+struct PromptAttnCfg {
+  static constexpr int QB = G >= 5 ? 1 : 8 / G;  // 32-row query sub-blocks per workgroup
+  static constexpr int NWV = G * QB, NT = NWV * 64, BM = 32 * QB;
+  static constexpr int BN = 64;                  // keys per tile
+  static constexpr int KS = D / 16, DB = D / 32, C8 = D / 8;
+  static constexpr int KROW = D + 8;             // bf16 per K row in LDS: 16-byte reads of 16 rows hit 64 distinct banks
+  static constexpr int VROW = BN + 8;            // bf16 per V^T row in LDS: same property for its reads
+  static constexpr int K_ITEMS = BN * C8;        // 16-byte pieces of a K tile
+  static constexpr int V_ITEMS = (BN / 2) * C8;  // (key pair, 8 channels) pieces of a V tile
+  static constexpr int KI = (K_ITEMS + NT - 1) / NT, VI = (V_ITEMS + NT - 1) / NT;
+  static constexpr size_t lds_bytes = (size_t)2 * (BN * KROW + D * VROW) * 2;
+};
+
+// Key slot order inside a V^T row: the two index bits that the result layout of the first product splits
+// between register and lane half (bits 2 and 3) trade places, so that the 8 keys one lane holds
+// exponentials for are 16 contiguous bytes of the row.
+__device__ __forceinline__ int pa_slot(int key) { return (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1); }
+
+template <int D, int G>
+__global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(PromptAttnParams P) {
+  using Cf = PromptAttnCfg<D, G>;
+  constexpr int NT = Cf::NT, BM = Cf::BM, BN = Cf::BN, KS = Cf::KS, DB = Cf::DB, C8 = Cf::C8;
+  constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI, VI = Cf::VI;
+  extern __shared__ __align__(16) unsigned char pa_smem[];
+  bf16_t *Ks = (bf16_t *)pa_smem;        // [2][BN][KROW]
+  bf16_t *Vt = Ks + 2 * BN * KROW;       // [2][D][VROW], key slots permuted by pa_slot
+
+  const int tid = threadIdx.x, wave = tid / WAVE, lane = tid % WAVE, h = lane / 32, col = lane % 32;
+  const int u = blockIdx.y, lb = u / P.Mkv, kh = u % P.Mkv, b = lb % P.B;
+  const int N = P.plen[b];
+  // long rows first: the last workgroups to start are the short ones
+  const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * BM;
+  if (q0 >= N) return;
+  const int g = wave % G, qs = q0 + (wave / G) * 32;
+  const bool wave_on = qs < N;
+  const int query = qs + col;
+  const int qm = min(query, N - 1);        // rows past the prompt repeat the last row and are never stored
+  const int q_lo = min(qs, N - 1), q_hi = min(qs + 31, N - 1);
+  const int ntile = (min(q0 + BM, N) - 1) / BN + 1;
+  const bf16_t *Kb = P.K + (size_t)u * P.Nmax * D, *Vb = P.V + (size_t)u * P.Nmax * D;
+  const size_t head = (size_t)lb * P.Mq + (size_t)kh * G + g;
+
+  // the wave's queries as B fragments: lane (h, col) holds channels 16s + 8h .. +8 of row qs + col
+  pa_bf16x8 qf[KS];
+  {
+    const bf16_t *qrow = P.Q + (head * P.Nmax + qm) * D;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(pa_bf16x8, *(const uint4 *)(qrow + 16 * s + 8 * h));
+  }
+
+  pa_f32x16 Oacc[DB];
+#pragma unroll
+  for (int blk = 0; blk < DB; ++blk)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Oacc[blk][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;  // log2 domain; l_run is this lane's share of the row sum
+
+  // Trip t works on tile t out of LDS buffer t & 1 while tile t + 1 travels global -> registers (issued before
+  // the arithmetic) -> the other buffer (after it); trip -1 only stages tile 0.
+  for (int t = -1; t < ntile; ++t) {
+    const int buf = t & 1, kb = t * BN;
+    const bool more = t + 1 < ntile;
+    uint4 kr[KI], va[VI], vb[VI];
+    if (more) {
+      const int kn = kb + BN;
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int e = tid + i * NT;
+        kr[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS) {
+          const int row = min(kn + e / C8, N - 1);  // rows past the prompt are masked below
+          kr[i] = *(const uint4 *)(Kb + (size_t)row * D + (e % C8) * 8);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < VI; ++i) {
+        const int e = tid + i * NT;
+        // a value row past the prompt is taken as zero: a zero weight must not meet a NaN
+        va[i] = make_uint4(0u, 0u, 0u, 0u);
+        vb[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (Cf::V_ITEMS % NT == 0 || e < Cf::V_ITEMS) {
+          // a wave takes 4 neighbouring pieces (64 bytes) of 16 key pairs
+          const int c = (e / 128) * 4 + (e % 4), k0 = kn + 2 * ((e / 4) % 32);
+          if (k0 < N) va[i] = *(const uint4 *)(Vb + (size_t)k0 * D + c * 8);
+          if (k0 + 1 < N) vb[i] = *(const uint4 *)(Vb + (size_t)(k0 + 1) * D + c * 8);
+        }
+      }
+    }
+    if (t >= 0 && wave_on && kb <= q_hi) {
+      pa_f32x16 s[2];
+#pragma unroll
+      for (int hk = 0; hk < 2; ++hk)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[hk][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int hk = 0; hk < 2; ++hk) {
+          const pa_bf16x8 a = __builtin_bit_cast(
+              pa_bf16x8, *(const uint4 *)(Ks + (buf * BN + 32 * hk + col) * KROW + 16 * ks + 8 * h));
+          s[hk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[hk], 0, 0, 0);
+        }
+      // register v of lane (h, col): key kb + 32 hk + 8 (v / 4) + 4 h + v % 4, query qs + col
+      if (kb + BN - 1 > q_lo) {
+#pragma unroll
+        for (int hk = 0; hk < 2; ++hk)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = kb + 32 * hk + 8 * (v / 4) + 4 * h + (v % 4);
+            s[hk][v] = key <= qm ? s[hk][v] : -INFINITY;
+          }
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int hk = 0; hk < 2; ++hk)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[hk][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx * P.scale_log2);  // finite from the first tile on: key 0 is visible to every row
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      float lsum = 0.f;
+#pragma unroll
+      for (int hk = 0; hk < 2; ++hk)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s[hk][v] = __builtin_amdgcn_exp2f(fmaf(s[hk][v], P.scale_log2, -m_new));
+          lsum += s[hk][v];
+        }
+      l_run = l_run * alpha + lsum;
+      m_run = m_new;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int blk = 0; blk < DB; ++blk)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) Oacc[blk][v] *= alpha;
+      }
+#pragma unroll
+      for (int hk = 0; hk < 2; ++hk)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          pa_bf16x8 pf;
+#pragma unroll
+          for (int j = 0; j < 8; j += 2) {
+            const pa_f32x2 two = {s[hk][8 * m + j], s[hk][8 * m + j + 1]};
+            const pa_bf16x2 r = __builtin_convertvector(two, pa_bf16x2);
+            pf[j] = r[0];
+            pf[j + 1] = r[1];
+          }
+#pragma unroll
+          for (int blk = 0; blk < DB; ++blk) {
+            const pa_bf16x8 a = __builtin_bit_cast(
+                pa_bf16x8, *(const uint4 *)(Vt + (buf * D + 32 * blk + col) * VROW + 32 * hk + 16 * m + 8 * h));
+            Oacc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, Oacc[blk], 0, 0, 0);
+          }
+        }
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int e = tid + i * NT;
+        if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS)
+          *(uint4 *)(Ks + ((buf ^ 1) * BN + e / C8) * KROW + (e % C8) * 8) = kr[i];
+      }
+#pragma unroll
+      for (int i = 0; i < VI; ++i) {
+        const int e = tid + i * NT;
+        if (Cf::V_ITEMS % NT == 0 || e < Cf::V_ITEMS) {
+          const int c = (e / 128) * 4 + (e % 4), kl = 2 * ((e / 4) % 32);
+          bf16_t *dst = Vt + ((buf ^ 1) * D + c * 8) * VROW + pa_slot(kl);
+          // channel by channel: key kl in the low half of the word, key kl + 1 in the high half
+          *(uint32_t *)(dst + 0 * VROW) = (va[i].x & 0xffffu) | (vb[i].x << 16);
+          *(uint32_t *)(dst + 1 * VROW) = (va[i].x >> 16) | (vb[i].x & 0xffff0000u);
+          *(uint32_t *)(dst + 2 * VROW) = (va[i].y & 0xffffu) | (vb[i].y << 16);
+          *(uint32_t *)(dst + 3 * VROW) = (va[i].y >> 16) | (vb[i].y & 0xffff0000u);
+          *(uint32_t *)(dst + 4 * VROW) = (va[i].z & 0xffffu) | (vb[i].z << 16);
+          *(uint32_t *)(dst + 5 * VROW) = (va[i].z >> 16) | (vb[i].z & 0xffff0000u);
+          *(uint32_t *)(dst + 6 * VROW) = (va[i].w & 0xffffu) | (vb[i].w << 16);
+          *(uint32_t *)(dst + 7 * VROW) = (va[i].w >> 16) | (vb[i].w & 0xffff0000u);
+        }
+      }
+    }
+    __syncthreads();  // the next tile is in place, and every read of this one is done before it is overwritten
+  }
+
+  if (!wave_on) return;
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (query >= N) return;
+  const float inv = 1.0f / l_tot;
+  bf16_t *orow = P.O + (head * P.Nmax + query) * D;
+#pragma unroll
+  for (int blk = 0; blk < DB; ++blk)
+#pragma unroll
+    for (int b4 = 0; b4 < 4; ++b4) {
+      // registers 4 b4 .. +4 are channels 32 blk + 8 b4 + 4 h .. +4 of this lane's row
+      const pa_f32x2 lo = {Oacc[blk][4 * b4] * inv, Oacc[blk][4 * b4 + 1] * inv};
+      const pa_f32x2 hi = {Oacc[blk][4 * b4 + 2] * inv, Oacc[blk][4 * b4 + 3] * inv};
+      uint2 w;
+      w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, pa_bf16x2));
+      w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, pa_bf16x2));
+      *(uint2 *)(orow + 32 * blk + 8 * b4 + 4 * h) = w;
+    }
+  if (h == 0) {
+    const float lse = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;  // log2 domain -> natural log
+    if (P.lse) P.lse[head * P.Nmax + query] = lse;
+    const int Rw = min(P.R, N), j = query - (N - Rw);
+    if (j >= 0) P.lse_w[head * P.R + j] = lse;
+  }
+}
+
+}  // namespace mkv

@@ -30,6 +30,7 @@ _C2 = 0x94D049BB133111EB
 
 # tensor ids (upper bits of the stream number)
 T_PROMPT_K, T_PROMPT_V, T_PROMPT_Q, T_DEC_Q, T_DEC_K, T_DEC_V, T_LEN, T_OUTLIER = range(1, 9)
+T_PROMPT_QALL = 9
 
 
 def _s64(x: int) -> int:
@@ -170,6 +171,24 @@ class Workload:
                 K[l, i] = (self._slab(T_PROMPT_K, l, b, Mk, Nm, device) * ksc[l, 0]).to(dt)
                 V[l, i] = self._slab(T_PROMPT_V, l, b, Mk, Nm, device).to(dt)
         return Q, K, V
+
+    def prompt_queries(self, device="cpu", batch_index: Optional[List[int]] = None) -> torch.Tensor:
+        """Queries of every prompt position, [L,B,M,Nmax,d] in the workload dtype, ~N(0,1).
+
+        The last min(R, N_b) rows before N_b are the rows of prompt()'s Q_window, so that a pass over the whole
+        prompt and the window-only entry see the same window queries; rows at or beyond N_b are padding.
+        """
+        bs = list(range(self.batch)) if batch_index is None else list(batch_index)
+        L, Mq, d, Nm, R = self.n_layers, self.n_q_heads, self.head_dim, self.Nmax, self.R
+        dt = self.torch_dtype
+        Q = torch.empty(L, len(bs), Mq, Nm, d, dtype=dt, device=device)
+        for l in range(L):
+            for i, b in enumerate(bs):
+                Q[l, i] = self._slab(T_PROMPT_QALL, l, b, Mq, Nm, device).to(dt)
+                N = self.prompt_lens[b]
+                Rw = min(R, N)
+                Q[l, i, :, N - Rw:N] = self._slab(T_PROMPT_Q, l, b, Mq, R, device).to(dt)[:, :Rw]
+        return Q
 
     def decode_inputs(self, step: int, device="cpu", batch_index: Optional[List[int]] = None):
         """(q [L,B,M,d], k_new [L,B,M',d], v_new [L,B,M',d]) of decode step ``step`` (0-based)."""

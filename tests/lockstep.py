@@ -85,7 +85,7 @@ def window_lse(wl, Qw, K):
 
 class LockStep:
     def __init__(self, wl, device="cuda:0", batch_index: Optional[List[int]] = None, gen_device=None,
-                 capture_scores=False, per_layer=False, use_lse=False):
+                 capture_scores=False, per_layer=False, use_lse=False, use_attend=False):
         self.wl = wl
         self.device = device
         self.bidx = list(range(wl.batch)) if batch_index is None else list(batch_index)
@@ -99,6 +99,8 @@ class LockStep:
         self.scoreF = self.gpu.capture_scores(True) if capture_scores else None
         self.t = 0
         self.use_lse = use_lse       # prefill through the variant that takes the rows' log-sum-exp from the caller
+        self.use_attend = use_attend  # prefill through the entry that also runs the prompt's attention pass
+        self.attn_out = None          # (Q, O, lse) of that pass, for the caller to check
         self.per_layer = per_layer   # one call per layer (reverse order, to show the calls are independent)
 
     # ---- prefill --------------------------------------------------------
@@ -107,7 +109,14 @@ class LockStep:
         Qw, K, V = wl.prompt(self.gen_device)
         plen = wl.prompt_len_tensor().numpy()
         lse = window_lse(wl, Qw, K).to(self.device) if self.use_lse else None
-        self.gpu.prefill_select(Qw.to(self.device), K.to(self.device), V.to(self.device), plen, lse_window=lse)
+        if self.use_attend:
+            Q = wl.prompt_queries(self.gen_device).to(self.device)
+            lse_all = torch.full(Q.shape[:-1], float("nan"), dtype=torch.float32, device=self.device)
+            O = torch.full_like(Q, float("nan"))
+            self.gpu.prefill_attend_select(Q, K.to(self.device), V.to(self.device), plen, O=O, lse=lse_all)
+            self.attn_out = (Q, O, lse_all)
+        else:
+            self.gpu.prefill_select(Qw.to(self.device), K.to(self.device), V.to(self.device), plen, lse_window=lse)
         ix = torch.tensor(self.bidx, device=Qw.device)
         Qo, Ko, Vo = (t.index_select(1, ix).cpu().contiguous() for t in (Qw, K, V))
         del Qw, K, V

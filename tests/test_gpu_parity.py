@@ -4,7 +4,10 @@ Bars (written here as the tests enforce them):
   * retained positions: bit-exact, except near-ties at the top-C boundary (< 1e-5 relative in the
     oracle's scores), which are adopted and counted;
   * attention output: max abs error <= 2e-3 for bf16 inputs (fp32 accumulation), <= 1e-5 for fp32;
-  * fused scores (where captured): relative error <= 1e-5 against the oracle's fp64 scores.
+  * fused scores (where captured): relative error <= 1e-5 against the oracle's fp64 scores;
+  * prompt attention output (bf16, weights rounded to bf16 before they meet V): |O - O_ref| <= 2^-8 max|V| per
+    sequence (2^-9 relative from the rounding of each weight, 2^-9 of |O| <= max|V| from the rounding of the
+    result), and rms error <= 2^-9 rms(O_ref) + 1e-3; log-sum-exp: <= 1e-5 + 1e-6 |lse|.
 """
 import numpy as np
 import pytest
@@ -251,6 +254,154 @@ def test_c5_sampled_units_full_size(oracle_lib):
     ls = _lockstep(wl, DEV, batch_index=[17], gen_device=DEV).prefill()
     rep = ls.run(64, check_every=32)
     _report("c5", rep)
+
+
+# ---- the prompt's attention pass fused with the selection over the prompt
+def _check_attention(wl, attn_out, bidx=None, rows=None):
+    """O and lse of the pass against the dense fp64 definition, sequence by sequence (all rows, or sampled rows of
+    sampled heads when the prompt is long)."""
+    from oracle.prompt_attn_ref import prompt_attention
+    Q, O, lse = attn_out
+    bs = range(wl.batch) if bidx is None else bidx
+    worst = (0.0, 0.0)
+    for l in range(wl.n_layers):
+        for b in bs:
+            N = wl.prompt_lens[b]
+            q, o, ls_ = Q[l, b], O[l, b], lse[l, b]
+            assert torch.isnan(o[:, N:].float()).all() and torch.isnan(ls_[:, N:]).all(), "rows beyond the prompt were written"
+            Kb, Vb = wl_kv(wl, l, b)
+            Oref, lref = prompt_attention(q.float().cpu().numpy(), Kb, Vb, N)
+            got = o[:, :N].float().cpu().numpy().astype(np.float64)
+            assert np.isfinite(got).all()
+            vmax = np.abs(Vb[:, :N]).max()
+            err = np.abs(got - Oref)
+            assert err.max() <= 2.0 ** -8 * vmax, f"O off by {err.max():.3e} (bound {2.0 ** -8 * vmax:.3e}) l={l} b={b}"
+            rms = np.sqrt((err ** 2).mean())
+            assert rms <= 2.0 ** -9 * np.sqrt((Oref ** 2).mean()) + 1e-3, f"O rms error {rms:.3e}"
+            lerr = np.abs(ls_[:, :N].cpu().numpy().astype(np.float64) - lref)
+            assert (lerr <= 1e-5 + 1e-6 * np.abs(lref)).all(), f"lse off by {lerr.max():.3e}"
+            worst = (max(worst[0], err.max()), max(worst[1], lerr.max()))
+    return worst
+
+
+def wl_kv(wl, l, b):
+    _, K, V = wl.prompt("cpu", batch_index=[b])
+    return K[l, 0].float().numpy(), V[l, 0].float().numpy()
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("G", range(1, 9))
+def test_prompt_attention_every_instantiation(d, G, oracle_lib):
+    """prefill_attend_select for every (head dimension, group size) build: O and lse of the whole prompt against the
+    dense fp64 definition; the selection it leaves behind and the decode steps after it against the oracle in
+    lock-step.  Ragged prompts: one token, below one tile, not a multiple of the 32-row and 64-key tiles, several
+    tiles."""
+    Mkv = 2 if G <= 4 else 1
+    wl = inputs.small_workload(31000 + 10 * d + G, L=1, B=4, M=G * Mkv, Mkv=Mkv, d=d, dtype="bf16", C=40, R=12,
+                               fusion="sum" if G & 1 else "max", prompt_lens=(1, 45, 333, 200), steps=12)
+    ls = _lockstep(wl, DEV, use_attend=True, capture_scores=True).prefill()
+    worst = _check_attention(wl, ls.attn_out)
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"attend_d{d}_g{G} O_err={worst[0]:.2e} lse_err={worst[1]:.1e}", rep)
+    assert rep.max_score_rel_err <= 1e-5
+
+
+ATTEND = [
+    ("layers_ragged", dict(L=2, B=3, M=8, Mkv=2, d=128, dtype="bf16", C=64, R=24, fusion="sum", prompt_lens=(700, 20, 300), steps=20)),
+    ("g7_long", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(1100, 150), steps=20)),
+    ("outliers_T4", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=48, R=16, fusion="sum", prompt_lens=(513, 64), steps=24,
+                         n_outlier_channels=3, evict_every=4)),
+    ("window_longer_than_prompt", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=10, R=40, fusion="sum", prompt_lens=(17, 90), steps=50)),
+]
+
+
+@pytest.mark.parametrize("case", ATTEND, ids=[c[0] for c in ATTEND])
+def test_prompt_attention_then_decode(case, oracle_lib):
+    name, kw = case
+    wl = inputs.small_workload(32000 + ATTEND.index(case), **kw)
+    ls = _lockstep(wl, DEV, use_attend=True, capture_scores=wl.evict_every == 1).prefill()
+    worst = _check_attention(wl, ls.attn_out)
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"attend_{name} O_err={worst[0]:.2e} lse_err={worst[1]:.1e}", rep)
+
+
+def test_prompt_attention_same_state_as_window_entry():
+    """The state left by prefill_attend_select is bit for bit the state prefill_select_lse leaves when it is given
+    the same window queries and the attention pass's own log-sum-exp."""
+    from paper_2503_00979_amd import binding
+    wl = inputs.small_workload(33000, L=2, B=3, M=8, Mkv=2, d=128, dtype="bf16", C=64, R=24, fusion="sum",
+                               prompt_lens=(700, 20, 300), steps=4)
+    Qw, K, V = (t.to(DEV) for t in wl.prompt())
+    Q = wl.prompt_queries(DEV)
+    plen = wl.prompt_len_tensor().numpy()
+    a = binding.MorphKV.from_workload(wl, DEV)
+    lse = torch.zeros(Q.shape[:-1], dtype=torch.float32, device=DEV)
+    a.prefill_attend_select(Q, K, V, plen, lse=lse)
+    lse_w = torch.zeros(wl.n_layers, wl.batch, wl.n_q_heads, wl.R, dtype=torch.float32, device=DEV)
+    for b, N in enumerate(wl.prompt_lens):
+        Rw = min(wl.R, N)
+        lse_w[:, b, :, :Rw] = lse[:, b, :, N - Rw:N]
+    bb = binding.MorphKV.from_workload(wl, DEV)
+    bb.prefill_select(Qw, K, V, plen, lse_window=lse_w)
+    pa, na = a.export_positions()
+    pb, nb = bb.export_positions()
+    assert torch.equal(pa, pb) and torch.equal(na, nb)
+    for t in range(wl.steps):
+        q, k, v = (x.to(DEV) for x in wl.decode_inputs(t))
+        assert torch.equal(a.decode_step(q, k, v), bb.decode_step(q, k, v))
+        assert torch.equal(a.export_evicted(), bb.export_evicted())
+
+
+def test_prompt_attention_full_size_sampled():
+    """At the sizes the benchmark times (c5: G=7, 16k prompts; c3: ragged 1k-8k prompts): sampled rows of sampled
+    heads of O and lse against the dense definition evaluated for those rows only."""
+    from paper_2503_00979_amd import binding
+    for name, bsel in (("c5", [17, 40]), ("c3", [3, 11, 30])):
+        wl_full = inputs.workload(name)
+        wl = wl_full.with_batch_subset(bsel)
+        g = binding.MorphKV.from_workload(wl, DEV)
+        _, K, V = wl_full.prompt(DEV, batch_index=bsel)
+        Q = wl_full.prompt_queries(DEV, batch_index=bsel)
+        K, V, Q = (t[:, :, :, :wl.Nmax].contiguous() for t in (K, V, Q))   # the subset's own padded length
+        O = torch.full_like(Q, float("nan"))
+        lse = torch.full(Q.shape[:-1], float("nan"), dtype=torch.float32, device=DEV)
+        g.prefill_attend_select(Q, K, V, wl.prompt_len_tensor().numpy(), O=O, lse=lse)
+        G, d = wl.G, wl.head_dim
+        rng = np.random.default_rng(5)
+        for b, N in enumerate(wl.prompt_lens):
+            assert torch.isnan(O[0, b, :, N:].float()).all()
+            rows = sorted({0, 1, 31, 32, 63, 64, N - 1, N - 2, *rng.integers(0, N, 24).tolist()})
+            for h in rng.choice(wl.n_q_heads, 3, replace=False):
+                Kh = K[0, b, h // G, :N].double()
+                Vh = V[0, b, h // G, :N].double()
+                for i in rows:
+                    l = (Kh[:i + 1] @ Q[0, b, h, i].double()) / d ** 0.5
+                    ref_lse = torch.logsumexp(l, 0)
+                    ref = torch.softmax(l, 0) @ Vh[:i + 1]
+                    err = (O[0, b, h, i].double() - ref).abs().max().item()
+                    assert err <= 2.0 ** -8 * Vh.abs().max().item(), f"{name} b={b} h={h} row {i}: O off by {err:.3e}"
+                    lerr = abs(lse[0, b, h, i].item() - ref_lse.item())
+                    assert lerr <= 1e-5 + 1e-6 * abs(ref_lse.item()), f"{name} b={b} h={h} row {i}: lse off by {lerr:.3e}"
+        del g, K, V, Q, O, lse
+        torch.cuda.empty_cache()
+
+
+def test_prompt_attention_error_paths():
+    from paper_2503_00979_amd import binding
+    wl = inputs.small_workload(7, L=1, B=1, M=2, Mkv=1, d=64, dtype="f32", C=4, R=2, prompt_lens=(8,), steps=1)
+    g = binding.MorphKV.from_workload(wl, DEV)
+    Q = wl.prompt_queries(DEV)
+    _, K, V = (t.to(DEV) for t in wl.prompt())
+    with pytest.raises(binding.MorphKVError) as e:
+        g.prefill_attend_select(Q, K, V, [8])
+    assert e.value.code == binding.EINVAL and "bf16" in str(e.value)
+    wl = inputs.small_workload(7, L=1, B=1, M=2, Mkv=1, d=64, dtype="bf16", C=4, R=2, prompt_lens=(8,), steps=1)
+    g = binding.MorphKV.from_workload(wl, DEV)
+    Q = wl.prompt_queries(DEV)
+    _, K, V = (t.to(DEV) for t in wl.prompt())
+    with pytest.raises(binding.MorphKVError) as e:
+        g.prefill_attend_select(Q, K, V, [9])
+    assert e.value.code == binding.EINVAL
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
