@@ -101,8 +101,9 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
         const int e = tid + i * NT;
         kr[i] = make_uint4(0u, 0u, 0u, 0u);
         if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS) {
-          const int row = min(kn + e / C8, N - 1);  // rows past the prompt are masked below
-          kr[i] = *(const uint4 *)(Kb + (size_t)row * D + (e % C8) * 8);
+          // (32-bit offsets from the unit's base: a thread keeps no 64-bit address per piece)
+          const uint32_t row = (uint32_t)min(kn + e / C8, N - 1);  // rows past the prompt are masked below
+          kr[i] = *(const uint4 *)(Kb + (row * (uint32_t)D + (uint32_t)(e % C8) * 8u));
         }
       }
 #pragma unroll
@@ -114,8 +115,9 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
         if (Cf::V_ITEMS % NT == 0 || e < Cf::V_ITEMS) {
           // a wave takes 4 neighbouring pieces (64 bytes) of 16 key pairs
           const int c = (e / 128) * 4 + (e % 4), k0 = kn + 2 * ((e / 4) % 32);
-          if (k0 < N) va[i] = *(const uint4 *)(Vb + (size_t)k0 * D + c * 8);
-          if (k0 + 1 < N) vb[i] = *(const uint4 *)(Vb + (size_t)(k0 + 1) * D + c * 8);
+          const uint32_t off = (uint32_t)k0 * (uint32_t)D + (uint32_t)c * 8u;
+          if (k0 < N) va[i] = *(const uint4 *)(Vb + off);
+          if (k0 + 1 < N) vb[i] = *(const uint4 *)(Vb + (off + (uint32_t)D));
         }
       }
     }
@@ -143,23 +145,29 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
             s[hk][v] = key <= qm ? s[hk][v] : -INFINITY;
           }
       }
-      float mx = -INFINITY;
+      // (four partial maxima and sums: short dependency chains)
+      float mx4[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
       for (int hk = 0; hk < 2; ++hk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[hk][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * P.scale_log2);  // finite from the first tile on: key 0 is visible to every row
+        for (int v = 0; v < 16; ++v) mx4[v & 3] = fmaxf(mx4[v & 3], s[hk][v]);
+      float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * P.scale_log2;
+      // The reference only moves when the row's maximum has outgrown it by 2^8 (any reference gives the same
+      // quotient; the exponentials stay below 2^8, far from any overflow): the accumulators are rescaled a
+      // few times per row instead of at every new maximum.  Finite from the first tile on: key 0 is visible
+      // to every row.
+      const float m_new = mx > m_run + 8.0f ? mx : m_run;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      float lsum = 0.f;
+      float ls4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int hk = 0; hk < 2; ++hk)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           s[hk][v] = __builtin_amdgcn_exp2f(fmaf(s[hk][v], P.scale_log2, -m_new));
-          lsum += s[hk][v];
+          ls4[v & 3] += s[hk][v];
         }
-      l_run = l_run * alpha + lsum;
+      l_run = l_run * alpha + ((ls4[0] + ls4[1]) + (ls4[2] + ls4[3]));
       m_run = m_new;
       if (__any(alpha != 1.0f)) {
 #pragma unroll
