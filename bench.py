@@ -102,6 +102,9 @@ def main():
                          "median is reported as prefill_select_ms")
     ap.add_argument("--prefill-lse", action="store_true",
                     help="also time prefill_select_lse (window rows' log-sum-exp supplied by the caller)")
+    ap.add_argument("--prefill-attend", action="store_true",
+                    help="also time prefill_attend_select (causal attention over the whole prompt + selection; bf16 "
+                         "workloads) and report it against the bf16 matrix-core peak")
     ap.add_argument("--no-stream-ref", action="store_true",
                     help="skip the plain streaming-read measurement reported as roofline.stream_read_GBs")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -165,6 +168,28 @@ def main():
             pfl.append(e0.elapsed_time(e1))
         prefill_lse_ms = sorted(pfl)[len(pfl) // 2]
         del lse
+    attend = None
+    if args.prefill_attend:
+        Qall = wl.prompt_queries(dev)
+        Oall = torch.empty_like(Qall)
+        pa = []
+        for _ in range(max(1, args.prefill_repeats)):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.prefill_attend_select(Qall, K, V, wl.prompt_len_tensor().numpy(), O=Oall)
+            e1.record()
+            torch.cuda.synchronize()
+            pa.append(e0.elapsed_time(e1))
+        ms = sorted(pa)[len(pa) // 2]
+        # 2 d flop per (query, key <= query) pair and head for each of the two products
+        flop = sum(4.0 * wl.head_dim * (n * (n + 1) / 2) for n in wl.prompt_lens) * wl.n_q_heads * wl.n_layers
+        attend = {"prefill_attend_select_ms": ms, "flop": flop,
+                  "whole_call": {"bound": "mfma", "achieved": flop / (ms / 1e3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                                 "frac": flop / (ms / 1e3) / 1e12 / 2500.0},
+                  "note": "achieved = attention flop / time of the whole call (attention pass + selection passes)"}
+        del Qall, Oall
+        g.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())   # back to the state every other run starts from
     fill_steps = max(0, max(wl.C + wl.R - n for n in wl.prompt_lens))
     step_no = 0
     out = torch.empty(g.out_shape, dtype=torch.float32, device=dev)
@@ -296,6 +321,7 @@ def main():
                    "wall_ms_per_step": wall_s / K_steps * 1e3, "prefill_select_ms": prefill_ms,
                    "prefill_select_first_call_ms": pf[0],
                    **({"prefill_select_lse_ms": prefill_lse_ms} if prefill_lse_ms is not None else {}),
+                   **({"prompt_attention": attend} if attend is not None else {}),
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.per_layer or wl.evict_every > 1) else read_traffic(wl.name),
