@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
   // row (one query, consecutive channel groups) then fall into different banks, as the reads do anyway
   constexpr int QROW = 17;
   __shared__ uint4 qs[2][G * KB * 4 * QROW];
-  __shared__ float2 sts[2][ST ? 1 : G * 16];           // (max, 1/sum) of (head, query) for the weights
+  __shared__ float2 sts[2][ST ? 1 : G * 16];           // .x = log2-sum-exp of (head, query), what a weight's exponent is taken against
   __shared__ float2 wst[ST ? 4 : 1][ST ? G : 1][ST ? JC * 16 : 1];
   const int blk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x;
   const int wave = tid / WAVE, lane = tid % WAVE, col = lane & 15, kq = lane >> 4;
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
     if constexpr (!ST) {
       if (tid < G * 16) {
         const int g = tid >> 4, j = jt * 16 + (tid & 15);
-        sst = j < Rw ? stu[g * R16 + j] : make_float2(0.f, 0.f);
+        sst = j < Rw ? stu[g * R16 + j] : make_float2(INFINITY, 0.f);
       }
     }
   };
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
       __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
     }
   };
-  // st = (max, 1/sum) of (head g, query j) for the weights; (0, 0): no such query
+  // st.x = log2-sum-exp of (head g, query j); +inf: no such query
   auto valu = [&](int jt, int g, float2 st, f32x4_t (&acc)[KT]) {
     const int j = jt * 16 + col;
     const int pj = j < Rw ? N - Rw + j : -1;  // causal: query j sees keys 0..pj
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
         [[maybe_unused]] const int kpp[4] = {kp[t].x, kp[t].y, kp[t].z, kp[t].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float e = __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -st.x)) * st.y;
+          float e = __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -st.x));  // st.x = +inf: no such query, weight 0
           if constexpr (MODE == PF_RING) e = (kpp[i] >= 0 && kpp[i] <= pj) ? e : 0.f;
           S[t][i] += e;
         }
@@ -477,8 +477,9 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
   }
 }
 
-// merges the per-block statistics of a unit: Sfin[g][j] = (max, 1 / sum of exp2(logit - max)) over the
-// whole causal row of query j, (0, 0) for queries that do not exist
+// merges the per-block statistics of a unit: Sfin[g][j].x = max + log2(sum of exp2(logit - max)) over the
+// whole causal row of query j (the row's log-sum-exp, base 2), +inf for queries that do not exist: a weight is
+// exp2(logit - .x), one fma and one exp2, no multiplication by 1/sum
 template <int G>
 __global__ __launch_bounds__(64) void prefill_stats_merge_kernel(PrefillParams P, int nblk) {
   const int u = blockIdx.x, g = blockIdx.y, j = blockIdx.z * 64 + threadIdx.x;
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(64) void prefill_stats_merge_kernel(PrefillParams P
       m = mn;
     }
   }
-  P.Sfin[(size_t)u * G * R16 + idx] = z > 0.f ? make_float2(m, 1.0f / z) : make_float2(0.f, 0.f);
+  P.Sfin[(size_t)u * G * R16 + idx] = z > 0.f ? make_float2(m + log2f(z), 1.0f) : make_float2(INFINITY, 0.f);
 }
 
 // the same from the caller's log-sum-exp of the window rows (natural log, as attention kernels return it):
@@ -506,7 +507,7 @@ __global__ __launch_bounds__(64) void prefill_stats_from_lse_kernel(PrefillParam
   const int b = (u / P.Mkv) % P.B;
   const int N = P.plen[b], R = P.R, Rw = N < R ? N : R, R16 = (R + 15) & ~15;
   if (j >= R16) return;
-  float2 st = make_float2(0.f, 0.f);
+  float2 st = make_float2(INFINITY, 0.f);
   if (j < Rw) st = make_float2(P.lse[((size_t)u * G + g) * R + j] * 1.4426950408889634f, 1.0f);
   P.Sfin[((size_t)u * G + g) * R16 + j] = st;
 }
