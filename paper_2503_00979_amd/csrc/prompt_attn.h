@@ -7,7 +7,7 @@
 // query heads that share one KV head: every K/V tile staged in LDS is used by all of them.  A wave owns 32
 // rows of one head and keeps, per lane, ONE query column of the transposed problem
 //     S^T[key][query] = K Q^T          (A = keys from LDS, B = the wave's query fragments, in registers)
-//     O^T[dv][query] += V^T P^T        (A = transposed values from LDS, B = the exponentials just computed)
+//     O^T[dv][query] += V^T P^T        (A = values from LDS through the transposing read, B = the exponentials)
 // so the results of the first product are, as they lie in registers, the B operand of the second, and the row
 // statistics (running maximum, running sum) are per-lane scalars shared by the two lanes l and l+32.
 #pragma once
@@ -19,6 +19,9 @@ typedef __bf16 pa_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 pa_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float pa_f32x16 __attribute__((ext_vector_type(16)));
 typedef float pa_f32x2 __attribute__((ext_vector_type(2)));
+typedef short pa_s16x4 __attribute__((ext_vector_type(4)));
+typedef short pa_s16x8 __attribute__((ext_vector_type(8)));
+typedef pa_s16x4 __attribute__((address_space(3))) pa_lds_s16x4;
 
 struct PromptAttnParams {
   const bf16_t *Q, *K, *V;  // [L][B][M][Nmax][D], [L][B][M'][Nmax][D] x2
@@ -37,26 +40,22 @@ struct PromptAttnCfg {
   static constexpr int BN = 64;                  // keys per tile
   static constexpr int KS = D / 16, DB = D / 32, C8 = D / 8;
   static constexpr int KROW = D + 8;             // bf16 per K row in LDS: 16-byte reads of 16 rows hit 64 distinct banks
-  static constexpr int VROW = BN + 8;            // bf16 per V^T row in LDS: same property for its reads
-  static constexpr int K_ITEMS = BN * C8;        // 16-byte pieces of a K tile
-  static constexpr int V_ITEMS = (BN / 2) * C8;  // (key pair, 8 channels) pieces of a V tile
-  static constexpr int KI = (K_ITEMS + NT - 1) / NT, VI = (V_ITEMS + NT - 1) / NT;
-  static constexpr size_t lds_bytes = (size_t)2 * (BN * KROW + D * VROW) * 2;
+  static constexpr int VROW = D + 32;            // bf16 per V row in LDS: 4 consecutive rows start 16 banks apart, so
+                                                 // the 4-key x 16-channel blocks of a transposing read (two per
+                                                 // 32 lanes) cover all 64 banks
+  static constexpr int K_ITEMS = BN * C8;        // 16-byte pieces of a K tile, and of a V tile
+  static constexpr int KI = (K_ITEMS + NT - 1) / NT;
+  static constexpr size_t lds_bytes = (size_t)2 * BN * (KROW + VROW) * 2;
 };
-
-// Key slot order inside a V^T row: the two index bits that the result layout of the first product splits
-// between register and lane half (bits 2 and 3) trade places, so that the 8 keys one lane holds
-// exponentials for are 16 contiguous bytes of the row.
-__device__ __forceinline__ int pa_slot(int key) { return (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1); }
 
 template <int D, int G>
 __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(PromptAttnParams P) {
   using Cf = PromptAttnCfg<D, G>;
   constexpr int NT = Cf::NT, BM = Cf::BM, BN = Cf::BN, KS = Cf::KS, DB = Cf::DB, C8 = Cf::C8;
-  constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI, VI = Cf::VI;
+  constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI;
   extern __shared__ __align__(16) unsigned char pa_smem[];
   bf16_t *Ks = (bf16_t *)pa_smem;        // [2][BN][KROW]
-  bf16_t *Vt = Ks + 2 * BN * KROW;       // [2][D][VROW], key slots permuted by pa_slot
+  bf16_t *Vs = Ks + 2 * BN * KROW;       // [2][BN][VROW], row-major like K
 
   const int tid = threadIdx.x, wave = tid / WAVE, lane = tid % WAVE, h = lane / 32, col = lane % 32;
   const int u = blockIdx.y, lb = u / P.Mkv, kh = u % P.Mkv, b = lb % P.B;
@@ -93,7 +92,7 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
   for (int t = -1; t < ntile; ++t) {
     const int buf = t & 1, kb = t * BN;
     const bool more = t + 1 < ntile;
-    uint4 kr[KI], va[VI], vb[VI];
+    uint4 kr[KI], vr[KI];
     if (more) {
       const int kn = kb + BN;
 #pragma unroll
@@ -104,20 +103,9 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
           // (32-bit offsets from the unit's base: a thread keeps no 64-bit address per piece)
           const uint32_t row = (uint32_t)min(kn + e / C8, N - 1);  // rows past the prompt are masked below
           kr[i] = *(const uint4 *)(Kb + (row * (uint32_t)D + (uint32_t)(e % C8) * 8u));
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < VI; ++i) {
-        const int e = tid + i * NT;
-        // a value row past the prompt is taken as zero: a zero weight must not meet a NaN
-        va[i] = make_uint4(0u, 0u, 0u, 0u);
-        vb[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (Cf::V_ITEMS % NT == 0 || e < Cf::V_ITEMS) {
-          // a wave takes 4 neighbouring pieces (64 bytes) of 16 key pairs
-          const int c = (e / 128) * 4 + (e % 4), k0 = kn + 2 * ((e / 4) % 32);
-          const uint32_t off = (uint32_t)k0 * (uint32_t)D + (uint32_t)c * 8u;
-          if (k0 < N) va[i] = *(const uint4 *)(Vb + off);
-          if (k0 + 1 < N) vb[i] = *(const uint4 *)(Vb + (off + (uint32_t)D));
+          // a value row past the prompt is taken as zero: a zero weight must not meet a NaN
+          vr[i] = make_uint4(0u, 0u, 0u, 0u);
+          if (kn + e / C8 < N) vr[i] = *(const uint4 *)(Vb + (row * (uint32_t)D + (uint32_t)(e % C8) * 8u));
         }
       }
     }
@@ -175,6 +163,9 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
 #pragma unroll
           for (int v = 0; v < 16; ++v) Oacc[blk][v] *= alpha;
       }
+      // lane a of a 16-lane group points at key a / 4 of its 4-key block and at channels 4 (a % 4) .. +3 of the
+      // group's 16 channels; the second half-wave takes the keys 4 further on
+      const bf16_t *vtr = Vs + (buf * BN + 4 * h + (lane % 16) / 4) * VROW + 16 * ((lane % 32) / 16) + 4 * (lane % 4);
 #pragma unroll
       for (int hk = 0; hk < 2; ++hk)
 #pragma unroll
@@ -189,8 +180,13 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
           }
 #pragma unroll
           for (int blk = 0; blk < DB; ++blk) {
-            const pa_bf16x8 a = __builtin_bit_cast(
-                pa_bf16x8, *(const uint4 *)(Vt + (buf * D + 32 * blk + col) * VROW + 32 * hk + 16 * m + 8 * h));
+            // A fragment = V^T: channel 32 blk + lane % 32, keys 32 hk + 16 m + 8 b + 4 h + (0..3) for b = 0, 1.
+            // One transposing read hands each lane of a 16-lane group one channel of a 4-key x 16-channel block.
+            const bf16_t *vp = vtr + (32 * hk + 16 * m) * VROW + 32 * blk;
+            const pa_s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((pa_lds_s16x4 *)vp);
+            const pa_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((pa_lds_s16x4 *)(vp + 8 * VROW));
+            const pa_s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            const pa_bf16x8 a = __builtin_bit_cast(pa_bf16x8, a8);
             Oacc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, Oacc[blk], 0, 0, 0);
           }
         }
@@ -199,24 +195,9 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
 #pragma unroll
       for (int i = 0; i < KI; ++i) {
         const int e = tid + i * NT;
-        if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS)
+        if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS) {
           *(uint4 *)(Ks + ((buf ^ 1) * BN + e / C8) * KROW + (e % C8) * 8) = kr[i];
-      }
-#pragma unroll
-      for (int i = 0; i < VI; ++i) {
-        const int e = tid + i * NT;
-        if (Cf::V_ITEMS % NT == 0 || e < Cf::V_ITEMS) {
-          const int c = (e / 128) * 4 + (e % 4), kl = 2 * ((e / 4) % 32);
-          bf16_t *dst = Vt + ((buf ^ 1) * D + c * 8) * VROW + pa_slot(kl);
-          // channel by channel: key kl in the low half of the word, key kl + 1 in the high half
-          *(uint32_t *)(dst + 0 * VROW) = (va[i].x & 0xffffu) | (vb[i].x << 16);
-          *(uint32_t *)(dst + 1 * VROW) = (va[i].x >> 16) | (vb[i].x & 0xffff0000u);
-          *(uint32_t *)(dst + 2 * VROW) = (va[i].y & 0xffffu) | (vb[i].y << 16);
-          *(uint32_t *)(dst + 3 * VROW) = (va[i].y >> 16) | (vb[i].y & 0xffff0000u);
-          *(uint32_t *)(dst + 4 * VROW) = (va[i].z & 0xffffu) | (vb[i].z << 16);
-          *(uint32_t *)(dst + 5 * VROW) = (va[i].z >> 16) | (vb[i].z & 0xffff0000u);
-          *(uint32_t *)(dst + 6 * VROW) = (va[i].w & 0xffffu) | (vb[i].w << 16);
-          *(uint32_t *)(dst + 7 * VROW) = (va[i].w >> 16) | (vb[i].w & 0xffff0000u);
+          *(uint4 *)(Vs + ((buf ^ 1) * BN + e / C8) * VROW + (e % C8) * 8) = vr[i];
         }
       }
     }
