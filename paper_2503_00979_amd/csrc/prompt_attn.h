@@ -140,7 +140,12 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx4[v & 3] = fmaxf(mx4[v & 3], s[hk][v]);
       float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 32)) * P.scale_log2;
+      {
+        // the other half-wave's maximum for the same row, by a register swap between the halves (no LDS trip):
+        // afterwards the two results hold (low half's, high half's) value in every lane
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * P.scale_log2;
+      }
       // The reference only moves when the row's maximum has outgrown it by 2^8 (any reference gives the same
       // quotient; the exponentials stay below 2^8, far from any overflow): the accumulators are rescaled a
       // few times per row instead of at every new maximum.  Finite from the first tile on: key 0 is visible
