@@ -38,6 +38,7 @@ struct PromptAttnCfg {
   static constexpr int QB = G >= 5 ? 1 : 8 / G;  // 32-row query sub-blocks per workgroup
   static constexpr int NWV = G * QB, NT = NWV * 64, BM = 32 * QB;
   static constexpr int BN = 64;                  // keys per tile
+  static constexpr int NSUB = 2, NBUF = 2 * NSUB; // tiles per barrier; tile buffers in LDS
   static constexpr int KS = D / 16, DB = D / 32, C8 = D / 8;
   static constexpr int KROW = D + 8;             // bf16 per K row in LDS: 16-byte reads of 16 rows hit 64 distinct banks
   static constexpr int VROW = D + 32;            // bf16 per V row in LDS: 4 consecutive rows start 16 banks apart, so
@@ -45,17 +46,17 @@ struct PromptAttnCfg {
                                                  // 32 lanes) cover all 64 banks
   static constexpr int K_ITEMS = BN * C8;        // 16-byte pieces of a K tile, and of a V tile
   static constexpr int KI = (K_ITEMS + NT - 1) / NT;
-  static constexpr size_t lds_bytes = (size_t)2 * BN * (KROW + VROW) * 2;
+  static constexpr size_t lds_bytes = (size_t)NBUF * BN * (KROW + VROW) * 2;
 };
 
 template <int D, int G>
 __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(PromptAttnParams P) {
   using Cf = PromptAttnCfg<D, G>;
   constexpr int NT = Cf::NT, BM = Cf::BM, BN = Cf::BN, KS = Cf::KS, DB = Cf::DB, C8 = Cf::C8;
-  constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI;
+  constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI, NSUB = Cf::NSUB, NBUF = Cf::NBUF;
   extern __shared__ __align__(16) unsigned char pa_smem[];
-  bf16_t *Ks = (bf16_t *)pa_smem;        // [2][BN][KROW]
-  bf16_t *Vs = Ks + 2 * BN * KROW;       // [2][BN][VROW], row-major like K
+  bf16_t *Ks = (bf16_t *)pa_smem;        // [NBUF][BN][KROW]
+  bf16_t *Vs = Ks + NBUF * BN * KROW;    // [NBUF][BN][VROW], row-major like K
 
   const int tid = threadIdx.x, wave = tid / WAVE, lane = tid % WAVE, h = lane / 32, col = lane % 32;
   const int u = blockIdx.y, lb = u / P.Mkv, kh = u % P.Mkv, b = lb % P.B;
@@ -87,14 +88,16 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
     for (int v = 0; v < 16; ++v) Oacc[blk][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;  // log2 domain; l_run is this lane's share of the row sum
 
-  // Trip t works on tile t out of LDS buffer t & 1 while tile t + 1 travels global -> registers (issued before
-  // the arithmetic) -> the other buffer (after it); trip -1 only stages tile 0.
-  for (int t = -1; t < ntile; ++t) {
-    const int buf = t & 1, kb = t * BN;
-    const bool more = t + 1 < ntile;
+  // Trip t works on tile t out of LDS buffer t % NBUF while tile t + NSUB travels global -> registers (issued
+  // before the arithmetic) -> its buffer (after it); the first NSUB trips only stage.  One barrier every NSUB
+  // trips: between the trip that writes a buffer and the trips that read it, and between the trips that read
+  // it and the next trip that overwrites it (NBUF = 2 NSUB trips apart), lies a trip that ends in a barrier.
+  for (int t = -NSUB; t < ntile; ++t) {
+    const int buf = (t + NBUF) % NBUF, nbuf = (t + NSUB + NBUF) % NBUF, kb = t * BN;
+    const bool more = t + NSUB < ntile;
     uint4 kr[KI], vr[KI];
     if (more) {
-      const int kn = kb + BN;
+      const int kn = kb + NSUB * BN;
 #pragma unroll
       for (int i = 0; i < KI; ++i) {
         const int e = tid + i * NT;
@@ -201,12 +204,12 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
       for (int i = 0; i < KI; ++i) {
         const int e = tid + i * NT;
         if (Cf::K_ITEMS % NT == 0 || e < Cf::K_ITEMS) {
-          *(uint4 *)(Ks + ((buf ^ 1) * BN + e / C8) * KROW + (e % C8) * 8) = kr[i];
-          *(uint4 *)(Vs + ((buf ^ 1) * BN + e / C8) * VROW + (e % C8) * 8) = vr[i];
+          *(uint4 *)(Ks + (nbuf * BN + e / C8) * KROW + (e % C8) * 8) = kr[i];
+          *(uint4 *)(Vs + (nbuf * BN + e / C8) * VROW + (e % C8) * 8) = vr[i];
         }
       }
     }
-    __syncthreads();  // the next tile is in place, and every read of this one is done before it is overwritten
+    if ((t + 1) % NSUB == 0) __syncthreads();
   }
 
   if (!wave_on) return;
