@@ -331,7 +331,8 @@ int launch_prompt_attn(const PromptAttnParams &P, int U, hipStream_t st) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::lds_bytes));
     raised = true;
   }
-  hipLaunchKernelGGL((prompt_attn_kernel<D, G>), dim3((P.Nmax + Cf::BM - 1) / Cf::BM, U), dim3(Cf::NT), Cf::lds_bytes,
+  const int ntask = (P.Nmax + 31) / 32 * G;  // (32-row block, head) pairs of one KV head
+  hipLaunchKernelGGL((prompt_attn_kernel<D, G>), dim3((ntask + Cf::NWV - 1) / Cf::NWV, U), dim3(Cf::NT), Cf::lds_bytes,
                      st, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;

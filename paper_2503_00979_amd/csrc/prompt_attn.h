@@ -3,9 +3,11 @@
 // that selection disappears, the prompt's keys are scored with the normalisers this pass has already made
 // (the fusion of selection with the prompt's attention pass that the paper's closing section leaves as future work).
 //
-// bf16 in, fp32 accumulate, bf16 out, v_mfma_f32_32x32x16_bf16.  One workgroup = 32*QB query rows of the G
-// query heads that share one KV head: every K/V tile staged in LDS is used by all of them.  A wave owns 32
-// rows of one head and keeps, per lane, ONE query column of the transposed problem
+// bf16 in, fp32 accumulate, bf16 out, v_mfma_f32_32x32x16_bf16.  The work of one KV head is a list of tasks
+// (32-row query block, query head of the group), row blocks outermost; a workgroup of 8 waves takes 8
+// consecutive tasks, one per wave, whatever G is: every SIMD holds two waves, and every K/V tile staged in LDS
+// is used by all 8 (they share the KV head; each wave follows its own causal limit).  A wave owns 32 rows of one
+// head and keeps, per lane, ONE query column of the transposed problem
 //     S^T[key][query] = K Q^T          (A = keys from LDS, B = the wave's query fragments, in registers)
 //     O^T[dv][query] += V^T P^T        (A = values from LDS through the transposing read, B = the exponentials)
 // so the results of the first product are, as they lie in registers, the B operand of the second, and the row
@@ -35,8 +37,7 @@ struct PromptAttnParams {
 
 template <int D, int G>
 struct PromptAttnCfg {
-  static constexpr int QB = G >= 5 ? 1 : 8 / G;  // 32-row query sub-blocks per workgroup
-  static constexpr int NWV = G * QB, NT = NWV * 64, BM = 32 * QB;
+  static constexpr int NWV = 8, NT = NWV * 64;    // tasks (waves) per workgroup
   static constexpr int BN = 64;                  // keys per tile
   static constexpr int NSUB = 2, NBUF = 2 * NSUB; // tiles per barrier; tile buffers in LDS
   static constexpr int KS = D / 16, DB = D / 32, C8 = D / 8;
@@ -52,7 +53,7 @@ struct PromptAttnCfg {
 template <int D, int G>
 __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(PromptAttnParams P) {
   using Cf = PromptAttnCfg<D, G>;
-  constexpr int NT = Cf::NT, BM = Cf::BM, BN = Cf::BN, KS = Cf::KS, DB = Cf::DB, C8 = Cf::C8;
+  constexpr int NT = Cf::NT, NWV = Cf::NWV, BN = Cf::BN, KS = Cf::KS, DB = Cf::DB, C8 = Cf::C8;
   constexpr int KROW = Cf::KROW, VROW = Cf::VROW, KI = Cf::KI, NSUB = Cf::NSUB, NBUF = Cf::NBUF;
   extern __shared__ __align__(16) unsigned char pa_smem[];
   bf16_t *Ks = (bf16_t *)pa_smem;        // [NBUF][BN][KROW]
@@ -62,14 +63,14 @@ __global__ __launch_bounds__((PromptAttnCfg<D, G>::NT)) void prompt_attn_kernel(
   const int u = blockIdx.y, lb = u / P.Mkv, kh = u % P.Mkv, b = lb % P.B;
   const int N = P.plen[b];
   // long rows first: the last workgroups to start are the short ones
-  const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * BM;
-  if (q0 >= N) return;
-  const int g = wave % G, qs = q0 + (wave / G) * 32;
+  const int task0 = (int)(gridDim.x - 1 - blockIdx.x) * NWV;
+  if ((task0 / G) * 32 >= N) return;  // the first task's rows are past the prompt, and so are the others'
+  const int task = task0 + wave, g = task % G, qs = (task / G) * 32;
   const bool wave_on = qs < N;
   const int query = qs + col;
   const int qm = min(query, N - 1);        // rows past the prompt repeat the last row and are never stored
   const int q_lo = min(qs, N - 1), q_hi = min(qs + 31, N - 1);
-  const int ntile = (min(q0 + BM, N) - 1) / BN + 1;
+  const int ntile = min(((task0 + NWV - 1) / G) * 32 + 31, N - 1) / BN + 1;  // up to the last task's last row
   const bf16_t *Kb = P.K + (size_t)u * P.Nmax * D, *Vb = P.V + (size_t)u * P.Nmax * D;
   const size_t head = (size_t)lb * P.Mq + (size_t)kh * G + g;
 
