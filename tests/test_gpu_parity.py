@@ -312,6 +312,8 @@ ATTEND = [
     ("outliers_T4", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=48, R=16, fusion="sum", prompt_lens=(513, 64), steps=24,
                          n_outlier_channels=3, evict_every=4)),
     ("window_longer_than_prompt", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=10, R=40, fusion="sum", prompt_lens=(17, 90), steps=50)),
+    ("prompts_below_one_tile", dict(L=2, B=3, M=6, Mkv=2, d=128, dtype="bf16", C=6, R=4, fusion="max", prompt_lens=(5, 1, 3), steps=30)),
+    ("mha_many_tasks", dict(L=1, B=1, M=3, Mkv=3, d=64, dtype="bf16", C=20, R=8, fusion="sum", prompt_lens=(700,), steps=10)),
 ]
 
 
