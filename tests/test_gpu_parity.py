@@ -202,7 +202,11 @@ def _random_case(i):
 def test_random_small_configs(i, oracle_lib):
     kw = _random_case(i)
     wl = inputs.small_workload(10000 + i, **kw)
-    ls = _lockstep(wl, DEV, per_layer=bool(i & 1), use_lse=bool(i & 2)).prefill()
+    # prefill through one of the three entries: plain, caller's log-sum-exp, fused with the prompt's attention (bf16)
+    attend = kw["dtype"] == "bf16" and i % 3 == 0
+    ls = _lockstep(wl, DEV, per_layer=bool(i & 1), use_lse=bool(i & 2) and not attend, use_attend=attend).prefill()
+    if attend:
+        _check_attention(wl, ls.attn_out)
     rep = ls.run(wl.steps, check_every=1)
     _report(f"random{i} {kw}", rep)
 
