@@ -209,7 +209,9 @@ int decode_threads(const morphkv_handle *h, int U) {
   if (U >= 8 * cu && h->cfg.R <= 512) return 128;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
-  return 1024;
+  // few units: the launch is a latency chain, and for a cache under 1024 slots 16 waves only add to its
+  // barriers (c4 layer by layer, 544 slots: 594 -> 555 us per step)
+  return h->L.n_pad < 1024 ? 512 : 1024;
 }
 
 template <typename T, int D, int G>
