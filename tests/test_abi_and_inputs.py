@@ -80,3 +80,25 @@ def test_workload_shapes_and_subsets():
     assert torch.equal(qs[:, 0], q[:, 2]) and torch.equal(ks[:, 1], k[:, 0])
     sc = s.key_channel_scale()
     assert int((sc == 5.0).sum()) <= 2 * 2 * 2 and int((sc == 5.0).sum()) >= 2 * 2
+
+
+def test_prompt_queries_hold_the_window_rows():
+    """The whole-prompt queries carry prompt()'s window queries in the last min(R, N_b) rows before N_b, so the
+    fused entry and the window-only entry are given the same window."""
+    wl = inputs.small_workload(5, L=2, B=3, M=4, Mkv=2, d=64, dtype="bf16", C=6, R=8, prompt_lens=(20, 3, 8), steps=1)
+    Qw, _, _ = wl.prompt()
+    Q = wl.prompt_queries()
+    assert tuple(Q.shape) == (2, 3, 4, wl.Nmax, 64)
+    for b, N in enumerate(wl.prompt_lens):
+        Rw = min(wl.R, N)
+        assert torch.equal(Q[:, b, :, N - Rw:N], Qw[:, b, :, :Rw])
+    sub = wl.prompt_queries(batch_index=[2])
+    assert torch.equal(sub[:, 0], Q[:, 2])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
