@@ -73,7 +73,11 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
 
 /* Host-only handle over caller-owned DEVICE buffers of at least morphkv_sizes bytes.
  * The buffers need no initialisation; prefill_select writes all state.  They must
- * stay valid until morphkv_destroy.  Ownership stays with the caller. */
+ * stay valid until morphkv_destroy.  Ownership stays with the caller.
+ * MORPHKV_EINVAL if C + R needs more LDS than a compute unit has (the reason is in morphkv_last_error).
+ * Two environment variables, read here, override tuning choices and never change results:
+ * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel) and
+ * MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least). */
 int morphkv_create(morphkv_handle **h, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch);
 int morphkv_destroy(morphkv_handle *h);
 
