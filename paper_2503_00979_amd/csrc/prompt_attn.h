@@ -1,7 +1,7 @@
 // Causal attention over the whole prompt (Eq.1 at every prompt position, a token attends to itself) that also
 // hands the window rows' softmax normalisers to the selection over the prompt (Eq.4-7): the statistics pass of
 // that selection disappears, the prompt's keys are scored with the normalisers this pass has already made
-// (the fusion of selection with the prompt's attention pass that the paper's closing section leaves as future work).
+// (the integration of selection with the attention kernel that Section 8, "Future Work", plans).
 //
 // bf16 in, fp32 accumulate, bf16 out, v_mfma_f32_32x32x16_bf16.  The work of one KV head is a list of tasks
 // (32-row query block, query head of the group), row blocks outermost; a workgroup of 8 waves takes 8
