@@ -327,12 +327,10 @@ int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_
 template <int D, int G>
 int launch_prompt_attn(const PromptAttnParams &P, int U, hipStream_t st) {
   using Cf = PromptAttnCfg<D, G>;
-  static bool raised = false;  // the kernel's LDS need is a constant of the build: ask once per process
-  if (!raised) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&prompt_attn_kernel<D, G>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::lds_bytes));
-    raised = true;
-  }
+  // more LDS than a launch gets by default; asked for at every call (a call lasts milliseconds, and the
+  // attribute belongs to the current device)
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&prompt_attn_kernel<D, G>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::lds_bytes));
   const int ntask = (P.Nmax + 31) / 32 * G;  // (32-row block, head) pairs of one KV head
   hipLaunchKernelGGL((prompt_attn_kernel<D, G>), dim3((ntask + Cf::NWV - 1) / Cf::NWV, U), dim3(Cf::NT), Cf::lds_bytes,
                      st, P);
