@@ -18,8 +18,9 @@
  *  - GQA: sum over the M/M' query heads of a group, then fuse (Alg.1);
  *  - ties in Top_C keep the lower position;
  *  - fewer than C older tokens: keep all of them, nothing is evicted;
- *  - coarse eviction (Appendix A.5): selection runs only at steps whose token
- *    position is a multiple of T; in between, tokens leaving the window are
+ *  - coarse eviction (Appendix A.5): selection runs only at every T-th
+ *    generation step of a sequence (its T-th, 2T-th, ... generated token,
+ *    whatever the prompt length); in between, tokens leaving the window are
  *    kept, so up to C+T-1 older tokens are resident.
  */
 #include "morphkv_ref.h"

@@ -466,3 +466,85 @@ def test_prompt_attention_window_rows_give_selection_scores(oracle_lib):
         got = o.prefill_scores(u)[:N - R]
         assert np.abs(got - F).max() < 1e-12
     o.close()
+
+
+# --------------------------------------------------------------------------
+# 10. coarse schedule (Appendix A.5): which generation steps select, pinned by hand-worked sequences
+#     (tests/golden/coarse_schedule.txt), not by the oracle's own formula
+# --------------------------------------------------------------------------
+def _read_coarse_schedule():
+    groups = {}
+    with open(os.path.join(GOLDEN, "coarse_schedule.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            head, ev, counts = (x.split() for x in line.split("|"))
+            T, C, n_old = (int(x) for x in head)
+            groups.setdefault((T, C), []).append((n_old, [int(x) for x in ev], [int(x) for x in counts]))
+    return sorted(groups.items())
+
+
+@pytest.mark.parametrize("group", _read_coarse_schedule(), ids=lambda g: f"T{g[0][0]}_C{g[0][1]}")
+@pytest.mark.parametrize("fusion", ["sum", "max"])
+def test_coarse_schedule_hand_worked(oracle_lib, group, fusion):
+    (T, C), rows = group
+    R = 3
+    plens = tuple(n_old + R for n_old, _, _ in rows)
+    steps = max(len(c) for _, _, c in rows)
+    wl = inputs.small_workload(900 + 10 * T + C, L=1, B=len(rows), M=2, Mkv=1, d=8, dtype="f32", C=C, R=R,
+                               fusion=fusion, prompt_lens=plens, steps=steps, evict_every=T)
+    o = _mk(oracle_lib, wl)
+    Qw, K, V = wl.prompt()
+    o.prefill_select(Qw, K, V, wl.prompt_len_tensor().numpy())
+    snaps, _ = o.export_positions()
+    for b, (n_old, _, _) in enumerate(rows):
+        assert len(snaps[b]) == min(n_old, C)
+    for t in range(steps):
+        q, k, v = wl.decode_inputs(t)
+        o.decode_begin(q, k, v)
+        _, _, _, n_evict, _ = o.candidates()
+        o.decode_commit(None)
+        snaps, wins = o.export_positions()
+        for b, (n_old, ev_steps, counts) in enumerate(rows):
+            if t >= len(counts):
+                continue
+            gen_step = t + 1
+            assert (n_evict[b] > 0) == (gen_step in ev_steps), (b, gen_step)
+            assert len(snaps[b]) == counts[t], (b, gen_step)
+            assert list(wins[b]) == list(range(plens[b] + t - R + 1, plens[b] + t + 1))
+
+
+# --------------------------------------------------------------------------
+# 11. a caller-imposed retained set at the prompt (the harness uses it to adopt another valid choice at a
+#     near-tie): from that set on, the oracle must behave as the brute force started from the same set
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("fusion,T", [("sum", 1), ("max", 1), ("sum", 3)])
+def test_forced_prompt_selection_then_bruteforce(oracle_lib, fusion, T):
+    C, R, N, steps, G = 5, 3, 30, 40, 2
+    wl = inputs.small_workload(950 + T, L=1, B=1, M=G, Mkv=1, d=8, dtype="f32", C=C, R=R, fusion=fusion,
+                               prompt_lens=(N,), steps=steps, evict_every=T)
+    Qw, K, V = wl.prompt()
+    o = _mk(oracle_lib, wl)
+    o.prefill_select(Qw, K, V, np.array([N], np.int32))
+    own = list(o.export_positions()[0][0])
+    # impose a different set: swap the two best-looking retained tokens for two that were not retained
+    others = [k for k in range(N - R) if k not in own]
+    forced = sorted(own[2:] + others[:1] + others[-1:])
+    assert forced != own and len(forced) == C
+    o.prefill_select(Qw, K, V, np.array([N], np.int32), forced_pos=np.array([forced], np.int32))
+    assert list(o.export_positions()[0][0]) == forced
+    F_own = o.prefill_scores(0)                    # the scores are still the oracle's own
+    x = BruteForceUnit(C, R, fusion, 1.0 / math.sqrt(wl.head_dim), T)
+    x.prefill(Qw[0, 0].numpy(), K[0, 0, 0, :N].numpy(), V[0, 0, 0, :N].numpy())
+    np.testing.assert_allclose(F_own, [x.last_scores[k] for k in range(N - R)], rtol=1e-12)
+    x.old = set(forced)
+    for t in range(steps):
+        q, k, v = wl.decode_inputs(t)
+        out = o.decode_step(q, k, v)
+        ob = x.decode(q[0, 0].numpy(), k[0, 0, 0].numpy(), v[0, 0, 0].numpy())
+        np.testing.assert_allclose(out[0, 0], ob, rtol=0, atol=1e-12)
+        snaps, wins = o.export_positions()
+        assert list(snaps[0]) == sorted(x.old), t
+    # a set that names a token outside the candidates is refused
+    with pytest.raises(RuntimeError):
+        o.prefill_select(Qw, K, V, np.array([N], np.int32), forced_pos=np.array([[0, 1, 2, 3, N - 1]], np.int32))
