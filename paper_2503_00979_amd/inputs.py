@@ -31,6 +31,7 @@ _C2 = 0x94D049BB133111EB
 # tensor ids (upper bits of the stream number)
 T_PROMPT_K, T_PROMPT_V, T_PROMPT_Q, T_DEC_Q, T_DEC_K, T_DEC_V, T_LEN, T_OUTLIER = range(1, 9)
 T_PROMPT_QALL = 9
+T_CODEBOOK, T_CODE_PROMPT, T_CODE_DEC = 10, 11, 12
 
 
 def _s64(x: int) -> int:
@@ -114,6 +115,8 @@ class Workload:
     outlier_scale: float = 5.0
     evict_every: int = 1
     max_new_tokens: int = 0   # only with evict_every == 0 (selection at the prompt only): room for decode steps
+    key_codes: int = 0        # > 0: every key is one of this many seeded vectors per (layer, KV head), so that
+                              # many tokens hold bit-identical keys (inputs with exact ties); 1 = all keys identical
 
     # ---- derived sizes -------------------------------------------------
     @property
@@ -152,6 +155,13 @@ class Workload:
     def _slab(self, tid: int, l: int, b: int, heads: int, rows: int, device) -> torch.Tensor:
         return normal(self.seed, (tid << 40) + l * self.batch + b, (heads, rows, self.head_dim), device)
 
+    def _coded_keys(self, l: int, tid: int, stream: int, rows: int, device) -> torch.Tensor:
+        """[M', rows, d] fp32: row r of head h is code word code[h, r] of that head's seeded codebook."""
+        book = normal(self.seed, (T_CODEBOOK << 40) + l, (self.n_kv_heads, self.key_codes, self.head_dim), device)
+        z = _lsr(raw_bits(self.seed, (tid << 40) + stream, self.n_kv_heads * rows, device), 11) % self.key_codes
+        idx = z.reshape(self.n_kv_heads, rows, 1).expand(-1, -1, self.head_dim)
+        return torch.gather(book, 1, idx)
+
     def prompt(self, device="cpu", batch_index: Optional[List[int]] = None):
         """(Q_window [L,B,M,R,d], K [L,B,M',Nmax,d], V [L,B,M',Nmax,d]) in the workload dtype.
 
@@ -169,6 +179,8 @@ class Workload:
             for i, b in enumerate(bs):
                 Q[l, i] = self._slab(T_PROMPT_Q, l, b, Mq, R, device).to(dt)
                 K[l, i] = (self._slab(T_PROMPT_K, l, b, Mk, Nm, device) * ksc[l, 0]).to(dt)
+                if self.key_codes:
+                    K[l, i] = self._coded_keys(l, T_CODE_PROMPT, l * self.batch + b, Nm, device).to(dt)
                 V[l, i] = self._slab(T_PROMPT_V, l, b, Mk, Nm, device).to(dt)
         return Q, K, V
 
@@ -198,6 +210,10 @@ class Workload:
         k = normal(self.seed, (T_DEC_K << 40) + step, (L, B, Mk, d), device)
         v = normal(self.seed, (T_DEC_V << 40) + step, (L, B, Mk, d), device)
         k = k * self.key_channel_scale(device)[:, :, :, 0, :]
+        if self.key_codes:
+            for l in range(L):
+                for b in range(B):
+                    k[l, b] = self._coded_keys(l, T_CODE_DEC, (step * L + l) * B + b, 1, device)[:, 0]
         q, k, v = q.to(dt), k.to(dt), v.to(dt)
         if batch_index is not None:
             ix = torch.tensor(list(batch_index), device=device)
@@ -238,7 +254,9 @@ def workload(name: str) -> Workload:
 
 
 def small_workload(seed: int, *, L=1, B=1, M=4, Mkv=2, d=64, dtype="f32", C=6, R=4, fusion="sum",
-                   prompt_lens=(20,), steps=30, n_outlier_channels=0, evict_every=1, max_new_tokens=0) -> Workload:
+                   prompt_lens=(20,), steps=30, n_outlier_channels=0, evict_every=1, max_new_tokens=0,
+                   key_codes=0) -> Workload:
     """Free-form small case for tests."""
     return Workload(f"small{seed}", L, B, M, Mkv, d, dtype, C, R, fusion, tuple(prompt_lens), steps, seed,
-                    n_outlier_channels=n_outlier_channels, evict_every=evict_every, max_new_tokens=max_new_tokens)
+                    n_outlier_channels=n_outlier_channels, evict_every=evict_every, max_new_tokens=max_new_tokens,
+                    key_codes=key_codes)

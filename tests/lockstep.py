@@ -4,8 +4,10 @@ Selection is chaotic after one divergent eviction, so both sides run the same st
 seeded inputs and are compared every step:
   * attention output: max abs error within tolerance (2e-3 for bf16 inputs, 1e-5 for fp32);
   * evicted position: identical, or -- the only exemption -- a near-tie at the top-C boundary,
-    where the oracle's own fp64 scores of the two choices differ by less than 1e-5 relative; the
-    oracle then adopts the GPU's choice (so the runs stay comparable) and the event is counted;
+    where the oracle's own fp64 scores of the two choices differ by less than 1e-5 relative (and
+    do differ); the oracle then adopts the GPU's choice (so the runs stay comparable) and the
+    event is counted.  Where the oracle's two scores are EQUAL the choice is fixed by the tie
+    rule (the lower position is kept) and any other choice fails the step;
   * retained sets: compared in full every `check_every` steps and at the end.
 The oracle may cover only a sample of the sequences (batch_index) when the full batch is too slow
 for the host; the GPU always runs the full configuration.
@@ -30,6 +32,8 @@ class Report:
     steps: int = 0
     near_ties_prefill: int = 0
     near_ties_decode: int = 0
+    exact_ties_prefill: int = 0   # units whose C-th largest prompt score is shared by several candidates
+    exact_ties_decode: int = 0    # selections whose boundary score is shared by several candidates (the tie rule decided)
     max_out_err: float = 0.0
     max_score_rel_err: float = 0.0
     evictions: int = 0
@@ -127,17 +131,27 @@ class LockStep:
         forced = None
         for i in range(len(self.umap)):
             assert list(gw[i]) == list(ow[i]), f"window differs after prefill, unit {i}"
+            F = self.oracle.prefill_scores(i)
+            kth = None
+            if len(F) > wl.C:
+                kth = np.sort(F)[::-1][wl.C - 1]
+                rep.exact_ties_prefill += int(np.count_nonzero(F == kth) > 1)
             if list(gs[i]) == list(os_[i]):
                 continue
+            assert kth is not None, f"prefill unit {i}: retained sets differ although every older token fits"
             # near-tie exemption: every element of the symmetric difference scores within 1e-5 relative
-            # of the C-th largest oracle score
-            F = self.oracle.prefill_scores(i)
-            kth = np.sort(F)[::-1][wl.C - 1]
+            # of the C-th largest oracle score -- and not exactly at it: equal scores are decided by position
             diff = set(gs[i]) ^ set(os_[i])
             assert len(gs[i]) == len(os_[i])
             for k in diff:
                 assert abs(F[k] - kth) <= NEAR_TIE_REL * abs(kth), (
                     f"prefill selection differs beyond a near-tie: unit {i} pos {k} F={F[k]!r} C-th={kth!r}")
+            lost, won = sorted(set(os_[i]) - set(gs[i])), sorted(set(gs[i]) - set(os_[i]))
+            for a in lost:
+                for b_ in won:
+                    assert F[a] != F[b_], (
+                        f"prefill unit {i}: positions {a} and {b_} have EQUAL scores {F[a]!r}; the tie rule keeps the "
+                        f"lower position, the GPU kept {b_}")
             rep.near_ties_prefill += len(diff) // 2
             if forced is None:
                 forced = np.full((len(self.umap), wl.C), -1, np.int32)
@@ -179,31 +193,44 @@ class LockStep:
         rep.max_out_err = max(rep.max_out_err, err)
         assert err <= self.tol, f"step {t}: attention output off by {err:.3e} (> {self.tol})"
         decided = np.full(len(self.umap), -1, np.int32)
+        Fg_all = self.scoreF.cpu().numpy() if self.scoreF is not None else None
         for i in range(len(self.umap)):
             if n_evict[i] == 0:
                 assert ev[i] == -1, f"step {t} unit {i}: GPU evicted {ev[i]} where nothing may be evicted"
                 continue
             rep.evictions += 1
+            nc = int(n_cand[i])
+            cp, cF = cand_pos[i, :nc], cand_F[i, :nc]
             e_or, e_gpu = int(choice[i, 0]), int(ev[i])
-            F = {int(cand_pos[i, x]): cand_F[i, x] for x in range(n_cand[i])}
+            F_or = cF[np.nonzero(cp == e_or)[0][0]]
+            rep.exact_ties_decode += int(np.count_nonzero(cF == F_or) > 1)
             if e_gpu != e_or:
-                assert e_gpu in F, f"step {t} unit {i}: GPU evicted {e_gpu}, not a candidate"
-                gap = F[e_gpu] - F[e_or]
-                assert gap <= NEAR_TIE_REL * abs(F[e_or]), (
-                    f"step {t} unit {i}: GPU evicted {e_gpu} (F={F[e_gpu]!r}), oracle {e_or} (F={F[e_or]!r}): "
+                hit = np.nonzero(cp == e_gpu)[0]
+                assert len(hit) == 1, f"step {t} unit {i}: GPU evicted {e_gpu}, not a candidate"
+                F_gpu = cF[hit[0]]
+                gap = F_gpu - F_or
+                assert gap != 0, (
+                    f"step {t} unit {i}: positions {e_gpu} and {e_or} have EQUAL scores {F_or!r}; the tie rule evicts "
+                    f"the higher position ({e_or}), the GPU evicted {e_gpu}")
+                assert gap <= NEAR_TIE_REL * abs(F_or), (
+                    f"step {t} unit {i}: GPU evicted {e_gpu} (F={F_gpu!r}), oracle {e_or} (F={F_or!r}): "
                     f"not a near-tie")
                 rep.near_ties_decode += 1
             decided[i] = e_gpu
-            if self.scoreF is not None:
-                Fg = self.scoreF.cpu().numpy()[self.umap[i]]
-                for slot in range(wl.C):
-                    pk = int(pos_before[i, slot])
-                    rel = abs(Fg[slot] - F[pk]) / max(abs(F[pk]), 1e-30)
-                    rep.max_score_rel_err = max(rep.max_score_rel_err, rel)
-                dem = [kk for kk in F if kk not in set(pos_before[i, :wl.C].tolist())]
+            if Fg_all is not None:
+                # captured GPU scores are in slot order ([C] = the token leaving the window): look each slot's
+                # position up among the oracle's candidates
+                Fg = Fg_all[self.umap[i]]
+                order = np.argsort(cp)
+                slots = pos_before[i, :wl.C]
+                at = order[np.searchsorted(cp[order], slots)]
+                assert np.array_equal(cp[at], slots)
+                rel = np.abs(Fg[:wl.C] - cF[at]) / np.maximum(np.abs(cF[at]), 1e-30)
+                dem = np.setdiff1d(cp, slots)
                 assert len(dem) == 1
-                rel = abs(Fg[wl.C] - F[dem[0]]) / max(abs(F[dem[0]]), 1e-30)
-                rep.max_score_rel_err = max(rep.max_score_rel_err, rel)
+                Fd = cF[np.nonzero(cp == dem[0])[0][0]]
+                rel_d = abs(Fg[wl.C] - Fd) / max(abs(Fd), 1e-30)
+                rep.max_score_rel_err = max(rep.max_score_rel_err, float(rel.max()), float(rel_d))
         self.oracle.decode_commit(decided)
         self.t += 1
         rep.steps += 1
@@ -233,13 +260,19 @@ class LockStep:
             rep.evictions += int(n_evict[i])
             o_set = set(int(x) for x in choice[i, :n_evict[i]])
             assert len(g_set) == n_evict[i], f"step {t} unit {i}: GPU evicted {len(g_set)} tokens, {n_evict[i]} are due"
+            F = {int(cand_pos[i, x]): cand_F[i, x] for x in range(n_cand[i])}
+            bound = max(F[e] for e in o_set)
+            rep.exact_ties_decode += int(sum(1 for f in F.values() if f == bound) > sum(1 for e in o_set if F[e] == bound))
             if g_set != o_set:
-                F = {int(cand_pos[i, x]): cand_F[i, x] for x in range(n_cand[i])}
-                bound = max(F[e] for e in o_set)
                 for e in g_set ^ o_set:
                     assert e in F, f"step {t} unit {i}: {e} is not a candidate"
                     assert abs(F[e] - bound) <= NEAR_TIE_REL * abs(bound), (
                         f"step {t} unit {i}: evicted sets differ beyond a near-tie at {e}: F={F[e]!r} boundary={bound!r}")
+                for a in g_set - o_set:
+                    for b_ in o_set - g_set:
+                        assert F[a] != F[b_], (
+                            f"step {t} unit {i}: positions {a} and {b_} have EQUAL scores {F[a]!r}; the tie rule evicts "
+                            f"the higher position ({b_}), the GPU evicted {a}")
                 rep.near_ties_decode += len(g_set - o_set)
             decided[i, :len(g_set)] = sorted(g_set)
         self.oracle.decode_commit(decided)
