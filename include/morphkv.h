@@ -85,13 +85,30 @@ int morphkv_destroy(morphkv_handle *h);
  *  Q_window  device [L][B][M][R][d]   queries of the last min(R,N_b) prompt tokens of each
  *                                     sequence; row j = query of position N_b - min(R,N_b) + j
  *  K, V      device [L][B][M'][Nmax][d]  prompt keys/values, rows >= N_b are ignored padding
- *  prompt_len HOST  [B]               1 <= N_b <= Nmax <= cfg.max_prompt_len
+ *  prompt_len HOST  [B]               1 <= N_b <= Nmax <= cfg.max_prompt_len; read before the call returns and
+ *                                     handed to the device as kernel arguments (no copy, no synchronisation:
+ *                                     the call can be captured in a HIP graph)
  * For every unit: causal softmax rows of the window queries over the whole prompt, summed
  * over the group's heads (Algorithm 1), fused over the rows (Eq.5/6) for the older tokens
  * k < N_b - min(R,N_b), top-min(C, count) kept (ties keep the lower position), K/V gathered
  * into the cache, and the recorded rows seeded.  Inputs are only read. */
 int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                            const int32_t *prompt_len, int32_t Nmax, void *stream /* hipStream_t */);
+
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): morphkv_prefill_select with the library's OWN workspace in
+ * place of the handle's `scratch` buffer -- a static device array of MORPHKV_NOALLOC_SCRATCH_BYTES that every
+ * GPU the library runs on holds until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine) and, like the other calls, only enqueues kernels on the stream.
+ * Arguments, results and the state left behind are those of morphkv_prefill_select (same kernels).
+ * MORPHKV_EINVAL, with the sizes in morphkv_last_error, if the configuration at this Nmax needs more workspace
+ * than the array holds (what morphkv_sizes reports as scratch_bytes for max_prompt_len = Nmax).
+ * All calls on one GPU share that array: two such calls that overlap in time on the same GPU (different streams
+ * or threads) race; calls on one stream are ordered.  The array keeps the previous call's contents; nothing
+ * in it has to start at zero (every field is written before it is read). */
+#define MORPHKV_NOALLOC_SCRATCH_BYTES (16u << 20)
+int morphkv_prefill_select_noalloc(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                                   const int32_t *prompt_len, int32_t Nmax, void *stream /* hipStream_t */);
 
 /* The same when the prompt's own attention pass has already been run by the caller (Section 8 names fusing the
  * selection into that pass as future work): attention kernels return, per query row, the natural logarithm of the

@@ -20,6 +20,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefill_select", "morphkv_prefill_select_lse",
+           "morphkv_prefill_select_noalloc",
            "morphkv_prefill_attend_select", "morphkv_decode_step",
            "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
@@ -56,6 +57,7 @@ def load_library():
     L.morphkv_create.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, vp, vp]
     L.morphkv_destroy.argtypes = [vp]
     L.morphkv_prefill_select.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
+    L.morphkv_prefill_select_noalloc.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_prefill_select_lse.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_prefill_attend_select.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.c_int32, vp]
     L.morphkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -180,6 +182,17 @@ class MorphKV:
             return
         _check(self.lib.morphkv_prefill_select(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V), pl, Nmax,
                                                self._stream()))
+
+    def prefill_select_noalloc(self, Q_window, K, V, prompt_len):
+        """prefill_select on the library's own static workspace (for callers that cannot allocate)."""
+        c = self.cfg
+        Nmax = K.shape[3]
+        self._want(Q_window, (c.n_layers, c.batch, c.n_q_heads, c.R, c.head_dim))
+        self._want(K, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        self._want(V, (c.n_layers, c.batch, c.n_kv_heads, Nmax, c.head_dim))
+        pl = (C.c_int32 * c.batch)(*[int(x) for x in prompt_len])
+        _check(self.lib.morphkv_prefill_select_noalloc(self._h, _dev_ptr(Q_window), _dev_ptr(K), _dev_ptr(V), pl, Nmax,
+                                                       self._stream()))
 
     def prefill_attend_select(self, Q, K, V, prompt_len, O=None, lse=None):
         """Causal attention over the whole prompt (O, optionally lse, are written) and the selection over it.

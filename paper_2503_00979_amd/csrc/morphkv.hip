@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -39,6 +40,50 @@ int fail(int code, const char *fmt, ...) {
   } while (0)
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- library-owned workspace for callers that cannot allocate (morphkv_prefill_select_noalloc): one array per
+// GPU, part of the loaded code object, held until the process ends.  In host code the array's name is only a
+// stand-in: its device address is looked up once per device and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)MORPHKV_NOALLOC_SCRATCH_BYTES;
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+char *g_scratch_ptr[MAX_DEVICES] = {};
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[(size_t)MORPHKV_NOALLOC_SCRATCH_BYTES];
+namespace {
+
+// device address of the current device's copy of `scratch`
+int static_scratch(char **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(MORPHKV_EHIP, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MORPHKV_EHIP, "hipGetSymbolAddress returned a null address for the library's workspace");
+    g_scratch_ptr[dev] = (char *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MORPHKV_OK;
+}
+
+// up to 256 host integers handed to the device as kernel arguments: no copy engine, no staging buffer, no host
+// synchronisation, and the launch can be captured in a HIP graph
+struct IntArgs { int32_t v[256]; };
+__global__ void store_ints_kernel(int32_t *dst, IntArgs a, int n) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = a.v[threadIdx.x];
+}
+int upload_ints(int32_t *dst, const int32_t *src, int n, hipStream_t st) {
+  for (int i0 = 0; i0 < n; i0 += 256) {
+    IntArgs a;
+    const int m = n - i0 < 256 ? n - i0 : 256;
+    for (int i = 0; i < 256; ++i) a.v[i] = i < m ? src[i0 + i] : 0;
+    hipLaunchKernelGGL(store_ints_kernel, dim3(1), dim3(256), 0, st, dst + i0, a, m);
+    HIP_TRY(hipGetLastError());
+  }
+  return MORPHKV_OK;
+}
 
 struct BufLayout {
   int U, G, Cs, CsP, n, n_pad, cps, cpt, esz;
@@ -174,15 +219,15 @@ DecodeParams decode_params(const morphkv_handle *h) {
   return P;
 }
 
-PrefillParams prefill_params(const morphkv_handle *h) {
+// scratch: the workspace the prompt-time kernels use (the caller's, or the library's own), carved up as L says
+PrefillParams prefill_params(const morphkv_handle *h, char *scratch_base, const BufLayout &L) {
   PrefillParams P{};
-  const BufLayout &L = h->L;
-  P.plen = (const int32_t *)(h->scratch + L.offPlen);
-  P.Srow = (float *)(h->scratch + L.offSrow);
-  P.Spart = (float2 *)(h->scratch + L.offSrow);
-  P.Sfin = (float2 *)(h->scratch + L.offStat);
-  P.F = (float *)(h->scratch + L.offF);
-  P.sel = (int32_t *)(h->scratch + L.offSel);
+  P.plen = (const int32_t *)(scratch_base + L.offPlen);
+  P.Srow = (float *)(scratch_base + L.offSrow);
+  P.Spart = (float2 *)(scratch_base + L.offSrow);
+  P.Sfin = (float2 *)(scratch_base + L.offStat);
+  P.F = (float *)(scratch_base + L.offF);
+  P.sel = (int32_t *)(scratch_base + L.offSel);
   P.Kc = h->cache + L.offK;
   P.Vc = h->cache + L.offV;
   P.pos = (int32_t *)(h->cache + L.offPos);
@@ -352,6 +397,27 @@ int dispatch_prompt_attn_g(int G, const PromptAttnParams &P, int U, hipStream_t 
   }
 }
 
+
+// selection over the prompt from the window queries (all three window entries end up here)
+int prefill_window(morphkv_handle *h, const void *Q_window, const void *K, const void *V, const float *lse_window,
+                   const int32_t *prompt_len, int32_t Nmax, hipStream_t st, char *scratch_base, const BufLayout &Ls) {
+  if (!Q_window || !K || !V || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
+  if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
+    return fail(MORPHKV_EINVAL, "Nmax %d outside 1..max_prompt_len (%d)", Nmax, h->cfg.max_prompt_len);
+  for (int b = 0; b < h->cfg.batch; ++b)
+    if (prompt_len[b] < 1 || prompt_len[b] > Nmax)
+      return fail(MORPHKV_EINVAL, "prompt_len[%d] = %d outside 1..Nmax (%d)", b, prompt_len[b], Nmax);
+  PrefillParams P = prefill_params(h, scratch_base, Ls);
+  P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax; P.lse = lse_window;
+  if (const int rc = upload_ints((int32_t *)P.plen, prompt_len, h->cfg.batch, st)) return rc;
+  const int rc = dispatch_prefill(h, P, st);
+  if (rc) return rc;
+  h->prefilled = true;
+  h->steps = 0;
+  std::fill(h->layer_steps.begin(), h->layer_steps.end(), 0u);
+  return MORPHKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -430,6 +496,13 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
     delete h;
     return rc;
   }
+  // set-up for morphkv_prefill_select_noalloc: the address of this device's copy of the library's workspace
+  // is looked up here, once per device, not inside a call that may be under stream capture
+  char *ws = nullptr;
+  if (const int rc = static_scratch(&ws)) {
+    delete h;
+    return rc;
+  }
   *out = h;
   return MORPHKV_OK;
 }
@@ -448,22 +521,26 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
 int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                                const float *lse_window, const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
-  if (!Q_window || !K || !V || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
+  return prefill_window(h, Q_window, K, V, lse_window, prompt_len, Nmax, (hipStream_t)stream, h->scratch, h->L);
+}
+
+int morphkv_prefill_select_noalloc(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                                   const int32_t *prompt_len, int32_t Nmax, void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
     return fail(MORPHKV_EINVAL, "Nmax %d outside 1..max_prompt_len (%d)", Nmax, h->cfg.max_prompt_len);
-  for (int b = 0; b < h->cfg.batch; ++b)
-    if (prompt_len[b] < 1 || prompt_len[b] > Nmax)
-      return fail(MORPHKV_EINVAL, "prompt_len[%d] = %d outside 1..Nmax (%d)", b, prompt_len[b], Nmax);
-  hipStream_t st = (hipStream_t)stream;
-  PrefillParams P = prefill_params(h);
-  P.Qw = Q_window; P.K = K; P.V = V; P.Nmax = Nmax; P.lse = lse_window;
-  HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
-  int rc = dispatch_prefill(h, P, st);
-  if (rc) return rc;
-  h->prefilled = true;
-  h->steps = 0;
-  std::fill(h->layer_steps.begin(), h->layer_steps.end(), 0u);
-  return MORPHKV_OK;
+  // the workspace is laid out for this call's Nmax, not for the handle's max_prompt_len
+  morphkv_config c = h->cfg;
+  c.max_prompt_len = Nmax;
+  const BufLayout Ls = make_layout(&c);
+  if (Ls.scratch_bytes > STATIC_SCRATCH_BYTES)
+    return fail(MORPHKV_EINVAL,
+                "prefill_select_noalloc: this configuration with Nmax = %d needs %zu bytes of workspace, the library's "
+                "own holds %zu (MORPHKV_NOALLOC_SCRATCH_BYTES); use morphkv_prefill_select with a caller-provided scratch",
+                Nmax, Ls.scratch_bytes, STATIC_SCRATCH_BYTES);
+  char *ws = nullptr;
+  if (const int rc = static_scratch(&ws)) return rc;
+  return prefill_window(h, Q_window, K, V, nullptr, prompt_len, Nmax, (hipStream_t)stream, ws, Ls);
 }
 
 int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O, float *lse,
@@ -480,8 +557,8 @@ int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
     return fail(MORPHKV_EINVAL, "Q, K, V and O must be 16-byte aligned");
   hipStream_t st = (hipStream_t)stream;
-  PrefillParams P = prefill_params(h);
-  HIP_TRY(hipMemcpyAsync((void *)P.plen, prompt_len, (size_t)h->cfg.batch * 4, hipMemcpyHostToDevice, st));
+  PrefillParams P = prefill_params(h, h->scratch, h->L);
+  if (const int rc = upload_ints((int32_t *)P.plen, prompt_len, h->cfg.batch, st)) return rc;
   PromptAttnParams A{};
   A.Q = (const bf16_t *)Q; A.K = (const bf16_t *)K; A.V = (const bf16_t *)V; A.O = (bf16_t *)O;
   A.lse = lse;
