@@ -75,9 +75,12 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
  * The buffers need no initialisation; prefill_select writes all state.  They must
  * stay valid until morphkv_destroy.  Ownership stays with the caller.
  * MORPHKV_EINVAL if C + R needs more LDS than a compute unit has (the reason is in morphkv_last_error).
- * Two environment variables, read here, override tuning choices and never change results:
- * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel) and
- * MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least). */
+ * Three environment variables, read here, override tuning choices and never change results:
+ * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel; raised where the
+ * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least) and
+ * MORPHKV_CACHE_BUDGET_MB (bf16 caches; default 208: how much of the handle's K/V is read with ordinary loads
+ * and so stays in the device's 256 MB memory-side cache from step to step; the rest is streamed with
+ * non-temporal loads that leave that cache alone). */
 int morphkv_create(morphkv_handle **h, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch);
 int morphkv_destroy(morphkv_handle *h);
 
@@ -165,27 +168,6 @@ int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, v
 int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream);
 /* evicted [U][evict_every] int32 device: every position evicted by the last decode step, -1 padded. */
 int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *stream);
-
-/* Optional capture of the fused scores each decode step takes its decision on:
- * F device [U][Cs+1] fp32 (slot order; [Cs] = the token leaving the window), or NULL to stop.
- * Costs 4 bytes written per older token per step while enabled. */
-int morphkv_capture_scores(morphkv_handle *h, float *F);
-
-/* Diagnostics: clocks device [U][8] int64, or NULL to stop.  While set, every decode step stores the
- * constant-rate device clock (100 MHz) per unit at: 0 kernel start, 1 end of the K pass, 2 end of
- * softmax/record, 3 end of the V pass, 4 end of the step, 5 / 6 last / first wave reaches the first
- * barrier, 7 first barrier passed. */
-int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks);
-
-/* Diagnostics: a plain device-to-device copy of `bytes` (multiple of 16) with a grid-stride kernel,
- * enqueued on the stream.  It moves a known number of bytes each way and serves as the yardstick the
- * profiler's HBM counters are scaled by. */
-int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/* Diagnostics: a plain read of `bytes` (multiple of 16) of device memory; every 16-byte piece is loaded once and
- * folded into sink[256] (device, uint32, xor-accumulated: zero it first if the value matters).  Times what the
- * device sustains when a kernel only streams: the practical ceiling next to the 8 TB/s of the data sheet. */
-int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream);
 
 const char *morphkv_last_error(void);
 

@@ -1,15 +1,17 @@
-"""Builds libmorphkv.so (HIP, gfx950) in-tree with hipcc."""
+"""Builds libmorphkv.so (HIP, gfx950) in-tree with hipcc: one object per translation unit, compiled in parallel."""
 from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
+OBJ = os.path.join(CSRC, "_build")
 LIB_PATH = os.path.join(_HERE, "libmorphkv.so")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -17,32 +19,51 @@ HIPCC_FLAGS = [
 
 
 def sources():
-    return [os.path.join(CSRC, "morphkv.hip")]
+    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def needs_build() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(_HERE, "..", "include", "morphkv.h")]
+    inc = os.path.join(_HERE, "..", "include")
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
+    deps += [os.path.join(inc, f) for f in os.listdir(inc)]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def _compile(hipcc, src, verbose):
+    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-c", "-o", obj, src]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, cwd=CSRC, stderr=subprocess.PIPE, text=True)
+    return src, obj, r.returncode, r.stderr
+
+
+def build(force: bool = True, verbose: bool = False, jobs: int = 8) -> str:
     if not force and not needs_build():
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", LIB_PATH] + sources()
+    os.makedirs(OBJ, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
+        results = list(ex.map(lambda s: _compile(hipcc, s, verbose), sources()))
+    spilling = []
+    for src, _, rc, err in results:
+        if rc != 0:
+            raise RuntimeError(f"hipcc failed on {os.path.basename(src)}:\n" + err[-4000:])
+        spilling += scratch_users(err)
+    if spilling:
+        if os.path.exists(LIB_PATH):
+            os.remove(LIB_PATH)
+        raise RuntimeError("kernels that spill vector registers to scratch (not allowed, see csrc/decode.h): "
+                           + ", ".join(f"{k} ({b} B/lane)" for k, b in spilling))
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", LIB_PATH] + [o for _, o, _, _ in results]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, cwd=CSRC, stderr=subprocess.PIPE, text=True)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stderr[-4000:])
-    spilling = scratch_users(r.stderr)
-    if spilling:
-        os.remove(LIB_PATH)
-        raise RuntimeError("kernels that spill vector registers to scratch (not allowed, see csrc/decode.h): "
-                           + ", ".join(f"{k} ({b} B/lane)" for k, b in spilling))
+        raise RuntimeError("link failed:\n" + r.stderr[-4000:])
     return LIB_PATH
 
 

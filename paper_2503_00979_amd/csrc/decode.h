@@ -46,8 +46,11 @@ struct DecodeParams {
   int32_t C, T;            // older tokens kept by a selection; selection every T steps (Appendix A.5), Cs = C+T-1
   int32_t *evl;            // [U][T] positions evicted by the last step, -1 padded
   int32_t zig;             // parity of the step count: direction of the walk over the cache
-  int32_t u0;              // first unit of the launch (a launch may cover one layer's units only);
-                           // q, k_new, v_new and out are addressed by the unit's index within the whole model
+  int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
+                           // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
+  int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)
+  int32_t io_u0;           // unit whose rows come first in q, k_new, v_new and out (u0 when the step's tensors
+                           // are one layer's own, 0 when they cover the whole model)
   float scale_log2;        // softmax scale * log2(e)
 };
 
@@ -101,6 +104,25 @@ inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, 
 
 __device__ inline bool slot_valid(int j, int n_snap, int Cs, int nwin) {
   return j < n_snap || (j >= Cs && j < Cs + nwin);
+}
+
+// 16-byte global load; STREAM: with the non-temporal hint (the line is not kept in the caches it passes)
+template <bool STREAM> __device__ inline uint4 ldg16(const void *p) {
+  if constexpr (STREAM) {
+    typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+    const u4v t = __builtin_nontemporal_load((const u4v *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+  } else {
+    return *(const uint4 *)p;
+  }
+}
+
+// 16-byte global store with the non-temporal hint: for data this launch does not read again (the recorded row,
+// the running aggregates), so that it leaves the L2 as it is written instead of in a burst when the kernel ends
+__device__ inline void stg16_stream(float *p, float4 v) {
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  const f4v t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, (f4v *)p);
 }
 
 // workgroup barrier that orders LDS traffic only: outstanding global loads/stores stay in flight
@@ -289,7 +311,206 @@ __device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion
   }
 }
 
-template <typename T, int D, int G>
+// ---- the end of a step, shared by the fused kernel and the merging workgroup of the split kernel -------------
+// Everything the two functions below need of a workgroup's state.  LDS arrays (see the carve-up in the kernels):
+//   sh  [16] 2: dest slot of the token leaving the window (-1: none), 3: evicted position, 4: new n_snap,
+//            5: a selection among more than C+1 candidates is due, 6: movers
+//   shf [16] 9: fused score of the token leaving the window
+//   Fl, Pl [CsP] fused score and position per older-token slot, colw [NW][R], lists [2][T], best2 [2][3][16] (T > 1 only)
+//   colv [R] column of the token leaving the window, oldest row first
+template <typename T> struct StepTail {
+  const DecodeParams &P;
+  int u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w;
+  bool cum;
+  int fusion, Tev;
+  int *sh;
+  float *shf, *Fl;
+  int *Pl;
+  float *colw;
+  int *lists;
+  float *best2, *colv, *ringu, *sfxu, *nwu;
+  int32_t *posu;
+  const T *knew, *vnew;
+};
+
+template <typename T, int D>
+__device__ __forceinline__ void coarse_select_and_move(const StepTail<T> &c) {
+  const DecodeParams &P = c.P;
+  const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane;
+  const int Cs = c.Cs, CsP = c.CsP, R = c.R, n_pad = c.n_pad, cps = c.cps, n_snap = c.n_snap, p = c.p, w = c.w;
+  const bool cum = c.cum;
+  const int fusion = c.fusion, Tev = c.Tev;
+  int *sh = c.sh;
+  float *shf = c.shf, *Fl = c.Fl, *colw = c.colw, *best2 = c.best2, *colv = c.colv;
+  int *Pl = c.Pl, *lists = c.lists;
+  float *ringu = c.ringu, *sfxu = c.sfxu, *nwu = c.nwu;
+  int32_t *posu = c.posu;
+  const T *knew = c.knew, *vnew = c.vnew;
+  using L = Layout<T, D>;
+  constexpr int EPL = Elem<T>::EPL;
+  (void)NW; (void)cps; (void)n_snap; (void)cum; (void)fusion; (void)Fl; (void)Pl; (void)colw; (void)best2; (void)lists;
+  (void)colv; (void)sfxu; (void)nwu; (void)ringu; (void)knew; (void)vnew; (void)shf; (void)CsP; (void)lane; (void)wave;
+  // ---- selection of the C best of up to C+T older tokens (Eq.7 with the coarse schedule of Appendix A.5):
+  // the n_snap+1-C candidates with the smallest scores go (ties: the higher position goes), survivors
+  // beyond slot C and the token leaving the window move into the freed slots below C.
+  if (Tev > 1) {
+    int32_t *evl = P.evl + (size_t)u * Tev;
+    const int n_ev = sh[5] ? n_snap + 1 - P.C : 0;  // 1..T at a selection step
+    if (tid >= n_ev && tid < Tev) evl[tid] = -1;
+    if (n_ev > 0) {
+      int *hole = lists, *msrc = lists + Tev;
+      const int wsl = Cs + w;
+      // n_ev rounds, each taking out the candidate that goes first.  Every wave works the round's result out
+      // for itself from the per-wave minima (two sets, used in turn: one barrier per round); slot j is read
+      // and, once taken, struck out by thread j mod NT only.
+      float fd = shf[9];  // score of the token leaving the window; +inf once it has been taken
+      int nh = 0;         // slots below C freed so far
+      for (int it = 0; it < n_ev; ++it) {
+        float f = INFINITY;
+        int bp = -1, bc = -1;
+        for (int j = tid; j < n_snap; j += NT) {
+          const float F = Fl[j];
+          const int pj = Pl[j];
+          if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
+        }
+        wave_argmin(f, bp, bc);
+        float *bF = best2 + (it & 1) * 48;
+        int *bPp = (int *)bF + 16, *bCc = (int *)bF + 32;
+        if (lane == 0) { bF[wave] = f; bPp[wave] = bp; bCc[wave] = bc; }
+        lds_barrier();
+        f = INFINITY; bp = -1; bc = -1;
+        if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
+        wave_argmin(f, bp, bc);
+        if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; fd = INFINITY; }
+        else if (bc % NT == tid) Fl[bc] = INFINITY;
+        if (tid == 0) {
+          evl[it] = bp;
+          if (it == 0) sh[3] = bp;
+          if (bc < P.C) hole[nh] = bc;
+        }
+        nh += bc < P.C;
+      }
+      lds_barrier();  // the last round's strike-out is visible
+      // movers = survivors at or above C, then the token leaving the window: as many as slots freed below C,
+      // at most T, listed by one wave
+      if (wave == 0) {
+        const int j = P.C + lane;  // n_snap - C <= T - 1 <= 63 candidates above C, then the window token
+        const bool mover = j < n_snap ? Fl[j] != INFINITY : (j == n_snap && fd != INFINITY);
+        const unsigned long long m = __ballot(mover);
+        if (mover) msrc[__popcll(m & ((1ull << lane) - 1ull))] = j < n_snap ? j : wsl;
+        if (lane == 0) sh[6] = nh;
+      }
+      __syncthreads();
+      const int nm = sh[6];
+      T *Kx = (T *)P.K + (size_t)u * n_pad * D;
+      T *Vx = (T *)P.V + (size_t)u * n_pad * D;
+      for (int m = wave; m < nm; m += NW) {
+        const int src = msrc[m], dst = hole[m];
+        float *cb = colw + (size_t)wave * R;
+        for (int a = lane; a < R; a += WAVE) {
+          int r = w + 1 + a;
+          r -= r >= R ? R : 0;
+          const float x = ringu[(size_t)r * n_pad + src];
+          cb[a] = x;
+          ringu[(size_t)r * n_pad + dst] = x;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+        if (cum && src != wsl) {
+          // a running sum reaches further back than the R rows: it moves with the token (the record phase's
+          // store of nw[src] is visible since the barrier after the V pass)
+          if (lane == 0) nwu[dst] = nwu[src];
+        } else {
+          move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP,
+                         nwu + dst);
+        }
+        constexpr int PCSx = D / EPL;
+        if (lane < PCSx) *(uint4 *)(Kx + L::k_off(dst, lane * EPL)) = *(const uint4 *)(Kx + L::k_off(src, lane * EPL));
+        if constexpr (L::tiled) {
+          for (int ch = lane; ch < D; ch += WAVE) ((uint16_t *)Vx)[L::v_off(dst, ch)] = ((const uint16_t *)Vx)[L::v_off(src, ch)];
+        } else {
+          if (lane < PCSx) *(uint4 *)(Vx + L::v_off(dst, lane * EPL)) = *(const uint4 *)(Vx + L::v_off(src, lane * EPL));
+        }
+        if (lane == 0) posu[dst] = src == wsl ? p - R : Pl[src];
+      }
+      __syncthreads();  // movers have read their sources before slots are cleared / the window slot is rewritten
+      for (int j = P.C + tid; j < Cs; j += NT) posu[j] = -1;
+    }
+  }
+}
+
+template <typename T, int D, bool CLK>
+__device__ __forceinline__ void compact_and_commit(const StepTail<T> &c) {
+  const DecodeParams &P = c.P;
+  const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane;
+  const int Cs = c.Cs, CsP = c.CsP, R = c.R, n_pad = c.n_pad, cps = c.cps, n_snap = c.n_snap, p = c.p, w = c.w;
+  const bool cum = c.cum;
+  const int fusion = c.fusion, Tev = c.Tev;
+  int *sh = c.sh;
+  float *shf = c.shf, *Fl = c.Fl, *colw = c.colw, *best2 = c.best2, *colv = c.colv;
+  int *Pl = c.Pl, *lists = c.lists;
+  float *ringu = c.ringu, *sfxu = c.sfxu, *nwu = c.nwu;
+  int32_t *posu = c.posu;
+  const T *knew = c.knew, *vnew = c.vnew;
+  using L = Layout<T, D>;
+  constexpr int EPL = Elem<T>::EPL;
+  (void)NW; (void)cps; (void)n_snap; (void)cum; (void)fusion; (void)Fl; (void)Pl; (void)colw; (void)best2; (void)lists;
+  (void)colv; (void)sfxu; (void)nwu; (void)ringu; (void)knew; (void)vnew; (void)shf; (void)CsP; (void)lane; (void)wave;
+  // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot
+  const int dest = sh[2];
+  const int wslot = Cs + w;
+  T *Kw_ = (T *)P.K + (size_t)u * n_pad * D;
+  T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
+  constexpr int PCS = D / EPL;  // 16-byte pieces per row
+  if (tid < PCS) {              // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
+    const int ch0 = tid * EPL;
+    uint4 *src = (uint4 *)(Kw_ + L::k_off(wslot, ch0));
+    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = *src;
+    *src = ((const uint4 *)knew)[tid];
+  }
+  if constexpr (L::tiled) {
+    // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
+    for (int ch = NT - 1 - tid; ch < D; ch += NT) {
+      uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
+      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = *src;
+      *src = ((const uint16_t *)vnew)[ch];
+    }
+  } else {
+    if (tid >= 64 && tid < 64 + PCS) {
+      const int ch0 = (tid - 64) * EPL;
+      uint4 *src = (uint4 *)(Vw_ + L::v_off(wslot, ch0));
+      if (dest >= 0) *(uint4 *)(Vw_ + L::v_off(dest, ch0)) = *src;
+      *src = ((const uint4 *)vnew)[tid - 64];
+    }
+  }
+  if (dest >= 0) {
+    if (wave == NW - 1) {
+      if (lane == 0) posu[dest] = p - R;
+      move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP,
+                     nwu + dest);
+    } else {
+      const int stride = NT - WAVE;
+      int r = (w + 1 + tid) % R;
+      for (int a = tid; a < R; a += stride) {
+        ringu[(size_t)r * n_pad + dest] = colv[a];
+        r += stride;
+        while (r >= R) r -= R;
+      }
+    }
+  }
+  if (tid == 0) {
+    posu[wslot] = p;
+    int32_t *m = P.meta + (size_t)u * META;
+    m[0] = sh[4];
+    m[1] = p + 1;
+    m[2] = sh[3];
+    m[3] = w + 1 == R ? 0 : w + 1;
+    if (CLK && P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
+  }
+}
+
+// CLK: the diagnostics build that stores phase time stamps to P.dbgT; the product build carries none of it
+template <typename T, int D, int G, bool CLK>
 __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
@@ -335,7 +556,8 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
-  const T *qb = (const T *)P.q + (size_t)u * G * D;  // query heads of unit u are rows u*G .. u*G+G-1
+  const int uio = u - P.io_u0;                          // the unit's index within the step's tensors
+  const T *qb = (const T *)P.q + (size_t)uio * G * D;   // query heads of the unit are rows uio*G .. uio*G+G-1
   // The cache is walked forwards on even steps and backwards on odd ones: what the previous step read
   // last is read first, so the part of K/V that still sits in the memory-side cache is hit instead of
   // being pushed out by the stream just ahead of its use.
@@ -355,12 +577,23 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   [[maybe_unused]] const int kntile = n_pad / 16, kngrp = (kntile + TU - 1) / TU;
   auto load_kgroup = [&](uint4 (&dst)[TU][KBc], int grp) {
     const int gidx = zig ? kngrp - 1 - grp : grp;
+    if (gidx < P.nt_k) {
 #pragma unroll
-    for (int t = 0; t < TU; ++t) {
-      const int tile = gidx * TU + t;
-      if (tile < kntile) {
+      for (int t = 0; t < TU; ++t) {
+        const int tile = gidx * TU + t;
+        if (tile < kntile) {
 #pragma unroll
-        for (int kb = 0; kb < KBc; ++kb) dst[t][kb] = *(const uint4 *)(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
+          for (int kb = 0; kb < KBc; ++kb) dst[t][kb] = ldg16<true>(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < TU; ++t) {
+        const int tile = gidx * TU + t;
+        if (tile < kntile) {
+#pragma unroll
+          for (int kb = 0; kb < KBc; ++kb) dst[t][kb] = ldg16<false>(Kb + ((size_t)tile * KBc + kb) * 512 + lane * 8);
+        }
       }
     }
   };
@@ -386,11 +619,11 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   float *sfxu = P.sfx + (size_t)u * R * CsP;
   float *nwu = P.nw + (size_t)u * CsP;
   int32_t *posu = P.pos + (size_t)u * n_pad;
-  const T *knew = (const T *)P.k_new + (size_t)u * D;
-  const T *vnew = (const T *)P.v_new + (size_t)u * D;
+  const T *knew = (const T *)P.k_new + (size_t)uio * D;
+  const T *vnew = (const T *)P.v_new + (size_t)uio * D;
 
   if (tid == 0) sh[0] = 2 * NW;  // every wave starts on the tile groups wave and wave + NW
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 0] = wall_clock64();
 
   // ---- prefetch of the per-column state this thread will update after the softmax (4 columns a group)
   const int nq = n_pad / 4;
@@ -489,10 +722,10 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     if (wave < kngrp) process_kgroup(ka[0], wave);
     if (wave + NW < kngrp) load_kgroup(ka[0], wave + NW);
   }
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
-  if (P.dbgT && tid == NT - 64) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 6] = wall_clock64();
+  if (CLK && P.dbgT && tid == NT - 64) P.dbgT[(size_t)u * 8 + 5] = wall_clock64();
   lds_barrier();  // the tile counter is initialised
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
 
   // ---- the last waves first rebuild the columns whose turn it is, then join the K pass
   if (wave >= NW - nrw) {
@@ -609,8 +842,13 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   [[maybe_unused]] uint4 vbuf[VBUF][L::CB];
   auto load_vtile = [&](uint4 (&dst)[L::CB], int ti) {
     const int tile = zig ? n_pad / 32 - 1 - ti : ti;
+    if (tile < P.nt_v) {
 #pragma unroll
-    for (int cb = 0; cb < L::CB; ++cb) dst[cb] = *(const uint4 *)(Vb + ((size_t)tile * L::CB + cb) * 512 + lane * 8);
+      for (int cb = 0; cb < L::CB; ++cb) dst[cb] = ldg16<true>(Vb + ((size_t)tile * L::CB + cb) * 512 + lane * 8);
+    } else {
+#pragma unroll
+      for (int cb = 0; cb < L::CB; ++cb) dst[cb] = ldg16<false>(Vb + ((size_t)tile * L::CB + cb) * 512 + lane * 8);
+    }
   };
   if constexpr (L::tiled) {
 #pragma unroll
@@ -618,7 +856,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       if (wave + b * NW < n_pad / 32) load_vtile(vbuf[b], wave + b * NW);
   }
   lds_barrier();
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 1] = wall_clock64();
 
   if constexpr (L::tiled) {
 #pragma unroll
@@ -685,7 +923,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       *pl = l;
       S[0] += l.x; S[1] += l.y; S[2] += l.z; S[3] += l.w;
     }
-    *(float4 *)(ringu + (size_t)w * n_pad + j0) = make_float4(S[0], S[1], S[2], S[3]);
+    stg16_stream(ringu + (size_t)w * n_pad + j0, make_float4(S[0], S[1], S[2], S[3]));
     if (j0 < n_snap) {
       float nwo[4] = {nw_old.x, nw_old.y, nw_old.z, nw_old.w};
       const float sfo[4] = {sfx_old.x, sfx_old.y, sfx_old.z, sfx_old.w};
@@ -703,7 +941,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
           if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         }
       }
-      *(float4 *)(nwu + j0) = make_float4(nwo[0], nwo[1], nwo[2], nwo[3]);
+      stg16_stream(nwu + j0, make_float4(nwo[0], nwo[1], nwo[2], nwo[3]));
     }
     if (Cs + w >= j0 && Cs + w < j0 + 4) {
       const int i = Cs + w - j0;
@@ -744,7 +982,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     }
   }
   lds_barrier();
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 2] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 2] = wall_clock64();
 
   // ---- decision (wave 0, before its share of the V pass): needs only the scores
   if (wave == 0) {
@@ -893,7 +1131,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
         for (int e = 0; e < EPL; ++e) lg[(size_t)(wave * G + g) * D + chunk * EPL + e] = acc[g][e];
     }
   }
-  if (P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
+  if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
   // full barrier: besides the output partials in LDS, every global store of the record phase has landed
   // before the compaction below rewrites some of the same addresses (ring[w][dest], nw[dest], sfx[.][dest])
   __syncthreads();
@@ -910,148 +1148,14 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) psg = gg == g ? pself[gg] : psg;
     o = fmaf(psg, vn, o);
-    P.out[((size_t)u * G + g) * D + ch] = o;
+    P.out[((size_t)uio * G + g) * D + ch] = o;
   }
 
-  // ---- selection of the C best of up to C+T older tokens (Eq.7 with the coarse schedule of Appendix A.5):
-  // the n_snap+1-C candidates with the smallest scores go (ties: the higher position goes), survivors
-  // beyond slot C and the token leaving the window move into the freed slots below C.
-  if (Tev > 1) {
-    int32_t *evl = P.evl + (size_t)u * Tev;
-    const int n_ev = sh[5] ? n_snap + 1 - P.C : 0;  // 1..T at a selection step
-    if (tid >= n_ev && tid < Tev) evl[tid] = -1;
-    if (n_ev > 0) {
-      int *hole = lists, *msrc = lists + Tev;
-      const int wsl = Cs + w;
-      // n_ev rounds, each taking out the candidate that goes first.  Every wave works the round's result out
-      // for itself from the per-wave minima (two sets, used in turn: one barrier per round); slot j is read
-      // and, once taken, struck out by thread j mod NT only.
-      float fd = shf[9];  // score of the token leaving the window; +inf once it has been taken
-      int nh = 0;         // slots below C freed so far
-      for (int it = 0; it < n_ev; ++it) {
-        float f = INFINITY;
-        int bp = -1, bc = -1;
-        for (int j = tid; j < n_snap; j += NT) {
-          const float F = Fl[j];
-          const int pj = Pl[j];
-          if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
-        }
-        wave_argmin(f, bp, bc);
-        float *bF = best2 + (it & 1) * 48;
-        int *bPp = (int *)bF + 16, *bCc = (int *)bF + 32;
-        if (lane == 0) { bF[wave] = f; bPp[wave] = bp; bCc[wave] = bc; }
-        lds_barrier();
-        f = INFINITY; bp = -1; bc = -1;
-        if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
-        wave_argmin(f, bp, bc);
-        if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; fd = INFINITY; }
-        else if (bc % NT == tid) Fl[bc] = INFINITY;
-        if (tid == 0) {
-          evl[it] = bp;
-          if (it == 0) sh[3] = bp;
-          if (bc < P.C) hole[nh] = bc;
-        }
-        nh += bc < P.C;
-      }
-      lds_barrier();  // the last round's strike-out is visible
-      // movers = survivors at or above C, then the token leaving the window: as many as slots freed below C,
-      // at most T, listed by one wave
-      if (wave == 0) {
-        const int j = P.C + lane;  // n_snap - C <= T - 1 <= 63 candidates above C, then the window token
-        const bool mover = j < n_snap ? Fl[j] != INFINITY : (j == n_snap && fd != INFINITY);
-        const unsigned long long m = __ballot(mover);
-        if (mover) msrc[__popcll(m & ((1ull << lane) - 1ull))] = j < n_snap ? j : wsl;
-        if (lane == 0) sh[6] = nh;
-      }
-      __syncthreads();
-      const int nm = sh[6];
-      T *Kx = (T *)P.K + (size_t)u * n_pad * D;
-      T *Vx = (T *)P.V + (size_t)u * n_pad * D;
-      for (int m = wave; m < nm; m += NW) {
-        const int src = msrc[m], dst = hole[m];
-        float *cb = colw + (size_t)wave * R;
-        for (int a = lane; a < R; a += WAVE) {
-          int r = w + 1 + a;
-          r -= r >= R ? R : 0;
-          const float x = ringu[(size_t)r * n_pad + src];
-          cb[a] = x;
-          ringu[(size_t)r * n_pad + dst] = x;
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_wave_barrier();
-        if (cum && src != wsl) {
-          // a running sum reaches further back than the R rows: it moves with the token (the record phase's
-          // store of nw[src] is visible since the barrier after the V pass)
-          if (lane == 0) nwu[dst] = nwu[src];
-        } else {
-          move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP,
-                         nwu + dst);
-        }
-        constexpr int PCSx = D / EPL;
-        if (lane < PCSx) *(uint4 *)(Kx + L::k_off(dst, lane * EPL)) = *(const uint4 *)(Kx + L::k_off(src, lane * EPL));
-        if constexpr (L::tiled) {
-          for (int ch = lane; ch < D; ch += WAVE) ((uint16_t *)Vx)[L::v_off(dst, ch)] = ((const uint16_t *)Vx)[L::v_off(src, ch)];
-        } else {
-          if (lane < PCSx) *(uint4 *)(Vx + L::v_off(dst, lane * EPL)) = *(const uint4 *)(Vx + L::v_off(src, lane * EPL));
-        }
-        if (lane == 0) posu[dst] = src == wsl ? p - R : Pl[src];
-      }
-      __syncthreads();  // movers have read their sources before slots are cleared / the window slot is rewritten
-      for (int j = P.C + tid; j < Cs; j += NT) posu[j] = -1;
-    }
-  }
-
-  // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot
-  const int dest = sh[2];
-  const int wslot = Cs + w;
-  T *Kw_ = (T *)P.K + (size_t)u * n_pad * D;
-  T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
-  constexpr int PCS = D / EPL;  // 16-byte pieces per row
-  if (tid < PCS) {              // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
-    const int ch0 = tid * EPL;
-    uint4 *src = (uint4 *)(Kw_ + L::k_off(wslot, ch0));
-    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = *src;
-    *src = ((const uint4 *)knew)[tid];
-  }
-  if constexpr (L::tiled) {
-    // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
-    for (int ch = NT - 1 - tid; ch < D; ch += NT) {
-      uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
-      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = *src;
-      *src = ((const uint16_t *)vnew)[ch];
-    }
-  } else {
-    if (tid >= 64 && tid < 64 + PCS) {
-      const int ch0 = (tid - 64) * EPL;
-      uint4 *src = (uint4 *)(Vw_ + L::v_off(wslot, ch0));
-      if (dest >= 0) *(uint4 *)(Vw_ + L::v_off(dest, ch0)) = *src;
-      *src = ((const uint4 *)vnew)[tid - 64];
-    }
-  }
-  if (dest >= 0) {
-    if (wave == NW - 1) {
-      if (lane == 0) posu[dest] = p - R;
-      move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP,
-                     nwu + dest);
-    } else {
-      const int stride = NT - WAVE;
-      int r = (w + 1 + tid) % R;
-      for (int a = tid; a < R; a += stride) {
-        ringu[(size_t)r * n_pad + dest] = colv[a];
-        r += stride;
-        while (r >= R) r -= R;
-      }
-    }
-  }
-  if (tid == 0) {
-    posu[wslot] = p;
-    int32_t *m = P.meta + (size_t)u * META;
-    m[0] = sh[4];
-    m[1] = p + 1;
-    m[2] = sh[3];
-    m[3] = w + 1 == R ? 0 : w + 1;
-    if (P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
-  }
+  // ---- selection among more than C+1 candidates (coarse schedule), compaction, commit: shared with the split kernel
+  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w, cum, fusion, Tev,
+                 sh, shf, Fl, Pl, colw, lists, best2, colv, ringu, sfxu, nwu, posu, knew, vnew};
+  coarse_select_and_move<T, D>(tc);
+  compact_and_commit<T, D, CLK>(tc);
 }
 
 // Register budgets.  The compiler version this is built with places spill stores at the top of the block
@@ -1059,13 +1163,13 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 // there is lost for waves that skipped the branch (seen: the fp32 d=64 G=8 build moved only 16 of a key's 256
 // bytes at compaction).  So no build may spill vector registers: the bf16 builds fit 128 registers (1024-thread
 // groups); the fp32 builds, which keep G x 4 products per lane in flight, get 256 (groups of at most 512).
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool CLK = false>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
-  decode_fused_body<T, D, G>(P);
+  decode_fused_body<T, D, G, CLK>(P);
 }
 template <typename T, int D, int G>
 __global__ __launch_bounds__(512) void decode_fused_kernel_512(DecodeParams P) {
-  decode_fused_body<T, D, G>(P);
+  decode_fused_body<T, D, G, false>(P);
 }
 
 }  // namespace mkv

@@ -1,6 +1,7 @@
 // C-ABI of libmorphkv (see include/morphkv.h): argument checks, buffer carve-up, kernel launches.
 // Host code only enqueues work on the caller's stream; all device memory is the caller's.
 #include "../../include/morphkv.h"
+#include "../../include/morphkv_diag.h"
 
 #include <hip/hip_runtime.h>
 
@@ -14,18 +15,19 @@
 #include <mutex>
 #include <new>
 
-#include "common.h"
+#include "host.h"
 #include "decode.h"
 #include "prefill.h"
 #include "prompt_attn.h"
+#include "misc_kernels.h"
 
 using namespace mkv;
 
 namespace {
-
 thread_local char g_err[512] = "";
+}  // namespace
 
-int fail(int code, const char *fmt, ...) {
+int mkv::fail(int code, const char *fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
@@ -33,11 +35,7 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
-#define HIP_TRY(expr)                                                                       \
-  do {                                                                                      \
-    hipError_t e_ = (expr);                                                                 \
-    if (e_ != hipSuccess) return fail(MORPHKV_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
-  } while (0)
+namespace {
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -191,6 +189,7 @@ struct morphkv_handle {
   int n_cu;
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
+  int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
 };
 
 namespace {
@@ -211,6 +210,8 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.C = h->cfg.C; P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.evl = (int32_t *)(h->cache + L.offEvl);
   P.zig = (int32_t)(h->steps & 1u);
+  P.nt_k = h->nt_k;
+  P.nt_v = h->nt_v;
   P.cpt_shift = -1;
   for (int sft = 0; sft < 16; ++sft)
     if ((1 << sft) == L.cpt) P.cpt_shift = sft;
@@ -248,7 +249,12 @@ PrefillParams prefill_params(const morphkv_handle *h, char *scratch_base, const 
 // threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
 // over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
 int decode_threads(const morphkv_handle *h, int U) {
-  if (h->force_threads) return h->force_threads == 128 && h->cfg.R > 512 ? 256 : h->force_threads;
+  if (h->force_threads) {
+    // a thread keeps at most 4 of the R-1 rows of the leaving token's column: the override is raised until they fit
+    int nt = h->force_threads;
+    while (4 * nt < h->cfg.R - 1 && nt < 1024) nt += 64;
+    return nt;
+  }
   const int cu = h->n_cu > 0 ? h->n_cu : 256;
   // (a thread keeps at most 4 of the R-1 rows of the leaving token's column: groups of 128 need R <= 512)
   if (U >= 8 * cu && h->cfg.R <= 512) return 128;
@@ -259,144 +265,53 @@ int decode_threads(const morphkv_handle *h, int U) {
   return h->L.n_pad < 1024 ? 512 : 1024;
 }
 
-template <typename T, int D, int G>
-int launch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
-  constexpr bool wide = !Layout<T, D>::tiled;  // fp32 builds: 256 registers a lane, groups of at most 512 threads
-  int NT = decode_threads(h, n_units);
-  if (wide && NT > 512) NT = 512;
-  size_t lds = decode_lds_bytes(P.n_pad, G, D, NT, P.R, P.cps, P.CsP, P.T);
-  if (lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, lds);
-  if (h->min_lds > lds && h->min_lds <= 160 * 1024) lds = h->min_lds;
-  void (*kern)(DecodeParams);
-  if constexpr (wide) kern = decode_fused_kernel_512<T, D, G>;
-  else kern = decode_fused_kernel<T, D, G>;
-  // (the kernel's dynamic-LDS limit was raised when the handle was made, on the device current then)
-  hipLaunchKernelGGL(kern, dim3(n_units), dim3(NT), lds, st, P);
-  HIP_TRY(hipGetLastError());
-  return MORPHKV_OK;
-}
-
-// raises the decode kernel's dynamic-LDS limit for this handle's configuration (once, at creation: not inside a
-// launch, which may be under stream capture)
-template <typename T, int D, int G>
-int set_decode_lds_limit(size_t lds) {
-  void (*kern)(DecodeParams);
-  if constexpr (!Layout<T, D>::tiled) kern = decode_fused_kernel_512<T, D, G>;
-  else kern = decode_fused_kernel<T, D, G>;
-  static size_t limit = 0;  // per kernel build; only ever raised (another handle may need the larger value)
-  if (lds > limit) {
-    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    limit = lds;
-  }
-  return MORPHKV_OK;
-}
-
-template <typename T, int D, int G>
-int launch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
-  const int U = h->L.U;
-  constexpr bool mfma = Layout<T, D>::tiled;
-  const int nblk = (P.Nmax + PF_BLOCK - 1) / PF_BLOCK;
-  if constexpr (mfma) {
-    if (P.lse) {
-      hipLaunchKernelGGL((prefill_stats_from_lse_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P);
-      HIP_TRY(hipGetLastError());
-    } else {
-      hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_STATS>), dim3(nblk, U), dim3(256), 0, st, P);
-      HIP_TRY(hipGetLastError());
-      hipLaunchKernelGGL((prefill_stats_merge_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P, nblk);
-      HIP_TRY(hipGetLastError());
-    }
-    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_FUSE>), dim3(nblk, U), dim3(256), 0, st, P);
-    HIP_TRY(hipGetLastError());
-  } else {
-    hipLaunchKernelGGL((prefill_rows_kernel<T, D, G>), dim3(P.R, U), dim3(256), 0, st, P);
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(prefill_fuse_kernel, dim3((P.Nmax + 255) / 256, U), dim3(256), 0, st, P);
-    HIP_TRY(hipGetLastError());
-  }
-  hipLaunchKernelGGL(prefill_select_kernel, dim3(U), dim3(1024), 0, st, P);
-  HIP_TRY(hipGetLastError());
-  if constexpr (mfma) {
-    hipLaunchKernelGGL((prefill_gather_tiled_kernel<D>), dim3(P.n_pad / 32, U), dim3(256), 0, st, P);
-  } else {
-    constexpr int SPB = 256 / (2 * (D / Elem<T>::EPL));
-    hipLaunchKernelGGL((prefill_gather_kernel<T, D>), dim3((P.n_pad + SPB - 1) / SPB, U), dim3(256), 0, st, P);
-  }
-  HIP_TRY(hipGetLastError());
-  if constexpr (mfma)
-    hipLaunchKernelGGL((prefill_pass_kernel<D, G, PF_RING>), dim3((P.n_pad + PF_BLOCK - 1) / PF_BLOCK, U), dim3(256),
-                       0, st, P);
-  else
-    hipLaunchKernelGGL(prefill_ring_kernel, dim3((P.n_pad + 255) / 256, U), dim3(256), 0, st, P);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(prefill_state_kernel, dim3((P.CsP + 255) / 256, U), dim3(256), 0, st, P);
-  HIP_TRY(hipGetLastError());
-  return MORPHKV_OK;
-}
-
-// dispatch over (dtype, head_dim, group size)
-#define MKV_DISPATCH_G(FN, T, D, G, ...)                                      \
-  switch (G) {                                                                \
-    case 1: return FN<T, D, 1>(__VA_ARGS__);                                  \
-    case 2: return FN<T, D, 2>(__VA_ARGS__);                                  \
-    case 3: return FN<T, D, 3>(__VA_ARGS__);                                  \
-    case 4: return FN<T, D, 4>(__VA_ARGS__);                                  \
-    case 5: return FN<T, D, 5>(__VA_ARGS__);                                  \
-    case 6: return FN<T, D, 6>(__VA_ARGS__);                                  \
-    case 7: return FN<T, D, 7>(__VA_ARGS__);                                  \
-    case 8: return FN<T, D, 8>(__VA_ARGS__);                                  \
-    default: return fail(MORPHKV_EINVAL, "group size %d not supported", G);   \
-  }
-
-#define MKV_DISPATCH(FN, h, ...)                                              \
-  do {                                                                        \
-    const int G_ = (h)->L.G, D_ = (h)->cfg.head_dim;                          \
-    if ((h)->cfg.dtype == MORPHKV_DTYPE_BF16) {                               \
-      if (D_ == 128) { MKV_DISPATCH_G(FN, bf16_t, 128, G_, __VA_ARGS__) }     \
-      else { MKV_DISPATCH_G(FN, bf16_t, 64, G_, __VA_ARGS__) }                \
-    } else {                                                                  \
-      if (D_ == 128) { MKV_DISPATCH_G(FN, float, 128, G_, __VA_ARGS__) }      \
-      else { MKV_DISPATCH_G(FN, float, 64, G_, __VA_ARGS__) }                 \
-    }                                                                         \
-  } while (0)
-
 int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
-  MKV_DISPATCH(launch_decode, h, h, P, n_units, st);
-}
-int dispatch_lds_limit(const morphkv_handle *h, size_t lds) { MKV_DISPATCH(set_decode_lds_limit, h, lds); }
-int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
-  MKV_DISPATCH(launch_prefill, h, h, P, st);
+  const bool f32 = h->cfg.dtype == MORPHKV_DTYPE_F32;
+  const int G = h->L.G, D = h->cfg.head_dim;
+  DecodeLaunch L{};
+  L.n_units = n_units;
+  L.threads = decode_threads(h, n_units);
+  if (f32 && L.threads > 512) L.threads = 512;  // fp32 builds: 256 registers a lane, groups of at most 512 threads
+  L.lds = decode_lds_bytes(P.n_pad, G, D, L.threads, P.R, P.cps, P.CsP, P.T);
+  if (L.lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, L.lds);
+  if (h->min_lds > L.lds && h->min_lds <= 160 * 1024) L.lds = h->min_lds;
+  L.clocks = P.dbgT != nullptr;
+  L.stream = st;
+  // (the kernels' dynamic-LDS limit was raised when the handle was made, on the device current then)
+  if (f32) {
+    if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for bf16 caches with head_dim 128 only");
+    return launch_decode_f32(D, G, P, L);
+  }
+  return L.clocks ? launch_decode_bf16_clocks(D, G, P, L) : launch_decode_bf16_product(D, G, P, L);
 }
 
-// causal attention over the prompt, bf16 only
-template <int D, int G>
-int launch_prompt_attn(const PromptAttnParams &P, int U, hipStream_t st) {
-  using Cf = PromptAttnCfg<D, G>;
-  // more LDS than a launch gets by default; asked for at every call (a call lasts milliseconds, and the
-  // attribute belongs to the current device)
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&prompt_attn_kernel<D, G>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::lds_bytes));
-  const int ntask = (P.Nmax + 31) / 32 * G;  // (32-row block, head) pairs of one KV head
-  hipLaunchKernelGGL((prompt_attn_kernel<D, G>), dim3((ntask + Cf::NWV - 1) / Cf::NWV, U), dim3(Cf::NT), Cf::lds_bytes,
-                     st, P);
-  HIP_TRY(hipGetLastError());
+// raises the decode kernels' dynamic-LDS limit for this handle's configuration on the current device (once, at
+// creation: not inside a launch, which may be under stream capture); only ever raised, since another handle on
+// the same device may need the larger value
+int dispatch_lds_limit(const morphkv_handle *h, size_t lds) {
+  static size_t limit[MAX_DEVICES][2][2][9] = {};  // [device][f32?][d == 128?][G]
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(MORPHKV_EHIP, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+  const bool f32 = h->cfg.dtype == MORPHKV_DTYPE_F32;
+  const int G = h->L.G, D = h->cfg.head_dim;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  size_t &cur = limit[dev][f32 ? 1 : 0][D == 128 ? 1 : 0][G];
+  if (lds <= cur) return MORPHKV_OK;
+  if (f32) {
+    if (const int rc = decode_lds_limit_f32(D, G, lds)) return rc;
+  } else {
+    if (const int rc = decode_lds_limit_bf16_product(D, G, lds)) return rc;
+    if (const int rc = decode_lds_limit_bf16_clocks(D, G, lds)) return rc;
+  }
+  cur = lds;
   return MORPHKV_OK;
 }
-template <int D>
-int dispatch_prompt_attn_g(int G, const PromptAttnParams &P, int U, hipStream_t st) {
-  switch (G) {
-    case 1: return launch_prompt_attn<D, 1>(P, U, st);
-    case 2: return launch_prompt_attn<D, 2>(P, U, st);
-    case 3: return launch_prompt_attn<D, 3>(P, U, st);
-    case 4: return launch_prompt_attn<D, 4>(P, U, st);
-    case 5: return launch_prompt_attn<D, 5>(P, U, st);
-    case 6: return launch_prompt_attn<D, 6>(P, U, st);
-    case 7: return launch_prompt_attn<D, 7>(P, U, st);
-    case 8: return launch_prompt_attn<D, 8>(P, U, st);
-    default: return fail(MORPHKV_EINVAL, "group size %d not supported", G);
-  }
-}
 
+int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_t st) {
+  return h->cfg.dtype == MORPHKV_DTYPE_F32 ? launch_prefill_f32(h->cfg.head_dim, h->L.G, P, h->L.U, st)
+                                           : launch_prefill_bf16(h->cfg.head_dim, h->L.G, P, h->L.U, st);
+}
 
 // selection over the prompt from the window queries (all three window entries end up here)
 int prefill_window(morphkv_handle *h, const void *Q_window, const void *K, const void *V, const float *lse_window,
@@ -465,6 +380,24 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   h->force_threads = 0;
   h->min_lds = 0;
   if (const char *e = std::getenv("MORPHKV_DECODE_MIN_LDS")) h->min_lds = (size_t)std::atol(e);
+  // Which part of K/V streams past the caches.  The device has a 256 MB memory-side cache in front of HBM: a
+  // step that reads more than that through ordinary loads evicts everything before the next step can reuse
+  // it.  So only `budget` bytes of the handle's K/V are read with ordinary loads (V first, then the end of K:
+  // they stay resident from step to step), the rest with the non-temporal hint, which neither displaces the
+  // resident part nor pays for being inserted.
+  h->nt_k = 0; h->nt_v = 0;
+  if (cfg->dtype == MORPHKV_DTYPE_BF16) {
+    double budget_mb = 208.0;
+    if (const char *e = std::getenv("MORPHKV_CACHE_BUDGET_MB")) budget_mb = std::atof(e);
+    const double half = (double)h->L.U * h->L.n_pad * cfg->head_dim * 2.0;  // bytes of K (= bytes of V) of the handle
+    const double stream = 2.0 * half - budget_mb * 1048576.0;              // bytes that have to stream
+    const int kgroups = (h->L.n_pad / 16 + 1) / 2, vtiles = h->L.n_pad / 32;
+    if (stream > 0.0) {
+      const double fk = stream >= half ? 1.0 : stream / half, fv = stream > half ? (stream - half) / half : 0.0;
+      h->nt_k = (int)(fk * kgroups + 0.5);
+      h->nt_v = (int)((fv > 1.0 ? 1.0 : fv) * vtiles + 0.5);
+    }
+  }
   if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
     const int v = std::atoi(e);
     if (v >= 128 && v <= 1024 && v % 64 == 0) h->force_threads = v;
@@ -566,8 +499,7 @@ int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *
   A.plen = P.plen;
   A.B = h->cfg.batch; A.Mq = h->cfg.n_q_heads; A.Mkv = h->cfg.n_kv_heads; A.R = h->cfg.R; A.Nmax = Nmax;
   A.scale_log2 = h->scale_log2;
-  int rc = h->cfg.head_dim == 128 ? dispatch_prompt_attn_g<128>(h->L.G, A, h->L.U, st)
-                                  : dispatch_prompt_attn_g<64>(h->L.G, A, h->L.U, st);
+  int rc = launch_prompt_attn(h->cfg.head_dim, h->L.G, A, h->L.U, st);
   if (rc) return rc;
   // selection over the prompt, with the window queries read in place and their normalisers from the pass above
   P.Qw = Q; P.q_rows = Nmax; P.q_prompt = 1;
@@ -606,14 +538,9 @@ int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, c
   const int upl = h->cfg.batch * h->cfg.n_kv_heads;  // units per layer
   DecodeParams P = decode_params(h);
   P.u0 = layer * upl;
+  P.io_u0 = P.u0;  // q, k_new, v_new and out are this layer's own tensors
   P.zig = (int32_t)(h->layer_steps[layer] & 1u);
-  // the kernel addresses the step's tensors by the unit's index in the whole model: shift the layer's
-  // own tensors back by the units that come before it
-  const size_t d = (size_t)h->cfg.head_dim, esz = (size_t)h->L.esz, G = (size_t)h->L.G, u0 = (size_t)P.u0;
-  P.q = (const void *)((uintptr_t)q - u0 * G * d * esz);
-  P.k_new = (const void *)((uintptr_t)k_new - u0 * d * esz);
-  P.v_new = (const void *)((uintptr_t)v_new - u0 * d * esz);
-  P.out = (float *)((uintptr_t)out - u0 * G * d * sizeof(float));
+  P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
   const int rc = dispatch_decode(h, P, upl, (hipStream_t)stream);
   if (rc == MORPHKV_OK) ++h->layer_steps[layer];
   return rc;

@@ -1,8 +1,8 @@
 """Turns a rocprofv3 results database (rocpd sqlite) into the few lines kept under profiles/.
 
-  python -m paper_2503_00979_amd.rocprof_summary trace  <results.db> <n_last>   # --kernel-trace runs
-  python -m paper_2503_00979_amd.rocprof_summary pmc    <results.db> <n_last>   # --pmc runs
-  python -m paper_2503_00979_amd.rocprof_summary kernels <results.db> <n_last>  # every kernel of the library
+  python profile_summary.py trace  <results.db> <n_last>   # --kernel-trace runs
+  python profile_summary.py pmc    <results.db> <n_last>   # --pmc runs
+  python profile_summary.py kernels <results.db> <n_last>  # every kernel of the library
 
 Only the library's kernels are looked at; <n_last> = how many of the last decode dispatches form the
 steady-state sample (the timed region of bench.py).

@@ -14,9 +14,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "morphkv.h")).read()
-    declared = set(re.findall(r"\b(morphkv_[a-z_]+)\s*\(", hdr))
+    declared = set()
+    for name in ("morphkv.h", "morphkv_diag.h"):     # the product interface and the diagnostics beside it
+        hdr = open(os.path.join(ROOT, "include", name)).read()
+        declared |= set(re.findall(r"\b(morphkv_[a-z_]+)\s*\(", hdr))
     assert declared == set(binding.EXPORTS)
+    product = open(os.path.join(ROOT, "include", "morphkv.h")).read()
+    for diag in ("morphkv_capture_scores", "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_calib_read"):
+        assert diag not in product
     lib = binding.load_library()
     for name in declared:
         assert hasattr(lib, name), name
