@@ -74,8 +74,12 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
 /* Host-only handle over caller-owned DEVICE buffers of at least morphkv_sizes bytes.
  * The buffers need no initialisation; prefill_select writes all state.  They must
  * stay valid until morphkv_destroy.  Ownership stays with the caller.
- * MORPHKV_EINVAL if C + R needs more LDS than a compute unit has (the reason is in morphkv_last_error).
- * Three environment variables, read here, override tuning choices and never change results:
+ * MORPHKV_EINVAL if C + R is beyond what the decode kernels can hold (the reason is in morphkv_last_error): fp32
+ * caches keep one weight per (query head, slot) in LDS (C + R up to about 9 k slots at 4 heads a group); bf16
+ * caches beyond that run with several workgroups per unit, up to about 130 k slots at 4 heads a group.
+ * Environment variables, read by morphkv_sizes and here, override tuning choices and never change results:
+ * MORPHKV_SPLIT_BPS (bf16: a positive value splits every unit over several workgroups of that many 32-slot blocks
+ * each; unset or 0 = only units that one workgroup cannot hold are split),
  * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel; raised where the
  * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least) and
  * MORPHKV_CACHE_BUDGET_MB (bf16 caches; default 208: how much of the handle's K/V is read with ordinary loads

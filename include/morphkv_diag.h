@@ -34,6 +34,10 @@ int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
  * device sustains when a kernel only streams: the practical ceiling next to the 8 TB/s of the data sheet. */
 int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream);
 
+/* How a decode launch over n_units units (all of the handle's, or one layer's) is laid out: 1 workgroup per unit
+ * = the fused kernel; more = the split kernel, each workgroup on blocks_per_workgroup blocks of 32 slots. */
+int morphkv_decode_plan(morphkv_handle *h, int32_t n_units, int32_t *workgroups_per_unit, int32_t *blocks_per_workgroup);
+
 #ifdef __cplusplus
 }
 #endif

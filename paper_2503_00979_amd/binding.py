@@ -24,7 +24,8 @@ EXPORTS = ("morphkv_sizes", "morphkv_create", "morphkv_destroy", "morphkv_prefil
            "morphkv_prefill_attend_select", "morphkv_decode_step",
            "morphkv_decode_step_layer",
            "morphkv_export_positions", "morphkv_export_evicted", "morphkv_export_evicted_list", "morphkv_capture_scores",
-           "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_calib_read", "morphkv_last_error")
+           "morphkv_capture_phase_clocks", "morphkv_calib_copy", "morphkv_calib_read", "morphkv_decode_plan",
+           "morphkv_last_error")
 
 
 class MorphKVError(RuntimeError):
@@ -67,6 +68,7 @@ def load_library():
     L.morphkv_export_evicted_list.argtypes = [vp, vp, vp]
     L.morphkv_capture_scores.argtypes = [vp, vp]
     L.morphkv_capture_phase_clocks.argtypes = [vp, vp]
+    L.morphkv_decode_plan.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.morphkv_calib_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.morphkv_calib_read.argtypes = [vp, vp, C.c_size_t, vp]
     L.morphkv_last_error.argtypes = []
@@ -266,6 +268,12 @@ class MorphKV:
         ev = torch.empty(self.U, max(self.cfg.evict_every, 1), dtype=torch.int32, device=self.device)
         _check(self.lib.morphkv_export_evicted_list(self._h, _dev_ptr(ev), self._stream()))
         return ev
+
+    def decode_plan(self, n_units=None):
+        """(workgroups per unit, 32-slot blocks per workgroup) of a decode launch over n_units units (default: all)."""
+        a, b = C.c_int32(), C.c_int32()
+        _check(self.lib.morphkv_decode_plan(self._h, self.U if n_units is None else int(n_units), C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def capture_scores(self, enable=True):
         """Returns the [U, C+1] fp32 device tensor the next decode steps write their fused scores to."""

@@ -46,6 +46,11 @@ struct DecodeParams {
   int32_t C, T;            // older tokens kept by a selection; selection every T steps (Appendix A.5), Cs = C+T-1
   int32_t *evl;            // [U][T] positions evicted by the last step, -1 padded
   int32_t zig;             // parity of the step count: direction of the walk over the cache
+  // split kernel only (decode_split.h): workspace of the partial results and the arrival counters
+  float *sp_part;          // [U][sp_smax][2G + G*D] local maximum, local sum, partial output per workgroup
+  float *sp_w;             // [U][G][n_pad] logits of the step
+  int32_t *sp_cnt;         // [U] workgroups of the unit that have finished their share (0 between launches)
+  int32_t sp_bps, sp_smax; // blocks of 32 slots per workgroup; record stride of sp_part
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
   int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)
@@ -188,7 +193,9 @@ __host__ __device__ inline int turn_group_width(int R) {
   while (gw > 1 && (R - 1 + WAVE / gw - 1) / (WAVE / gw) > 2 * RB) gw >>= 1;
   return gw;
 }
-struct TurnRebuild {
+// RBT = rows per lane and batch: RB where registers are short; 2 * RB takes a whole chunk in one batch, i.e. one
+// round trip to memory
+template <int RBT> struct TurnRebuildT {
   int lane, p, R, rs, cpt, fusion, c0, ncol, r_top, gw, gstride, g0;
   const float *ringu;
   // current column group
@@ -220,7 +227,7 @@ struct TurnRebuild {
     i0 = min(q * Lc, R - 1); i1 = min(i0 + Lc, R - 1);
   }
   // rows i0+b .. i0+b+RB-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
-  __device__ inline void load(int b, float (&v)[RB]) const {
+  __device__ inline void load(int b, float (&v)[RBT]) const {
     // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is ignored
     // when the batch is consumed, so issuing it is straight-line code that waits for nothing
     const int ib = i0 + b;
@@ -228,7 +235,7 @@ struct TurnRebuild {
     r0 += r0 < 0 ? R : 0;
     const unsigned coff = (unsigned)(colok ? c : c0);
 #pragma unroll
-    for (int k = 0; k < RB; ++k) {
+    for (int k = 0; k < RBT; ++k) {
       int r = r0 - k;       // rows of the chunk wrap at most once; past its end any row will do
       r += r < 0 ? R : 0;
       r = r < 0 ? 0 : r;
@@ -236,10 +243,10 @@ struct TurnRebuild {
     }
 
   }
-  __device__ inline void begin(float (&v)[RB]) {
+  __device__ inline void begin(float (&v)[RBT]) {
     if (ncol > g0) { group(g0); load(0, v); }
   }
-  __device__ inline void finish(float (&v)[RB], float *stage, float *turn) {
+  __device__ inline void finish(float (&v)[RBT], float *stage, float *turn) {
     if (ncol <= g0) return;
     int b = 0;
     float acc = 0.f;
@@ -247,12 +254,12 @@ struct TurnRebuild {
       float *st = stage + cg + cc;
       const int ib = i0 + b;
 #pragma unroll
-      for (int k = 0; k < RB; ++k)
+      for (int k = 0; k < RBT; ++k)
         if (ib + k < i1) {
           acc = fuse2(fusion, acc, v[k]);
           st[(ib + k) * cpt] = acc;
         }
-      b += RB;
+      b += RBT;
       if (b >= Lc) {
         // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
         float incl = acc;
@@ -277,6 +284,7 @@ struct TurnRebuild {
     }
   }
 };
+using TurnRebuild = TurnRebuildT<RB>;
 
 // One wave computes the aggregate state of a single column from its R row values colv[a] (row of step
 // p-R+1+a), as of the end of step p with rebuild point p0 (same result as column_scan), and stores it.
@@ -439,8 +447,11 @@ __device__ __forceinline__ void coarse_select_and_move(const StepTail<T> &c) {
   }
 }
 
-template <typename T, int D, bool CLK>
-__device__ __forceinline__ void compact_and_commit(const StepTail<T> &c) {
+// PRE: the caller has already loaded this thread's piece of the window slot's K row (kpre: threads 0 .. D/EPL-1) and
+// its element of the V row (vpre; bf16 caches: thread tid holds channel NT-1-tid, workgroups of at least D threads)
+template <typename T, int D, bool CLK, bool PRE = false>
+__device__ __forceinline__ void compact_and_commit(const StepTail<T> &c, uint4 kpre = uint4{0u, 0u, 0u, 0u},
+                                                   uint16_t vpre = 0) {
   const DecodeParams &P = c.P;
   const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane;
   const int Cs = c.Cs, CsP = c.CsP, R = c.R, n_pad = c.n_pad, cps = c.cps, n_snap = c.n_snap, p = c.p, w = c.w;
@@ -465,14 +476,14 @@ __device__ __forceinline__ void compact_and_commit(const StepTail<T> &c) {
   if (tid < PCS) {              // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
     const int ch0 = tid * EPL;
     uint4 *src = (uint4 *)(Kw_ + L::k_off(wslot, ch0));
-    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = *src;
+    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = PRE ? kpre : *src;
     *src = ((const uint4 *)knew)[tid];
   }
   if constexpr (L::tiled) {
     // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
     for (int ch = NT - 1 - tid; ch < D; ch += NT) {
       uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
-      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = *src;
+      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = PRE ? vpre : *src;
       *src = ((const uint16_t *)vnew)[ch];
     }
   } else {

@@ -46,6 +46,9 @@ struct DecodeLaunch {
 int launch_decode_bf16_product(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
 int launch_decode_bf16_clocks(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
 int launch_decode_f32(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
+// the same step with S workgroups per unit (decode_split.hip); L.threads is ignored (fixed by the kernel)
+int launch_decode_split(int D, int G, const DecodeParams &P, const DecodeLaunch &L, int S);
+int decode_lds_limit_split(int D, int G, size_t lds);
 // raise the kernels' dynamic-LDS limit on the current device
 int decode_lds_limit_bf16_product(int D, int G, size_t lds);
 int decode_lds_limit_bf16_clocks(int D, int G, size_t lds);

@@ -17,6 +17,7 @@
 
 #include "host.h"
 #include "decode.h"
+#include "decode_split.h"
 #include "prefill.h"
 #include "prompt_attn.h"
 #include "misc_kernels.h"
@@ -88,7 +89,9 @@ struct BufLayout {
   // cache
   size_t offK, offV, offPos, offMeta, offEvl, cache_bytes;
   // scores_ring
-  size_t offRing, offSfx, offNw, ring_bytes;
+  size_t offRing, offSfx, offNw, offSpW, offSpPart, offSpCnt, ring_bytes;
+  int sp_smax;     // most workgroups a unit is ever split over (1: the split kernel is never used, no workspace)
+  int sp_force;    // MORPHKV_SPLIT_BPS: blocks per workgroup forced (tuning / tests), 0 = never split, -1 = choose
   // scratch
   size_t offSrow, offStat, offF, offSel, offPlen, offLseW, scratch_bytes;
 };
@@ -118,6 +121,39 @@ int validate(const morphkv_config *c) {
   if (U > 65535) return fail(MORPHKV_EINVAL, "too many units (layers*batch*kv_heads must be <= 65535)");
   if ((long long)c->C + c->R + (c->evict_every == 0 ? c->max_new_tokens : 0) > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
   return MORPHKV_OK;
+}
+
+
+// How a launch of n_units units is split over workgroups (decode_split.h): S workgroups per unit, each on bps
+// blocks of 32 slots.  S = 1: the fused kernel.  The device is taken to have N_CU_REF compute units (MI355X), so
+// that the plan -- and the workspace sized from it -- is the same wherever it is made.
+constexpr int N_CU_REF = 256;
+struct SplitPlan { int S, bps; };
+SplitPlan plan_split(int n_pad, int G, int D, int R, int cps, int CsP, int T, bool bf16, int n_units, int force_bps,
+                     bool fused_fits) {
+  SplitPlan one{1, n_pad / 32};
+  if (!bf16) return one;
+  const int nblk = n_pad / 32;
+  int bps;
+  // one workgroup per unit wherever it can hold the unit: the split kernel's chain (partial results out, count in,
+  // merge) was measured slower than the fused kernel even for launches of 8 and 64 units (1088 and 544 slots)
+  if (force_bps <= 0 && fused_fits) return one;
+  if (force_bps > 0) {
+    bps = force_bps;
+  } else {
+    // as many workgroups per unit as fill the device once
+    const int S0 = n_units >= N_CU_REF ? 1 : N_CU_REF / n_units;
+    bps = (nblk + S0 - 1) / S0;
+  }
+  // phase A keeps the share's G x (32 bps) logits in LDS: 64 KB at most; and at most SPLIT_MAX workgroups a unit
+  const int bps_lds = ((64 * 1024 / 4) / G - 4) / 32, bps_min = (nblk + SPLIT_MAX - 1) / SPLIT_MAX;
+  if (bps > bps_lds) bps = bps_lds;
+  if (bps < bps_min) bps = bps_min;
+  if (bps < 1) bps = 1;
+  SplitPlan pl{(nblk + bps - 1) / bps, bps};
+  if (pl.S < 2 && fused_fits) return one;
+  if (bps > bps_lds || decode_split_lds_bytes(bps, G, D, R, cps, CsP, T) > 160 * 1024) return SplitPlan{0, 0};  // does not fit
+  return pl;
 }
 
 BufLayout make_layout(const morphkv_config *c) {
@@ -158,6 +194,22 @@ BufLayout make_layout(const morphkv_config *c) {
   L.offRing = o; o = align_up(o + U * R * np * 4);
   L.offSfx = o; o = align_up(o + U * R * CsP * 4);
   L.offNw = o; o = align_up(o + U * CsP * 4);
+  // workspace of the split decode kernel, sized for the launches this configuration can make: all units at once,
+  // or one layer's
+  L.sp_force = -1;
+  if (const char *e = std::getenv("MORPHKV_SPLIT_BPS")) L.sp_force = std::atoi(e);
+  L.sp_smax = 1;
+  if (L.esz == 2) {
+    const bool fits = decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, L.cps, L.CsP, c->evict_every) <= 160 * 1024;
+    for (int units : {L.U, c->batch * c->n_kv_heads}) {
+      const SplitPlan pl = plan_split(L.n_pad, L.G, c->head_dim, c->R, L.cps, L.CsP, c->evict_every > 0 ? c->evict_every : 1,
+                                      true, units, L.sp_force, fits);
+      if (pl.S > L.sp_smax) L.sp_smax = pl.S;
+    }
+  }
+  L.offSpW = o; o = align_up(o + (L.sp_smax > 1 ? U * (size_t)L.G * np * 4 : 0));
+  L.offSpPart = o; o = align_up(o + (L.sp_smax > 1 ? U * (size_t)L.sp_smax * split_part_floats(L.G, c->head_dim) * 4 : 0));
+  L.offSpCnt = o; o = align_up(o + (L.sp_smax > 1 ? U * 4 : 0));
   L.ring_bytes = o;
   o = 0;
   const size_t Nm = (size_t)c->max_prompt_len;
@@ -212,6 +264,11 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.zig = (int32_t)(h->steps & 1u);
   P.nt_k = h->nt_k;
   P.nt_v = h->nt_v;
+  P.sp_w = (float *)(h->ring + L.offSpW);
+  P.sp_part = (float *)(h->ring + L.offSpPart);
+  P.sp_cnt = (int32_t *)(h->ring + L.offSpCnt);
+  P.sp_smax = L.sp_smax;
+  P.sp_bps = 0;
   P.cpt_shift = -1;
   for (int sft = 0; sft < 16; ++sft)
     if ((1 << sft) == L.cpt) P.cpt_shift = sft;
@@ -234,6 +291,7 @@ PrefillParams prefill_params(const morphkv_handle *h, char *scratch_base, const 
   P.pos = (int32_t *)(h->cache + L.offPos);
   P.meta = (int32_t *)(h->cache + L.offMeta);
   P.evl = (int32_t *)(h->cache + L.offEvl);
+  P.sp_cnt = h->L.sp_smax > 1 ? (int32_t *)(h->ring + h->L.offSpCnt) : nullptr;
   P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.ring = (float *)(h->ring + L.offRing);
   P.sfx = (float *)(h->ring + L.offSfx);
@@ -265,19 +323,41 @@ int decode_threads(const morphkv_handle *h, int U) {
   return h->L.n_pad < 1024 ? 512 : 1024;
 }
 
+// does the fused kernel's LDS-resident weight array fit (priced for its largest workgroup)?
+bool fused_fits(const morphkv_handle *h) {
+  return decode_lds_bytes(h->L.n_pad, h->L.G, h->cfg.head_dim, 1024, h->cfg.R, h->L.cps, h->L.CsP,
+                          h->cfg.evict_every) <= 160 * 1024;
+}
+SplitPlan handle_plan(const morphkv_handle *h, int n_units) {
+  return plan_split(h->L.n_pad, h->L.G, h->cfg.head_dim, h->cfg.R, h->L.cps, h->L.CsP,
+                    h->cfg.evict_every > 0 ? h->cfg.evict_every : 1, h->cfg.dtype == MORPHKV_DTYPE_BF16, n_units,
+                    h->L.sp_force, fused_fits(h));
+}
+
 int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units, hipStream_t st) {
   const bool f32 = h->cfg.dtype == MORPHKV_DTYPE_F32;
   const int G = h->L.G, D = h->cfg.head_dim;
   DecodeLaunch L{};
   L.n_units = n_units;
+  L.clocks = P.dbgT != nullptr;
+  L.stream = st;
+  // (the kernels' dynamic-LDS limits were raised when the handle was made, on the device current then)
+  const SplitPlan pl = handle_plan(h, n_units);
+  if (pl.S == 0) return fail(MORPHKV_EINVAL, "C + R = %d is too large for the decode kernels' LDS", P.n);
+  if (pl.S > 1) {
+    // few units, or a cache beyond the fused kernel's LDS: several workgroups per unit
+    if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
+    DecodeParams PS = P;
+    PS.sp_bps = pl.bps;
+    L.threads = SPLIT_NT;
+    L.lds = decode_split_lds_bytes(pl.bps, G, D, P.R, P.cps, P.CsP, P.T);
+    return launch_decode_split(D, G, PS, L, pl.S);
+  }
   L.threads = decode_threads(h, n_units);
   if (f32 && L.threads > 512) L.threads = 512;  // fp32 builds: 256 registers a lane, groups of at most 512 threads
   L.lds = decode_lds_bytes(P.n_pad, G, D, L.threads, P.R, P.cps, P.CsP, P.T);
   if (L.lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, L.lds);
   if (h->min_lds > L.lds && h->min_lds <= 160 * 1024) L.lds = h->min_lds;
-  L.clocks = P.dbgT != nullptr;
-  L.stream = st;
-  // (the kernels' dynamic-LDS limit was raised when the handle was made, on the device current then)
   if (f32) {
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for bf16 caches with head_dim 128 only");
     return launch_decode_f32(D, G, P, L);
@@ -288,7 +368,7 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
 // raises the decode kernels' dynamic-LDS limit for this handle's configuration on the current device (once, at
 // creation: not inside a launch, which may be under stream capture); only ever raised, since another handle on
 // the same device may need the larger value
-int dispatch_lds_limit(const morphkv_handle *h, size_t lds) {
+int dispatch_lds_limit(const morphkv_handle *h, size_t lds, size_t lds_split) {
   static size_t limit[MAX_DEVICES][2][2][9] = {};  // [device][f32?][d == 128?][G]
   int dev = -1;
   HIP_TRY(hipGetDevice(&dev));
@@ -296,6 +376,11 @@ int dispatch_lds_limit(const morphkv_handle *h, size_t lds) {
   const bool f32 = h->cfg.dtype == MORPHKV_DTYPE_F32;
   const int G = h->L.G, D = h->cfg.head_dim;
   std::lock_guard<std::mutex> lock(g_scratch_mu);
+  static size_t limit_split[MAX_DEVICES][2][9] = {};
+  if (!f32 && lds_split > limit_split[dev][D == 128 ? 1 : 0][G]) {
+    if (const int rc = decode_lds_limit_split(D, G, lds_split)) return rc;
+    limit_split[dev][D == 128 ? 1 : 0][G] = lds_split;
+  }
   size_t &cur = limit[dev][f32 ? 1 : 0][D == 128 ? 1 : 0][G];
   if (lds <= cur) return MORPHKV_OK;
   if (f32) {
@@ -408,15 +493,27 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
     h->n_cu = prop.multiProcessorCount;
   else
     (void)hipGetLastError();
-  // the decode kernel keeps one weight per (head, slot) in LDS: say so now if C + R is too large for that
+  // the fused decode kernel keeps one weight per (head, slot) in LDS; a cache too large for that runs in the split
+  // kernel (bf16), whose shares are bounded instead: say so now if neither can take C + R
   const int upl = cfg->batch * cfg->n_kv_heads;
-  size_t lds_max = 0;
+  size_t lds_max = 0, lds_split = 0;
   for (int units : {h->L.U, upl}) {
+    const SplitPlan pl = handle_plan(h, units);
+    if (pl.S == 0) {
+      const int n = h->L.n;
+      delete h;
+      return fail(MORPHKV_EINVAL, "C + R = %d needs more LDS than the decode kernels have (limit 163840 bytes)", n);
+    }
+    if (pl.S > 1) {
+      const size_t lds = decode_split_lds_bytes(pl.bps, h->L.G, cfg->head_dim, cfg->R, h->L.cps, h->L.CsP,
+                                                cfg->evict_every > 0 ? cfg->evict_every : 1);
+      lds_split = lds > lds_split ? lds : lds_split;
+      continue;
+    }
     const size_t lds = decode_lds_bytes(h->L.n_pad, h->L.G, cfg->head_dim,
                                         cfg->dtype == MORPHKV_DTYPE_F32 ? std::min(decode_threads(h, units), 512)
                                                                         : decode_threads(h, units),
-                                        cfg->R, h->L.cps,
-                                        h->L.CsP, cfg->evict_every);
+                                        cfg->R, h->L.cps, h->L.CsP, cfg->evict_every);
     if (lds > 160 * 1024) {
       const int n = h->L.n;
       delete h;
@@ -425,7 +522,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
     lds_max = lds > lds_max ? lds : lds_max;
   }
   if (h->min_lds > lds_max && h->min_lds <= 160 * 1024) lds_max = h->min_lds;
-  if (const int rc = dispatch_lds_limit(h, lds_max)) {
+  if (const int rc = dispatch_lds_limit(h, lds_max, lds_split)) {
     delete h;
     return rc;
   }
@@ -611,6 +708,15 @@ int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stre
   hipLaunchKernelGGL(calib_read_kernel, dim3(n_cu), dim3(1024), 0, (hipStream_t)stream, sink, (const uint4 *)src, nvec,
                      per_block);
   HIP_TRY(hipGetLastError());
+  return MORPHKV_OK;
+}
+
+int morphkv_decode_plan(morphkv_handle *h, int32_t n_units, int32_t *workgroups_per_unit, int32_t *blocks_per_workgroup) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (n_units < 1 || n_units > h->L.U) return fail(MORPHKV_EINVAL, "n_units %d outside 1..%d", n_units, h->L.U);
+  const SplitPlan pl = handle_plan(h, n_units);
+  if (workgroups_per_unit) *workgroups_per_unit = pl.S;
+  if (blocks_per_workgroup) *blocks_per_workgroup = pl.bps;
   return MORPHKV_OK;
 }
 

@@ -36,6 +36,7 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(PrefillParams P) {
     m[0] = keep; m[1] = N; m[2] = -1; m[3] = N % R; m[4] = N;
   }
   if (tid < P.T) P.evl[(size_t)u * P.T + tid] = -1;
+  if (tid == 0 && P.sp_cnt) P.sp_cnt[u] = 0;
   if (n_old <= P.C) {
     for (int k = tid; k < n_old; k += NT) sel[k] = k;
     return;

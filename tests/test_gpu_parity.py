@@ -149,6 +149,89 @@ def test_exact_ties_follow_the_position_rule(case, entry, oracle_lib):
     assert rep.exact_ties_decode > 0 and rep.exact_ties_prefill > 0
 
 
+# ---- several workgroups per unit (the split kernel): forced on small shapes, chosen by the library on c2 / c4 layer by layer
+SPLIT = [
+    ("bf16_g2_d64", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=50, R=9, fusion="sum", prompt_lens=(90, 61), steps=70)),
+    ("bf16_g3_d128", dict(L=1, B=1, M=6, Mkv=2, d=128, dtype="bf16", C=64, R=16, fusion="max", prompt_lens=(200,), steps=70)),
+    ("bf16_g7_d128", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(300, 150), steps=60)),
+    ("bf16_g8_d128", dict(L=1, B=1, M=8, Mkv=1, d=128, dtype="bf16", C=70, R=10, fusion="sum", prompt_lens=(111,), steps=60)),
+    ("short_prompts", dict(L=1, B=4, M=4, Mkv=2, d=64, dtype="bf16", C=12, R=8, fusion="sum", prompt_lens=(1, 5, 8, 17), steps=60)),
+    ("c_is_1", dict(L=1, B=1, M=4, Mkv=1, d=64, dtype="bf16", C=1, R=5, fusion="max", prompt_lens=(30,), steps=40)),
+    ("r_is_1", dict(L=1, B=1, M=4, Mkv=2, d=64, dtype="bf16", C=9, R=1, fusion="sum", prompt_lens=(30,), steps=40)),
+    ("r_gt_c", dict(L=1, B=1, M=2, Mkv=1, d=64, dtype="bf16", C=3, R=40, fusion="sum", prompt_lens=(100,), steps=90)),
+    ("many_units", dict(L=3, B=5, M=8, Mkv=4, d=64, dtype="bf16", C=21, R=4, fusion="sum", prompt_lens=(30, 9, 50, 26, 3), steps=40)),
+    ("T4", dict(L=1, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=50, R=9, fusion="sum", prompt_lens=(90, 61), steps=90, evict_every=4)),
+    ("T8_g7", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(300, 150), steps=80, evict_every=8)),
+    ("T64", dict(L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=90, R=12, fusion="sum", prompt_lens=(250,), steps=200, evict_every=64)),
+    ("cumsum", dict(L=2, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=96, R=12, fusion="cumsum", prompt_lens=(300, 61), steps=80)),
+    ("prompt_only", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=64, R=16, fusion="sum", prompt_lens=(200, 40), steps=70, evict_every=0, max_new_tokens=70)),
+    ("ties_all", dict(L=2, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=96, R=12, fusion="max", prompt_lens=(300, 61), steps=60, key_codes=1)),
+    ("ties_clusters_T8", dict(L=1, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=100, R=20, fusion="max", prompt_lens=(300, 150), steps=80, key_codes=6, evict_every=8)),
+    ("mid", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=1024, R=64, fusion="sum", prompt_lens=(2000, 700), steps=100)),
+]
+
+
+@pytest.mark.parametrize("bps", [1, 3])
+@pytest.mark.parametrize("case", SPLIT, ids=[c[0] for c in SPLIT])
+def test_split_kernel_forced(case, bps, oracle_lib, monkeypatch):
+    """The step with a unit's cache spread over several workgroups of `bps` 32-slot blocks each (partial maxima, sums
+    and outputs merged by the last workgroup to finish, which then records, fuses, selects and compacts) against the
+    oracle: same bar as the fused kernel, every step."""
+    name, kw = case
+    monkeypatch.setenv("MORPHKV_SPLIT_BPS", str(bps))
+    wl = inputs.small_workload(14000 + SPLIT.index(case), **kw)
+    T = wl.evict_every
+    ls = _lockstep(wl, DEV, capture_scores=T == 1).prefill()
+    S, b = ls.gpu.decode_plan()
+    n_pad = -(-(wl.C + (T - 1 if T >= 1 else wl.max_new_tokens) + wl.R) // 32) * 32
+    nblk = n_pad // 32
+    bps_used = max(bps, -(-nblk // 32))     # at most 32 workgroups a unit
+    want = -(-nblk // bps_used)
+    if want > 1:
+        assert S == want and b == bps_used, "the split kernel was not used as asked"
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"split{bps}_{name} S={S}", rep)
+    if T == 1:
+        assert rep.max_score_rel_err <= 1e-5
+    if wl.key_codes:
+        assert rep.near_ties_decode == 0 and rep.exact_ties_decode > 0
+
+
+def test_split_kernel_per_layer_calls_at_c4_size(oracle_lib, monkeypatch):
+    """c4 called layer by layer, as a model calls it: 64 units a launch, here spread over 4 workgroups a unit; the
+    oracle follows one sequence through all 32 layers."""
+    monkeypatch.setenv("MORPHKV_SPLIT_BPS", "5")
+    wl = inputs.workload("c4")
+    ls = _lockstep(wl, DEV, batch_index=[5], gen_device=DEV, per_layer=True).prefill()
+    assert ls.gpu.decode_plan(wl.batch * wl.n_kv_heads) == (4, 5)
+    rep = _full_size_run(ls, 96, check_every=32, capture_last=16)
+    _report("c4_per_layer_split", rep)
+    assert rep.evictions == 96 * 32 * 8 and rep.max_score_rel_err <= 1e-5
+
+
+def test_split_kernel_at_c2_size(oracle_lib, monkeypatch):
+    """c2 (8 units of 1088 slots) with every unit spread over 17 workgroups: 256 steps, every unit."""
+    monkeypatch.setenv("MORPHKV_SPLIT_BPS", "2")
+    wl = inputs.workload("c2")
+    ls = _lockstep(wl, DEV).prefill()
+    assert ls.gpu.decode_plan() == (17, 2)
+    rep = ls.run(256, check_every=32)
+    _report("c2_split", rep)
+    assert rep.evictions == 256 * wl.n_units
+
+
+def test_split_kernel_beyond_fused_lds(oracle_lib):
+    """A cache too large for the fused kernel's LDS-resident weights (C + R = 12128 slots, 4 heads a group) runs in the
+    split kernel, whose merging workgroup holds no weights in LDS: past one rotation of the window."""
+    wl = inputs.small_workload(14100, L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=12000, R=128, fusion="sum",
+                               prompt_lens=(13000,), steps=128 + 12)
+    ls = _lockstep(wl, DEV, gen_device=DEV).prefill()
+    assert ls.gpu.decode_plan()[0] > 1
+    rep = ls.run(wl.steps, check_every=16)
+    _report("split_c12000", rep)
+    assert rep.evictions > 0
+
+
 @pytest.mark.parametrize("T", [1, 4])
 def test_per_layer_calls(T, oracle_lib):
     """One call per layer, as a model's attention layers make them, gives what the whole-model call gives."""
@@ -623,10 +706,17 @@ def test_error_paths(oracle_lib):
     with pytest.raises(binding.MorphKVError) as e:
         g.prefill_select(Qw, K, V, [9])
     assert e.value.code == binding.EINVAL
-    # a cache too large for the LDS-resident weights is refused when the handle is made, with the reason
-    big = inputs.small_workload(8, L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=12000, R=128, prompt_lens=(100,), steps=1)
+    # a cache too large for the decode kernels is refused when the handle is made, with the reason: fp32 keeps every
+    # weight of a step in LDS; bf16 goes on with several workgroups per unit, up to 32 shares that each fit
+    big = inputs.small_workload(8, L=1, B=1, M=8, Mkv=2, d=128, dtype="f32", C=12000, R=128, prompt_lens=(100,), steps=1)
     with pytest.raises(binding.MorphKVError) as e:
         binding.MorphKV.from_workload(big, DEV)
+    assert e.value.code == binding.EINVAL and "LDS" in str(e.value)
+    huge = inputs.small_workload(8, L=1, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=300000, R=128, prompt_lens=(100,), steps=1)
+    with pytest.raises(binding.MorphKVError) as e:
+        binding.morphkv_sizes(binding.make_config(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, C_=300000,
+                                                  R=128, fusion="sum", dtype="bf16", max_prompt_len=100)) and None
+        binding.MorphKV.from_workload(huge, DEV)
     assert e.value.code == binding.EINVAL and "LDS" in str(e.value)
     with pytest.raises(binding.MorphKVError) as e:
         g.decode_step_layer(1, q[0], k[0], v[0], torch.empty(g.out_shape[1:], dtype=torch.float32, device=DEV))
