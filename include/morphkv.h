@@ -62,8 +62,12 @@ typedef struct morphkv_config {
                              is kept (SnapKV, Section 5 "Baselines"); needs max_new_tokens */
   int32_t max_prompt_len; /* largest Nmax that will be passed to prefill_select */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim) (Eq.1) */
-  int32_t max_new_tokens; /* only with evict_every == 0: decode steps the cache has room for (the step after
-                             that returns MORPHKV_ESTATE); otherwise ignored */
+  int32_t max_new_tokens; /* with evict_every == 0 or n_keep_all_layers > 0: decode steps the cache has room for
+                             (the step after that returns MORPHKV_ESTATE); otherwise ignored */
+  int32_t n_keep_all_layers; /* Appendix A.6 (selective layer retention): MorphKV is off in the first
+                             n_keep_all_layers layers, which keep every token of the prompt and of the response
+                             (max_prompt_len + max_new_tokens slots; attention only: nothing is recorded, fused or
+                             selected there); the other layers run as configured above.  0..n_layers; bf16 only */
 } morphkv_config;
 
 typedef struct morphkv_handle morphkv_handle;
@@ -164,7 +168,9 @@ int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, c
 
 /* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
  *  pos    [U][Cs+R] int32, Cs = C+evict_every-1 (C+max_new_tokens when evict_every == 0): slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
- *         window slot (position mod R)
+ *         window slot (position mod R).  With n_keep_all_layers > 0 the rows are max(Cs, Ck) + R long, Ck =
+ *         max_prompt_len + max_new_tokens being the older-token slots of a layer that keeps everything: a unit's row
+ *         holds its own older-token slots, then its R window slots, then -1
  *  n_snap [U]      int32: older tokens currently held */
 int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream);
 /* evicted [U] int32 device: position evicted by the last decode step, -1 if none (with evict_every > 1:

@@ -101,6 +101,8 @@ class RefMorphKV:
 
     @classmethod
     def from_workload(cls, wl, **kw):
+        if getattr(wl, "n_keep_all_layers", 0):
+            return RefMorphKVLayered(wl, **kw)
         return cls(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                    head_dim=wl.head_dim, C_=wl.C, R=wl.R, fusion=wl.fusion, dtype=wl.dtype,
                    evict_every=wl.evict_every, max_new_tokens=wl.max_new_tokens, **kw)
@@ -188,4 +190,86 @@ class RefMorphKV:
             raise RuntimeError(f"morphkv_ref_export_positions failed: {rc}")
         snaps = [pos[u, :n_snap[u]].copy() for u in range(self.U)]
         wins = [pos[u, n_snap[u]:n_snap[u] + n_win[u]].copy() for u in range(self.U)]
+        return snaps, wins
+
+
+class RefMorphKVLayered:
+    """Selective layer retention (Appendix A.6): the method is switched off in the first k layers, which keep every
+    token.  No new arithmetic: those layers are the same oracle with room for every token (nothing is ever evicted
+    there, so each step is plain attention over the whole history), the other layers are the oracle as configured;
+    this class only splits the tensors by layer and joins the results (units of the first k layers come first).
+    """
+
+    def __init__(self, wl, **kw):
+        k = wl.n_keep_all_layers
+        assert 0 < k <= wl.n_layers
+        common = dict(batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, R=wl.R,
+                      fusion=wl.fusion, dtype=wl.dtype, **kw)
+        self.k = k
+        self.keep = RefMorphKV(n_layers=k, C_=wl.Nmax, evict_every=0, max_new_tokens=wl.max_new_tokens, **common)
+        self.sel = (RefMorphKV(n_layers=wl.n_layers - k, C_=wl.C, evict_every=wl.evict_every,
+                               max_new_tokens=wl.max_new_tokens, **common) if k < wl.n_layers else None)
+        self.parts = [p for p in (self.keep, self.sel) if p is not None]
+        self.dtype = wl.dtype
+        self.U = sum(p.U for p in self.parts)
+        self.C, self.R, self.T = wl.C, wl.R, wl.evict_every
+        self.Cs = self.sel.Cs if self.sel else self.keep.Cs
+        self.out_shape = (wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim)
+
+    def _split(self, t):
+        return [t[: self.k].contiguous(), t[self.k:].contiguous()][: len(self.parts)]
+
+    def close(self):
+        for p in self.parts:
+            p.close()
+
+    def prefill_select(self, Qw, K, V, prompt_len, forced_pos: Optional[np.ndarray] = None) -> None:
+        for i, (p, q, k, v) in enumerate(zip(self.parts, self._split(Qw), self._split(K), self._split(V))):
+            fp = None
+            if forced_pos is not None and p is self.sel:
+                fp = np.ascontiguousarray(forced_pos[self.keep.U:])
+            p.prefill_select(q, k, v, prompt_len, forced_pos=fp)
+
+    def prefill_scores(self, unit: int) -> np.ndarray:
+        return self.keep.prefill_scores(unit) if unit < self.keep.U else self.sel.prefill_scores(unit - self.keep.U)
+
+    def decode_begin(self, q, k_new, v_new) -> np.ndarray:
+        outs = [p.decode_begin(a, b, c) for p, a, b, c in
+                zip(self.parts, self._split(q), self._split(k_new), self._split(v_new))]
+        return np.concatenate(outs, axis=0)
+
+    def candidates(self):
+        T = max(self.T, 1)
+        n_cand = np.zeros(self.U, np.int32)
+        n_evict = np.zeros(self.U, np.int32)
+        cand_pos = np.full((self.U, self.Cs + 1), -1, np.int32)
+        cand_F = np.zeros((self.U, self.Cs + 1), np.float64)
+        choice = np.full((self.U, T), -1, np.int32)
+        if self.sel is not None:
+            a, b, c, d, e = self.sel.candidates()
+            u0 = self.keep.U
+            n_cand[u0:], cand_pos[u0:], cand_F[u0:], n_evict[u0:], choice[u0:] = a, b, c, d, e
+        ka = self.keep.candidates()
+        assert not ka[0].any() and not ka[3].any(), "a layer that keeps every token never has candidates"
+        return n_cand, cand_pos, cand_F, n_evict, choice
+
+    def decode_commit(self, evict_pos: Optional[np.ndarray] = None) -> None:
+        self.keep.decode_commit(None)
+        if self.sel is not None:
+            ep = None
+            if evict_pos is not None:
+                ep = np.asarray(evict_pos).reshape(self.U, -1)[self.keep.U:]
+            self.sel.decode_commit(ep)
+
+    def decode_step(self, q, k_new, v_new) -> np.ndarray:
+        out = self.decode_begin(q, k_new, v_new)
+        self.decode_commit(None)
+        return out
+
+    def export_positions(self):
+        snaps, wins = [], []
+        for p in self.parts:
+            a, b = p.export_positions()
+            snaps += a
+            wins += b
         return snaps, wins

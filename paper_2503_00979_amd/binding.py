@@ -37,7 +37,8 @@ class MorphKVError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "C", "R", "fusion", "dtype",
-                 "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float), ("max_new_tokens", C.c_int32)]
+                 "evict_every", "max_prompt_len")] + [("softmax_scale", C.c_float), ("max_new_tokens", C.c_int32),
+                                                      ("n_keep_all_layers", C.c_int32)]
 
 
 _lib = None
@@ -93,9 +94,9 @@ def _dev_ptr(t: torch.Tensor):
 
 
 def make_config(*, n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, fusion, dtype, max_prompt_len,
-                evict_every=1, softmax_scale=0.0, max_new_tokens=0) -> Config:
+                evict_every=1, softmax_scale=0.0, max_new_tokens=0, n_keep_all_layers=0) -> Config:
     return Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, C_, R, FUSION[fusion], DTYPE[dtype],
-                  evict_every, max_prompt_len, softmax_scale, max_new_tokens)
+                  evict_every, max_prompt_len, softmax_scale, max_new_tokens, n_keep_all_layers)
 
 
 def morphkv_sizes(cfg: Config):
@@ -129,7 +130,11 @@ class MorphKV:
         if self.device.type != "cuda":
             raise ValueError("libmorphkv needs a GPU device")
         self.U = cfg.n_layers * cfg.batch * cfg.n_kv_heads
-        self.n = cfg.C + (cfg.evict_every - 1 if cfg.evict_every >= 1 else cfg.max_new_tokens) + cfg.R
+        # older-token slots of a selecting layer and of a layer that keeps every token; rows of export_positions
+        self.Cs = cfg.C + (cfg.evict_every - 1 if cfg.evict_every >= 1 else cfg.max_new_tokens)
+        self.Cs_keep = cfg.max_prompt_len + cfg.max_new_tokens
+        k = cfg.n_keep_all_layers
+        self.n = (max(self.Cs, self.Cs_keep) if 0 < k < cfg.n_layers else self.Cs_keep if k else self.Cs) + cfg.R
         self.dtype = _TORCH_DTYPE["f32" if cfg.dtype == 0 else "bf16"]
         cb, rb, sb = morphkv_sizes(cfg)
         self.bytes = (cb, rb, sb)
@@ -147,7 +152,7 @@ class MorphKV:
         cfg = make_config(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                           head_dim=wl.head_dim, C_=wl.C, R=wl.R, fusion=wl.fusion, dtype=wl.dtype,
                           max_prompt_len=wl.Nmax, evict_every=wl.evict_every,
-                          max_new_tokens=wl.max_new_tokens, **kw)
+                          max_new_tokens=wl.max_new_tokens, n_keep_all_layers=wl.n_keep_all_layers, **kw)
         return cls(cfg, device)
 
     def close(self):
@@ -278,7 +283,7 @@ class MorphKV:
     def capture_scores(self, enable=True):
         """Returns the [U, C+1] fp32 device tensor the next decode steps write their fused scores to."""
         if enable:
-            self._scoreF = torch.zeros(self.U, self.n - self.cfg.R + 1, dtype=torch.float32, device=self.device)
+            self._scoreF = torch.zeros(self.U, self.Cs + 1, dtype=torch.float32, device=self.device)
             _check(self.lib.morphkv_capture_scores(self._h, _dev_ptr(self._scoreF)))
         else:
             _check(self.lib.morphkv_capture_scores(self._h, None))

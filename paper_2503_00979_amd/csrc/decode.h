@@ -51,6 +51,8 @@ struct DecodeParams {
   float *sp_w;             // [U][G][n_pad] logits of the step
   int32_t *sp_cnt;         // [U] workgroups of the unit that have finished their share (0 between launches)
   int32_t sp_bps, sp_smax; // blocks of 32 slots per workgroup; record stride of sp_part
+  int32_t keep_all;        // split kernel only: a layer that keeps every token (Appendix A.6): nothing is recorded,
+                           // fused or selected; the token leaving the window is appended to the older tokens
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
   int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)
@@ -494,7 +496,9 @@ __device__ __forceinline__ void compact_and_commit(const StepTail<T> &c, uint4 k
       *src = ((const uint4 *)vnew)[tid - 64];
     }
   }
-  if (dest >= 0) {
+  if (dest >= 0 && P.keep_all) {
+    if (tid == 0) posu[dest] = p - R;  // no recorded rows, no aggregates to move
+  } else if (dest >= 0) {
     if (wave == NW - 1) {
       if (lane == 0) posu[dest] = p - R;
       move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP,

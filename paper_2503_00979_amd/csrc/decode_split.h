@@ -79,6 +79,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   const bool cum = P.fusion == 2;
   const int fusion = cum ? 0 : P.fusion;
   const int Tev = P.T;
+  const bool keep = P.keep_all != 0;  // a layer that keeps every token: attention and append only
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     int r = w + 1 + a;
     r -= r >= R ? R : 0;
     cvr[k] = 0.f;
-    if (a < R - 1 && win_full) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
+    if (a < R - 1 && win_full && !keep) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
   }
   // the rebuild's loads (one batch: a lane's whole chunk of rows) go out now, are consumed after the K loop
   TurnRebuildT<2 * RB> tr;
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   const int tgw = turn_group_width(R);
   int nrw = (cps + tgw - 1) / tgw;
   nrw = nrw > NW / 2 ? NW / 2 : nrw;
-  const bool rebuilds = wave >= NW - nrw;
+  const bool rebuilds = wave >= NW - nrw && !keep;
   if (rebuilds) {
     tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
     tr.begin(rbv);
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
-        ws_store4(wts, (uint32_t)(g * n_pad + j0s + 4 * jq), l);
+        if (!keep) ws_store4(wts, (uint32_t)(g * n_pad + j0s + 4 * jq), l);
         l.x = exp2f(l.x - mref[g]); l.y = exp2f(l.y - mref[g]); l.z = exp2f(l.z - mref[g]); l.w = exp2f(l.w - mref[g]);
         *pl = l;
         zs[g] += (l.x + l.y) + (l.z + l.w);
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   const int nq = n_pad / 4;
   float4 lq[G], nw0 = make_float4(0.f, 0.f, 0.f, 0.f), sf0 = nw0;
   int4 pp0 = make_int4(-1, -1, -1, -1);
-  if (tid < nq) {
+  if (tid < nq && !keep) {
 #pragma unroll
     for (int g = 0; g < G; ++g) lq[g] = ws_load4(wts, (uint32_t)(g * n_pad + 4 * tid));
     if (4 * tid < n_snap) {
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
       shf[0] = i == 0 ? S4[0] : i == 1 ? S4[1] : i == 2 ? S4[2] : S4[3];
     }
   };
-  for (int jq = tid; jq < nq; jq += NT) {
+  for (int jq = tid; jq < nq && !keep; jq += NT) {
     // the next group's loads go out before this group's arithmetic
     const int jn = jq + NT;
     float4 ln[G], an = make_float4(0.f, 0.f, 0.f, 0.f), bn = an;
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   }
   wave_argmin(bF, bP, bC);
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
-  if (turn_n > 0) {
+  if (turn_n > 0 && !keep) {
     const int rz = wm1, r0 = wm1 == 0 ? R - 1 : wm1 - 1;
     const int total = R * cpt;
     const int csh = P.cpt_shift;
@@ -503,7 +504,15 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   lds_barrier();
 
   // ---- decision (wave 0)
-  if (wave == 0) {
+  if (keep) {
+    // every token is kept: the one leaving the window joins the older tokens (the host has made sure there is room)
+    if (tid == 0) {
+      sh[2] = win_full ? n_snap : -1;
+      sh[3] = -1;
+      sh[4] = n_snap + (win_full ? 1 : 0);
+      sh[5] = 0;
+    }
+  } else if (wave == 0) {
     float fd = 0.f;
     for (int a = lane; a < R; a += WAVE) {
       const float v = a == R - 1 ? shf[0] : colv[a];

@@ -37,11 +37,16 @@ __global__ __launch_bounds__(1024) void calib_read_kernel(uint32_t *sink, const 
 }
 
 // ---- exports
+// out rows are `row` long: the unit's n slots, then -1
 __global__ void export_positions_kernel(const int32_t *pos, const int32_t *meta, int32_t *out_pos,
-                                        int32_t *out_nsnap, int n, int n_pad) {
+                                        int32_t *out_nsnap, int n, int n_pad, int row) {
   const int u = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out_pos[(size_t)u * n + i] = pos[(size_t)u * n_pad + i];
+  if (i < row) out_pos[(size_t)u * row + i] = i < n ? pos[(size_t)u * n_pad + i] : -1;
   if (i == 0 && out_nsnap) out_nsnap[u] = meta[(size_t)u * META];
+}
+__global__ void fill_i32_kernel(int32_t *dst, size_t n, int32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
 }
 __global__ void export_evicted_kernel(const int32_t *meta, int32_t *out, int U) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;

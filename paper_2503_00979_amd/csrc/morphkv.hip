@@ -92,6 +92,7 @@ struct BufLayout {
   size_t offRing, offSfx, offNw, offSpW, offSpPart, offSpCnt, ring_bytes;
   int sp_smax;     // most workgroups a unit is ever split over (1: the split kernel is never used, no workspace)
   int sp_force;    // MORPHKV_SPLIT_BPS: blocks per workgroup forced (tuning / tests), 0 = never split, -1 = choose
+  bool keep_all;   // layers that keep every token: no recorded rows, no aggregates; always the split kernel
   // scratch
   size_t offSrow, offStat, offF, offSel, offPlen, offLseW, scratch_bytes;
 };
@@ -117,6 +118,12 @@ int validate(const morphkv_config *c) {
   if (c->max_prompt_len < 1) return fail(MORPHKV_EINVAL, "max_prompt_len must be >= 1");
   if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale))
     return fail(MORPHKV_EINVAL, "softmax_scale must be finite and >= 0");
+  if (c->n_keep_all_layers < 0 || c->n_keep_all_layers > c->n_layers)
+    return fail(MORPHKV_EINVAL, "n_keep_all_layers must be in 0..n_layers");
+  if (c->n_keep_all_layers > 0 && c->dtype != MORPHKV_DTYPE_BF16)
+    return fail(MORPHKV_EINVAL, "layers that keep every token (n_keep_all_layers) are built for bf16 caches only");
+  if (c->n_keep_all_layers > 0 && (c->max_new_tokens < 1 || c->max_new_tokens > (1 << 20)))
+    return fail(MORPHKV_EINVAL, "n_keep_all_layers > 0 needs max_new_tokens >= 1 (those layers hold max_prompt_len + max_new_tokens tokens)");
   const long long U = (long long)c->n_layers * c->batch * c->n_kv_heads;
   if (U > 65535) return fail(MORPHKV_EINVAL, "too many units (layers*batch*kv_heads must be <= 65535)");
   if ((long long)c->C + c->R + (c->evict_every == 0 ? c->max_new_tokens : 0) > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
@@ -156,8 +163,9 @@ SplitPlan plan_split(int n_pad, int G, int D, int R, int cps, int CsP, int T, bo
   return pl;
 }
 
-BufLayout make_layout(const morphkv_config *c) {
+BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
   BufLayout L{};
+  L.keep_all = keep_all;
   L.U = c->n_layers * c->batch * c->n_kv_heads;
   L.G = c->n_q_heads / c->n_kv_heads;
   L.Cs = c->C + (c->evict_every >= 1 ? c->evict_every - 1 : c->max_new_tokens);
@@ -191,25 +199,27 @@ BufLayout make_layout(const morphkv_config *c) {
   L.offEvl = o; o = align_up(o + U * (size_t)(c->evict_every > 0 ? c->evict_every : 1) * 4);
   L.cache_bytes = o;
   o = 0;
-  L.offRing = o; o = align_up(o + U * R * np * 4);
-  L.offSfx = o; o = align_up(o + U * R * CsP * 4);
-  L.offNw = o; o = align_up(o + U * CsP * 4);
+  L.offRing = o; o = align_up(o + (keep_all ? 0 : U * R * np * 4));
+  L.offSfx = o; o = align_up(o + (keep_all ? 0 : U * R * CsP * 4));
+  L.offNw = o; o = align_up(o + (keep_all ? 0 : U * CsP * 4));
   // workspace of the split decode kernel, sized for the launches this configuration can make: all units at once,
   // or one layer's
   L.sp_force = -1;
   if (const char *e = std::getenv("MORPHKV_SPLIT_BPS")) L.sp_force = std::atoi(e);
   L.sp_smax = 1;
   if (L.esz == 2) {
-    const bool fits = decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, L.cps, L.CsP, c->evict_every) <= 160 * 1024;
+    const bool fits = !keep_all &&
+                      decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, L.cps, L.CsP, c->evict_every) <= 160 * 1024;
     for (int units : {L.U, c->batch * c->n_kv_heads}) {
       const SplitPlan pl = plan_split(L.n_pad, L.G, c->head_dim, c->R, L.cps, L.CsP, c->evict_every > 0 ? c->evict_every : 1,
                                       true, units, L.sp_force, fits);
       if (pl.S > L.sp_smax) L.sp_smax = pl.S;
     }
   }
-  L.offSpW = o; o = align_up(o + (L.sp_smax > 1 ? U * (size_t)L.G * np * 4 : 0));
-  L.offSpPart = o; o = align_up(o + (L.sp_smax > 1 ? U * (size_t)L.sp_smax * split_part_floats(L.G, c->head_dim) * 4 : 0));
-  L.offSpCnt = o; o = align_up(o + (L.sp_smax > 1 ? U * 4 : 0));
+  const bool sp = L.sp_smax > 1 || keep_all;  // (a keep-all layer runs in the split kernel even with one workgroup a unit)
+  L.offSpW = o; o = align_up(o + (sp && !keep_all ? U * (size_t)L.G * np * 4 : 0));
+  L.offSpPart = o; o = align_up(o + (sp ? U * (size_t)L.sp_smax * split_part_floats(L.G, c->head_dim) * 4 : 0));
+  L.offSpCnt = o; o = align_up(o + (sp ? U * 4 : 0));
   L.ring_bytes = o;
   o = 0;
   const size_t Nm = (size_t)c->max_prompt_len;
@@ -242,6 +252,11 @@ struct morphkv_handle {
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
   int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
+  bool keep_all;      // this handle's layers keep every token (Appendix A.6)
+  // A configuration whose first layers keep every token is two handles: this one for the layers that select, and
+  // `keep` for the first keep->cfg.n_layers layers; every call goes to both with its tensors split by layer
+  morphkv_handle *keep;
+  morphkv_config pub;  // the configuration as the caller gave it
 };
 
 namespace {
@@ -269,6 +284,7 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.sp_cnt = (int32_t *)(h->ring + L.offSpCnt);
   P.sp_smax = L.sp_smax;
   P.sp_bps = 0;
+  P.keep_all = h->keep_all ? 1 : 0;
   P.cpt_shift = -1;
   for (int sft = 0; sft < 16; ++sft)
     if ((1 << sft) == L.cpt) P.cpt_shift = sft;
@@ -291,7 +307,8 @@ PrefillParams prefill_params(const morphkv_handle *h, char *scratch_base, const 
   P.pos = (int32_t *)(h->cache + L.offPos);
   P.meta = (int32_t *)(h->cache + L.offMeta);
   P.evl = (int32_t *)(h->cache + L.offEvl);
-  P.sp_cnt = h->L.sp_smax > 1 ? (int32_t *)(h->ring + h->L.offSpCnt) : nullptr;
+  P.sp_cnt = (h->L.sp_smax > 1 || h->keep_all) ? (int32_t *)(h->ring + h->L.offSpCnt) : nullptr;
+  P.keep_all = h->keep_all ? 1 : 0;
   P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.ring = (float *)(h->ring + L.offRing);
   P.sfx = (float *)(h->ring + L.offSfx);
@@ -325,7 +342,7 @@ int decode_threads(const morphkv_handle *h, int U) {
 
 // does the fused kernel's LDS-resident weight array fit (priced for its largest workgroup)?
 bool fused_fits(const morphkv_handle *h) {
-  return decode_lds_bytes(h->L.n_pad, h->L.G, h->cfg.head_dim, 1024, h->cfg.R, h->L.cps, h->L.CsP,
+  return !h->keep_all && decode_lds_bytes(h->L.n_pad, h->L.G, h->cfg.head_dim, 1024, h->cfg.R, h->L.cps, h->L.CsP,
                           h->cfg.evict_every) <= 160 * 1024;
 }
 SplitPlan handle_plan(const morphkv_handle *h, int n_units) {
@@ -344,8 +361,8 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   // (the kernels' dynamic-LDS limits were raised when the handle was made, on the device current then)
   const SplitPlan pl = handle_plan(h, n_units);
   if (pl.S == 0) return fail(MORPHKV_EINVAL, "C + R = %d is too large for the decode kernels' LDS", P.n);
-  if (pl.S > 1) {
-    // few units, or a cache beyond the fused kernel's LDS: several workgroups per unit
+  if (pl.S > 1 || h->keep_all) {
+    // a cache beyond the fused kernel's LDS, a layer that keeps every token, or on request: the split kernel
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
     DecodeParams PS = P;
     PS.sp_bps = pl.bps;
@@ -398,6 +415,33 @@ int dispatch_prefill(const morphkv_handle *h, const PrefillParams &P, hipStream_
                                            : launch_prefill_bf16(h->cfg.head_dim, h->L.G, P, h->L.U, st);
 }
 
+// A configuration with n_keep_all_layers = k > 0 is served by two handles: `keep` for the first k layers, which
+// hold every token (prompt and response: C = max_prompt_len older slots filled at the prompt plus max_new_tokens
+// more, nothing ever selected), and `sel` for the others.  Returns k.
+int split_config(const morphkv_config *c, morphkv_config *keep, morphkv_config *sel) {
+  const int k = c->n_keep_all_layers;
+  *keep = *c;
+  keep->n_layers = k;
+  keep->n_keep_all_layers = 0;
+  keep->C = c->max_prompt_len;
+  keep->evict_every = 0;
+  *sel = *c;
+  sel->n_layers = c->n_layers - k;
+  sel->n_keep_all_layers = 0;
+  return k;
+}
+
+// bytes per layer of the tensors the calls take
+struct LayerStrides { size_t q_win, kv_prompt, lse_win, q_prompt, lse_prompt, q_step, kv_step, out_step; };
+LayerStrides layer_strides(const morphkv_config *c, int Nmax) {
+  const size_t e = c->dtype == MORPHKV_DTYPE_F32 ? 4 : 2, B = (size_t)c->batch, M = (size_t)c->n_q_heads,
+               Mk = (size_t)c->n_kv_heads, d = (size_t)c->head_dim, R = (size_t)c->R, N = (size_t)Nmax;
+  return LayerStrides{B * M * R * d * e, B * Mk * N * d * e, B * M * R * 4, B * M * N * d * e, B * M * N * 4,
+                      B * M * d * e,     B * Mk * d * e,     B * M * d * 4};
+}
+const void *adv(const void *p, size_t bytes) { return p ? (const char *)p + bytes : nullptr; }
+void *adv(void *p, size_t bytes) { return p ? (char *)p + bytes : nullptr; }
+
 // selection over the prompt from the window queries (all three window entries end up here)
 int prefill_window(morphkv_handle *h, const void *Q_window, const void *K, const void *V, const float *lse_window,
                    const int32_t *prompt_len, int32_t Nmax, hipStream_t st, char *scratch_base, const BufLayout &Ls) {
@@ -427,25 +471,34 @@ const char *morphkv_last_error(void) { return g_err; }
 int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_bytes, size_t *scratch_bytes) {
   int rc = validate(cfg);
   if (rc) return rc;
-  const BufLayout L = make_layout(cfg);
-  if (cache_bytes) *cache_bytes = L.cache_bytes;
-  if (ring_bytes) *ring_bytes = L.ring_bytes;
-  if (scratch_bytes) *scratch_bytes = L.scratch_bytes;
+  morphkv_config ck, cs;
+  const int k = split_config(cfg, &ck, &cs);
+  size_t cb = 0, rb = 0, sb = 0;
+  if (k > 0) {
+    const BufLayout L = make_layout(&ck, true);
+    cb += L.cache_bytes; rb += L.ring_bytes; sb = std::max(sb, L.scratch_bytes);
+  }
+  if (k < cfg->n_layers) {
+    const BufLayout L = make_layout(&cs, false);
+    cb += L.cache_bytes; rb += L.ring_bytes; sb = std::max(sb, L.scratch_bytes);
+  }
+  if (cache_bytes) *cache_bytes = cb;
+  if (ring_bytes) *ring_bytes = std::max<size_t>(rb, 256);
+  if (scratch_bytes) *scratch_bytes = sb;
   return MORPHKV_OK;
 }
 
-int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch) {
-  if (!out) return fail(MORPHKV_EINVAL, "handle pointer is null");
+// one handle over layers that all behave alike: cfg is the configuration of those layers alone
+static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool keep_all, void *cache, void *scores_ring,
+                          void *scratch) {
   *out = nullptr;
-  int rc = validate(cfg);
-  if (rc) return rc;
-  if (!cache || !scores_ring || !scratch) return fail(MORPHKV_EINVAL, "cache, scores_ring and scratch must be non-null");
-  if (((uintptr_t)cache | (uintptr_t)scores_ring | (uintptr_t)scratch) & 255)
-    return fail(MORPHKV_EINVAL, "buffers must be 256-byte aligned");
   morphkv_handle *h = new (std::nothrow) morphkv_handle();
   if (!h) return fail(MORPHKV_EINVAL, "out of host memory");
   h->cfg = *cfg;
-  h->L = make_layout(cfg);
+  h->pub = *cfg;
+  h->keep_all = keep_all;
+  h->keep = nullptr;
+  h->L = make_layout(cfg, keep_all);
   h->cache = (char *)cache;
   h->ring = (char *)scores_ring;
   h->scratch = (char *)scratch;
@@ -504,7 +557,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
       delete h;
       return fail(MORPHKV_EINVAL, "C + R = %d needs more LDS than the decode kernels have (limit 163840 bytes)", n);
     }
-    if (pl.S > 1) {
+    if (pl.S > 1 || h->keep_all) {
       const size_t lds = decode_split_lds_bytes(pl.bps, h->L.G, cfg->head_dim, cfg->R, h->L.cps, h->L.CsP,
                                                 cfg->evict_every > 0 ? cfg->evict_every : 1);
       lds_split = lds > lds_split ? lds : lds_split;
@@ -537,8 +590,42 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   return MORPHKV_OK;
 }
 
+int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache, void *scores_ring, void *scratch) {
+  if (!out) return fail(MORPHKV_EINVAL, "handle pointer is null");
+  *out = nullptr;
+  if (const int rc = validate(cfg)) return rc;
+  if (!cache || !scores_ring || !scratch) return fail(MORPHKV_EINVAL, "cache, scores_ring and scratch must be non-null");
+  if (((uintptr_t)cache | (uintptr_t)scores_ring | (uintptr_t)scratch) & 255)
+    return fail(MORPHKV_EINVAL, "buffers must be 256-byte aligned");
+  morphkv_config ck, cs;
+  const int k = split_config(cfg, &ck, &cs);
+  morphkv_handle *hk = nullptr, *hs = nullptr;
+  size_t cache_k = 0, ring_k = 0;
+  if (k > 0) {
+    // the layers that keep every token come first in both buffers; the prompt-time workspace is shared (the two
+    // parts of a call run one after the other on the caller's stream)
+    if (const int rc = create_segment(&hk, &ck, true, cache, scores_ring, scratch)) return rc;
+    cache_k = hk->L.cache_bytes;
+    ring_k = hk->L.ring_bytes;
+    if (k == cfg->n_layers) {
+      hk->pub = *cfg;
+      *out = hk;
+      return MORPHKV_OK;
+    }
+  }
+  if (const int rc = create_segment(&hs, &cs, false, (char *)cache + cache_k, (char *)scores_ring + ring_k, scratch)) {
+    delete hk;
+    return rc;
+  }
+  hs->keep = hk;
+  hs->pub = *cfg;
+  *out = hs;
+  return MORPHKV_OK;
+}
+
 int morphkv_destroy(morphkv_handle *h) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  delete h->keep;
   delete h;
   return MORPHKV_OK;
 }
@@ -551,18 +638,26 @@ int morphkv_prefill_select(morphkv_handle *h, const void *Q_window, const void *
 int morphkv_prefill_select_lse(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                                const float *lse_window, const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (h->keep) {  // the first layers keep every token: their part of the tensors comes first
+    morphkv_handle *k = h->keep;
+    if (const int rc = prefill_window(k, Q_window, K, V, lse_window, prompt_len, Nmax, (hipStream_t)stream, k->scratch, k->L))
+      return rc;
+    const LayerStrides ls = layer_strides(&h->pub, Nmax);
+    const size_t nk = (size_t)k->cfg.n_layers;
+    Q_window = adv(Q_window, nk * ls.q_win); K = adv(K, nk * ls.kv_prompt); V = adv(V, nk * ls.kv_prompt);
+    lse_window = (const float *)adv((const void *)lse_window, nk * ls.lse_win);
+  }
   return prefill_window(h, Q_window, K, V, lse_window, prompt_len, Nmax, (hipStream_t)stream, h->scratch, h->L);
 }
 
-int morphkv_prefill_select_noalloc(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+static int prefill_noalloc_segment(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
                                    const int32_t *prompt_len, int32_t Nmax, void *stream) {
-  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (Nmax < 1 || Nmax > h->cfg.max_prompt_len)
     return fail(MORPHKV_EINVAL, "Nmax %d outside 1..max_prompt_len (%d)", Nmax, h->cfg.max_prompt_len);
   // the workspace is laid out for this call's Nmax, not for the handle's max_prompt_len
   morphkv_config c = h->cfg;
   c.max_prompt_len = Nmax;
-  const BufLayout Ls = make_layout(&c);
+  const BufLayout Ls = make_layout(&c, h->keep_all);
   if (Ls.scratch_bytes > STATIC_SCRATCH_BYTES)
     return fail(MORPHKV_EINVAL,
                 "prefill_select_noalloc: this configuration with Nmax = %d needs %zu bytes of workspace, the library's "
@@ -573,9 +668,20 @@ int morphkv_prefill_select_noalloc(morphkv_handle *h, const void *Q_window, cons
   return prefill_window(h, Q_window, K, V, nullptr, prompt_len, Nmax, (hipStream_t)stream, ws, Ls);
 }
 
-int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O, float *lse,
-                                  const int32_t *prompt_len, int32_t Nmax, void *stream) {
+int morphkv_prefill_select_noalloc(morphkv_handle *h, const void *Q_window, const void *K, const void *V,
+                                   const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (h->keep) {
+    if (const int rc = prefill_noalloc_segment(h->keep, Q_window, K, V, prompt_len, Nmax, stream)) return rc;
+    const LayerStrides ls = layer_strides(&h->pub, Nmax);
+    const size_t nk = (size_t)h->keep->cfg.n_layers;
+    Q_window = adv(Q_window, nk * ls.q_win); K = adv(K, nk * ls.kv_prompt); V = adv(V, nk * ls.kv_prompt);
+  }
+  return prefill_noalloc_segment(h, Q_window, K, V, prompt_len, Nmax, stream);
+}
+
+static int attend_select_segment(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O, float *lse,
+                                 const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!Q || !K || !V || !O || !prompt_len) return fail(MORPHKV_EINVAL, "null input pointer");
   if (h->cfg.dtype != MORPHKV_DTYPE_BF16)
     return fail(MORPHKV_EINVAL, "prefill_attend_select is built for bf16 only");
@@ -609,12 +715,26 @@ int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *
   return MORPHKV_OK;
 }
 
-int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
-                        void *stream) {
+int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *K, const void *V, void *O, float *lse,
+                                  const int32_t *prompt_len, int32_t Nmax, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (h->keep) {
+    if (const int rc = attend_select_segment(h->keep, Q, K, V, O, lse, prompt_len, Nmax, stream)) return rc;
+    const LayerStrides ls = layer_strides(&h->pub, Nmax);
+    const size_t nk = (size_t)h->keep->cfg.n_layers;
+    Q = adv(Q, nk * ls.q_prompt); K = adv(K, nk * ls.kv_prompt); V = adv(V, nk * ls.kv_prompt);
+    O = adv(O, nk * ls.q_prompt);
+    lse = (float *)adv((void *)lse, nk * ls.lse_prompt);
+  }
+  return attend_select_segment(h, Q, K, V, O, lse, prompt_len, Nmax, stream);
+}
+
+static int decode_step_segment(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
+                               void *stream) {
   if (!q || !k_new || !v_new || !out) return fail(MORPHKV_EINVAL, "null pointer");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "decode_step before prefill_select");
-  if (h->cfg.evict_every == 0 && h->steps >= (unsigned)h->cfg.max_new_tokens)
+  if (h->cfg.evict_every == 0 &&
+      h->steps + *std::max_element(h->layer_steps.begin(), h->layer_steps.end()) >= (unsigned)h->cfg.max_new_tokens)
     return fail(MORPHKV_ESTATE, "the cache has room for max_new_tokens = %d decode steps only", h->cfg.max_new_tokens);
   DecodeParams P = decode_params(h);
   P.q = q; P.k_new = k_new; P.v_new = v_new; P.out = out;
@@ -623,9 +743,29 @@ int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, con
   return rc;
 }
 
+int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
+                        void *stream) {
+  if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (h->keep) {
+    if (const int rc = decode_step_segment(h->keep, q, k_new, v_new, out, stream)) return rc;
+    const LayerStrides ls = layer_strides(&h->pub, 1);
+    const size_t nk = (size_t)h->keep->cfg.n_layers;
+    q = adv(q, nk * ls.q_step); k_new = adv(k_new, nk * ls.kv_step); v_new = adv(v_new, nk * ls.kv_step);
+    out = (float *)adv((void *)out, nk * ls.out_step);
+  }
+  return decode_step_segment(h, q, k_new, v_new, out, stream);
+}
+
 int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, const void *k_new, const void *v_new,
                               float *out, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
+  if (h->keep) {  // the first layers live in the handle of the layers that keep every token
+    if (layer >= 0 && layer < h->keep->cfg.n_layers)
+      return morphkv_decode_step_layer(h->keep, layer, q, k_new, v_new, out, stream);
+    if (layer < 0 || layer >= h->pub.n_layers)
+      return fail(MORPHKV_EINVAL, "layer %d outside 0..%d", layer, h->pub.n_layers - 1);
+    layer -= h->keep->cfg.n_layers;
+  }
   if (!q || !k_new || !v_new || !out) return fail(MORPHKV_EINVAL, "null pointer");
   if (layer < 0 || layer >= h->cfg.n_layers)
     return fail(MORPHKV_EINVAL, "layer %d outside 0..%d", layer, h->cfg.n_layers - 1);
@@ -647,11 +787,18 @@ int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, v
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!pos) return fail(MORPHKV_EINVAL, "pos is null");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
-  const BufLayout &L = h->L;
-  hipLaunchKernelGGL(export_positions_kernel, dim3((L.n + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
-                     (const int32_t *)(h->cache + L.offPos), (const int32_t *)(h->cache + L.offMeta), pos, n_snap,
-                     L.n, L.n_pad);
-  HIP_TRY(hipGetLastError());
+  // rows are as long as the longest layer's; each layer's slots come first in its rows, -1 after them
+  const int row = h->keep ? std::max(h->L.n, h->keep->L.n) : h->L.n;
+  for (morphkv_handle *g : {h->keep, h}) {
+    if (!g) continue;
+    const BufLayout &L = g->L;
+    hipLaunchKernelGGL(export_positions_kernel, dim3((row + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
+                       (const int32_t *)(g->cache + L.offPos), (const int32_t *)(g->cache + L.offMeta), pos, n_snap,
+                       L.n, L.n_pad, row);
+    HIP_TRY(hipGetLastError());
+    pos += (size_t)L.U * row;
+    if (n_snap) n_snap += L.U;
+  }
   return MORPHKV_OK;
 }
 
@@ -659,10 +806,14 @@ int morphkv_export_evicted(morphkv_handle *h, int32_t *evicted, void *stream) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!evicted) return fail(MORPHKV_EINVAL, "evicted is null");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
-  const BufLayout &L = h->L;
-  hipLaunchKernelGGL(export_evicted_kernel, dim3((L.U + 255) / 256), dim3(256), 0, (hipStream_t)stream,
-                     (const int32_t *)(h->cache + L.offMeta), evicted, L.U);
-  HIP_TRY(hipGetLastError());
+  for (morphkv_handle *g : {h->keep, h}) {
+    if (!g) continue;
+    const BufLayout &L = g->L;
+    hipLaunchKernelGGL(export_evicted_kernel, dim3((L.U + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                       (const int32_t *)(g->cache + L.offMeta), evicted, L.U);
+    HIP_TRY(hipGetLastError());
+    evicted += L.U;
+  }
   return MORPHKV_OK;
 }
 
@@ -670,9 +821,15 @@ int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *strea
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (!evicted) return fail(MORPHKV_EINVAL, "evicted is null");
   if (!h->prefilled) return fail(MORPHKV_ESTATE, "export before prefill_select");
-  const BufLayout &L = h->L;
   const int T = h->cfg.evict_every;
   if (T <= 1) return morphkv_export_evicted(h, evicted, stream);
+  if (h->keep) {  // layers that keep every token evict nothing
+    const size_t n = (size_t)h->keep->L.U * T;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, evicted, n, -1);
+    HIP_TRY(hipGetLastError());
+    evicted += n;
+  }
+  const BufLayout &L = h->L;
   HIP_TRY(hipMemcpyAsync(evicted, h->cache + L.offEvl, (size_t)L.U * T * 4, hipMemcpyDeviceToDevice,
                          (hipStream_t)stream));
   return MORPHKV_OK;
@@ -680,7 +837,8 @@ int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *strea
 
 int morphkv_capture_scores(morphkv_handle *h, float *F) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
-  h->dbgF = F;
+  // rows of layers that keep every token are left untouched (they never score anything)
+  h->dbgF = (F && h->keep) ? F + (size_t)h->keep->L.U * (h->L.Cs + 1) : F;
   return MORPHKV_OK;
 }
 
@@ -722,7 +880,7 @@ int morphkv_decode_plan(morphkv_handle *h, int32_t n_units, int32_t *workgroups_
 
 int morphkv_capture_phase_clocks(morphkv_handle *h, long long *clocks) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
-  h->dbgT = clocks;
+  h->dbgT = (clocks && h->keep) ? clocks + (size_t)h->keep->L.U * 8 : clocks;
   return MORPHKV_OK;
 }
 

@@ -21,6 +21,7 @@ struct PrefillParams {
   void *Kc, *Vc;
   int32_t *pos, *meta;
   int32_t *evl;            // [U][T] positions evicted by the last step: none yet
+  int32_t keep_all;        // a layer that keeps every token: no scores, no recorded rows; select keeps all, gather
   int32_t *sp_cnt;         // nullable, [U]: arrival counters of the split decode kernel, zeroed here
   float *ring, *sfx, *nw;
   int32_t B, Mq, Mkv, C, Cs, CsP, R, n, n_pad, Nmax, fusion, cps, T;

@@ -8,6 +8,13 @@ namespace {
 template <int D, int G>
 int launch(const PrefillParams &P, int U, hipStream_t st) {
   const int nblk = (P.Nmax + PF_BLOCK - 1) / PF_BLOCK;
+  if (P.keep_all) {
+    // every prompt token is kept (the capacity covers the prompt): positions 0 .. N-R-1 in order, then the gather
+    if (const int rc = launch_prefill_select(P, U, st)) return rc;
+    hipLaunchKernelGGL((prefill_gather_tiled_kernel<D>), dim3(P.n_pad / 32, U), dim3(256), 0, st, P);
+    HIP_TRY(hipGetLastError());
+    return MORPHKV_OK;
+  }
   if (P.lse) {
     hipLaunchKernelGGL((prefill_stats_from_lse_kernel<G>), dim3(U, G, (P.R + 63) / 64), dim3(64), 0, st, P);
     HIP_TRY(hipGetLastError());

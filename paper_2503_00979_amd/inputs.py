@@ -115,6 +115,7 @@ class Workload:
     outlier_scale: float = 5.0
     evict_every: int = 1
     max_new_tokens: int = 0   # only with evict_every == 0 (selection at the prompt only): room for decode steps
+    n_keep_all_layers: int = 0  # the first layers keep every token (selective layer retention); needs max_new_tokens
     key_codes: int = 0        # > 0: every key is one of this many seeded vectors per (layer, KV head), so that
                               # many tokens hold bit-identical keys (inputs with exact ties); 1 = all keys identical
 
@@ -255,8 +256,8 @@ def workload(name: str) -> Workload:
 
 def small_workload(seed: int, *, L=1, B=1, M=4, Mkv=2, d=64, dtype="f32", C=6, R=4, fusion="sum",
                    prompt_lens=(20,), steps=30, n_outlier_channels=0, evict_every=1, max_new_tokens=0,
-                   key_codes=0) -> Workload:
+                   key_codes=0, n_keep_all_layers=0) -> Workload:
     """Free-form small case for tests."""
     return Workload(f"small{seed}", L, B, M, Mkv, d, dtype, C, R, fusion, tuple(prompt_lens), steps, seed,
                     n_outlier_channels=n_outlier_channels, evict_every=evict_every, max_new_tokens=max_new_tokens,
-                    key_codes=key_codes)
+                    key_codes=key_codes, n_keep_all_layers=n_keep_all_layers)

@@ -54,15 +54,20 @@ def _gpu_sets(gpu, wl, umap):
     pos, n_snap = gpu.export_positions()
     pos = pos.cpu().numpy()[umap]
     n_snap = n_snap.cpu().numpy()[umap]
-    # older-token slots: more than C are held between coarse selections, or for good when selection is at the prompt only
-    C = wl.C + (wl.evict_every - 1 if wl.evict_every >= 1 else wl.max_new_tokens)
+    # older-token slots: more than C are held between coarse selections, or for good when selection is at the prompt only;
+    # a layer that keeps every token has max_prompt_len + max_new_tokens of them (its row: those, the window, then -1)
+    C_sel = wl.C + (wl.evict_every - 1 if wl.evict_every >= 1 else wl.max_new_tokens)
+    C_keep = wl.Nmax + wl.max_new_tokens
+    upl = wl.batch * wl.n_kv_heads
     snaps, wins = [], []
     for i in range(len(umap)):
+        C = C_keep if umap[i] // upl < wl.n_keep_all_layers else C_sel
+        assert np.all(pos[i, C + wl.R:] == -1)
         s = pos[i, :C]
         assert np.all(s[n_snap[i]:] == -1), "unused older-token slots must be empty"
         assert np.all(s[:n_snap[i]] >= 0)
         snaps.append(np.sort(s[:n_snap[i]]))
-        wv = pos[i, C:]
+        wv = pos[i, C:C + wl.R]
         for x, pv in enumerate(wv):
             assert pv == -1 or pv % wl.R == x, "window slot must be position mod R"
         wins.append(np.sort(wv[wv >= 0]))

@@ -232,6 +232,67 @@ def test_split_kernel_beyond_fused_lds(oracle_lib):
     assert rep.evictions > 0
 
 
+# ---- selective layer retention (Appendix A.6): the first layers keep every token
+KEEP = [
+    ("k1_of_3", dict(L=3, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=40, R=8, fusion="sum", prompt_lens=(90, 30), steps=60, max_new_tokens=60, n_keep_all_layers=1)),
+    ("k2_of_3_T4_g7", dict(L=3, B=2, M=7, Mkv=1, d=128, dtype="bf16", C=50, R=9, fusion="max", prompt_lens=(200, 61), steps=70, max_new_tokens=70, n_keep_all_layers=2, evict_every=4)),
+    ("all_layers_d64", dict(L=2, B=2, M=4, Mkv=2, d=64, dtype="bf16", C=10, R=5, fusion="sum", prompt_lens=(40, 3), steps=50, max_new_tokens=50, n_keep_all_layers=2)),
+    ("short_prompts", dict(L=2, B=3, M=4, Mkv=2, d=64, dtype="bf16", C=12, R=8, fusion="sum", prompt_lens=(1, 5, 17), steps=40, max_new_tokens=45, n_keep_all_layers=1)),
+]
+
+
+@pytest.mark.parametrize("entry", ["window", "attend", "per_layer"])
+@pytest.mark.parametrize("case", KEEP, ids=[c[0] for c in KEEP])
+def test_keep_all_layers(case, entry, oracle_lib):
+    """One handle, the first layers without MorphKV (every token kept, attention only), the others selecting as
+    configured: outputs of every layer, retained sets, evictions against the layered oracle, every step; through the
+    window entry, the entry fused with the prompt's attention pass, and layer-by-layer decode calls."""
+    name, kw = case
+    wl = inputs.small_workload(15000 + KEEP.index(case), **kw)
+    ls = _lockstep(wl, DEV, use_attend=entry == "attend", per_layer=entry == "per_layer",
+                   capture_scores=wl.evict_every == 1 and wl.n_keep_all_layers < wl.n_layers).prefill()
+    if entry == "attend":
+        _check_attention(wl, ls.attn_out)
+    rep = ls.run(wl.steps, check_every=1)
+    _report(f"keep_{name}_{entry}", rep)
+    pos, n_snap = ls.gpu.export_positions()
+    upl = wl.batch * wl.n_kv_heads
+    for u in range(wl.n_keep_all_layers * upl):      # nothing was ever dropped in the first layers
+        b = (u // wl.n_kv_heads) % wl.batch
+        assert int(n_snap[u]) == max(0, wl.prompt_lens[b] + wl.steps - wl.R)
+    if wl.n_keep_all_layers < wl.n_layers:
+        assert rep.evictions > 0
+    from paper_2503_00979_amd import binding
+    q, k, v = (x.to(DEV) for x in wl.decode_inputs(wl.steps))
+    if wl.steps == wl.max_new_tokens:
+        with pytest.raises(binding.MorphKVError) as e:   # the layers that keep everything are full: refused
+            ls.gpu.decode_step(q, k, v)
+        assert e.value.code == binding.ESTATE
+
+
+def test_keep_all_layers_over_a_16k_token_run(oracle_lib):
+    """L = 4 with layers 0-1 keeping every token of a 15000-token prompt and 1100 generated tokens (16.1 k slots, far
+    beyond what one workgroup's LDS holds), layers 2-3 at C = 2048, R = 128: every step against the layered oracle."""
+    from paper_2503_00979_amd import binding
+    steps = 1100
+    wl = inputs.small_workload(15100, L=4, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=2048, R=128, fusion="sum",
+                               prompt_lens=(15000,), steps=steps, max_new_tokens=steps, n_keep_all_layers=2)
+    mk = lambda **kw: binding.make_config(n_layers=kw.pop("L", 4), batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                                          C_=kw.pop("C", 2048), R=128, fusion="sum", dtype="bf16", max_prompt_len=15000,
+                                          max_new_tokens=steps, **kw)
+    both = binding.morphkv_sizes(mk(n_keep_all_layers=2))
+    sel2 = binding.morphkv_sizes(mk(L=2))
+    # the two layers that keep everything cost their K/V (2 units x 16.1 k slots x 2 x 256 B each) and next to nothing
+    # in recorded rows: no R x (C + R) array
+    n_keep = 15000 + steps + 128
+    assert both[0] - sel2[0] >= 2 * 2 * n_keep * 128 * 2 * 2
+    assert both[1] - sel2[1] < 1 << 20
+    ls = _lockstep(wl, DEV, gen_device=DEV).prefill()
+    rep = _full_size_run(ls, steps, check_every=100)
+    _report("keep_16k", rep)
+    assert rep.evictions == steps * 2 * 2
+
+
 @pytest.mark.parametrize("T", [1, 4])
 def test_per_layer_calls(T, oracle_lib):
     """One call per layer, as a model's attention layers make them, gives what the whole-model call gives."""

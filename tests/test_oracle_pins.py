@@ -548,3 +548,44 @@ def test_forced_prompt_selection_then_bruteforce(oracle_lib, fusion, T):
     # a set that names a token outside the candidates is refused
     with pytest.raises(RuntimeError):
         o.prefill_select(Qw, K, V, np.array([N], np.int32), forced_pos=np.array([[0, 1, 2, 3, N - 1]], np.int32))
+
+
+# --------------------------------------------------------------------------
+# 12. selective layer retention (Appendix A.6): the first layers keep every token.  The layered oracle only routes
+#     tensors: its first layers must be plain dense attention over the whole history (torch, fp64), its other layers
+#     the plain oracle run on those layers alone.
+# --------------------------------------------------------------------------
+def test_layered_oracle_keeps_every_token_in_the_first_layers(oracle_lib):
+    L, k, B, M, Mkv, d, steps = 3, 1, 2, 4, 2, 16, 30
+    wl = inputs.small_workload(1200, L=L, B=B, M=M, Mkv=Mkv, d=d, dtype="bf16", C=6, R=4, fusion="sum",
+                               prompt_lens=(25, 7), steps=steps, max_new_tokens=steps, n_keep_all_layers=k)
+    G = M // Mkv
+    o = oracle_lib.RefMorphKV.from_workload(wl)
+    assert isinstance(o, oracle_lib.RefMorphKVLayered)
+    import dataclasses
+    wl_sel = dataclasses.replace(wl, n_layers=L - k, n_keep_all_layers=0)
+    plain = oracle_lib.RefMorphKV.from_workload(wl_sel)
+    Qw, K, V = wl.prompt()
+    plen = wl.prompt_len_tensor().numpy()
+    o.prefill_select(Qw, K, V, plen)
+    plain.prefill_select(Qw[k:].contiguous(), K[k:].contiguous(), V[k:].contiguous(), plen)
+    hist_k = [K[0, b, :, :wl.prompt_lens[b]].double() for b in range(B)]
+    hist_v = [V[0, b, :, :wl.prompt_lens[b]].double() for b in range(B)]
+    for t in range(steps):
+        q, kn, vn = wl.decode_inputs(t)
+        out = o.decode_step(q, kn, vn)
+        ref = plain.decode_step(q[k:].contiguous(), kn[k:].contiguous(), vn[k:].contiguous())
+        np.testing.assert_array_equal(out[k:], ref)
+        for b in range(B):
+            hist_k[b] = torch.cat([hist_k[b], kn[0, b].double()[:, None, :]], dim=1)
+            hist_v[b] = torch.cat([hist_v[b], vn[0, b].double()[:, None, :]], dim=1)
+            kk = hist_k[b].repeat_interleave(G, dim=0)
+            vv = hist_v[b].repeat_interleave(G, dim=0)
+            att = torch.softmax(torch.einsum("md,mnd->mn", q[0, b].double(), kk) / math.sqrt(d), dim=-1)
+            np.testing.assert_allclose(out[0, b], torch.einsum("mn,mnd->md", att, vv).numpy(), rtol=0, atol=1e-12)
+        snaps, wins = o.export_positions()
+        ps, pw = plain.export_positions()
+        assert [list(x) for x in snaps[k * B * Mkv:]] == [list(x) for x in ps]
+        for u in range(k * B * Mkv):
+            b = (u // Mkv) % B
+            assert sorted(list(snaps[u]) + list(wins[u])) == list(range(wl.prompt_lens[b] + t + 1))
