@@ -898,7 +898,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
-        l.x = exp2f(l.x - M[g]); l.y = exp2f(l.y - M[g]); l.z = exp2f(l.z - M[g]); l.w = exp2f(l.w - M[g]);
+        l.x = exp2_native(l.x - M[g]); l.y = exp2_native(l.y - M[g]); l.z = exp2_native(l.z - M[g]); l.w = exp2_native(l.w - M[g]);
         *pl = l;
         zs[g] += (l.x + l.y) + (l.z + l.w);
       }
@@ -918,7 +918,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     for (int m = 8; m < WAVE; m <<= 1) v += __shfl_xor(v, m);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float es = exp2f(selfl[g] - M[g]);
+      const float es = exp2_native(selfl[g] - M[g]);
       const float z = es + lane_bcast(v, g);
       inv[g] = 1.0f / z;
       pself[g] = es * inv[g];

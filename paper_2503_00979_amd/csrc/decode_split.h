@@ -262,7 +262,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
         if (!keep) ws_store4(wts, (uint32_t)(g * n_pad + j0s + 4 * jq), l);
-        l.x = exp2f(l.x - mref[g]); l.y = exp2f(l.y - mref[g]); l.z = exp2f(l.z - mref[g]); l.w = exp2f(l.w - mref[g]);
+        l.x = exp2_native(l.x - mref[g]); l.y = exp2_native(l.y - mref[g]); l.z = exp2_native(l.z - mref[g]); l.w = exp2_native(l.w - mref[g]);
         *pl = l;
         zs[g] += (l.x + l.y) + (l.z + l.w);
       }
@@ -399,10 +399,10 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     const int g = tid;
     float M = sfl[g];
     for (int ss = 0; ss < S; ++ss) M = fmaxf(M, msl[ss * 8 + g]);
-    const float es = exp2f(sfl[g] - M);
+    const float es = exp2_native(sfl[g] - M);
     float z = es;
     for (int ss = 0; ss < S; ++ss) {
-      const float f = msl[ss * 8 + g] == -INFINITY ? 0.f : exp2f(msl[ss * 8 + g] - M);
+      const float f = msl[ss * 8 + g] == -INFINITY ? 0.f : exp2_native(msl[ss * 8 + g] - M);
       fac[ss * 8 + g] = f;
       z += zsl[ss * 8 + g] * f;
     }
@@ -438,8 +438,8 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float Mg = Mgl[g], ig = invl[g];
-      S4[0] += exp2f(l4[g].x - Mg) * ig; S4[1] += exp2f(l4[g].y - Mg) * ig;
-      S4[2] += exp2f(l4[g].z - Mg) * ig; S4[3] += exp2f(l4[g].w - Mg) * ig;
+      S4[0] += exp2_native(l4[g].x - Mg) * ig; S4[1] += exp2_native(l4[g].y - Mg) * ig;
+      S4[2] += exp2_native(l4[g].z - Mg) * ig; S4[3] += exp2_native(l4[g].w - Mg) * ig;
     }
     stg16_stream(ringu + (size_t)w * n_pad + j0, make_float4(S4[0], S4[1], S4[2], S4[3]));
     if (j0 < n_snap) {
