@@ -39,12 +39,40 @@ def algorithmic_bytes_per_step(wl) -> int:
 
 
 def read_traffic(name: str):
-    """HBM bytes per launch of the decode kernel measured with rocprofv3 counters (profiles/), or None."""
+    """(bytes, source): HBM-side bytes per launch of the decode kernel from the STORED rocprofv3 counter runs under
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Not measured in this run: hardware
+    counters need the profiler around the process."""
     path = os.path.join(ROOT, "profiles", f"decode_fused_{name}_hbm_traffic.json")
     if os.path.exists(path):
         with open(path) as f:
-            return json.load(f).get("traffic_bytes_per_launch")
-    return None
+            return (json.load(f).get("traffic_bytes_per_launch"),
+                    f"stored profile profiles/decode_fused_{name}_hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / "
+                    f"WRITE_SIZE runs of this benchmark; not measured in this run)")
+    return None, None
+
+
+def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8):
+    """Phase time stamps of the fused decode kernel (diagnostics build, bf16 head_dim 128): per unit, microseconds
+    after the launch's first workgroup started; mean / p10 / p90 over units and sampled launches."""
+    import numpy as np
+    import torch
+    clk = g.capture_phase_clocks(True)
+    acc = []
+    for _ in range(launches + 1):
+        run_steps(steps_per_launch_sample)
+        torch.cuda.synchronize()
+        acc.append(clk.cpu().numpy().astype(np.int64).copy())
+    g.capture_phase_clocks(False)
+    a = np.stack(acc)[1:] * 0.01          # 100 MHz clock -> us
+    t0 = a[:, :, 0].min(1, keepdims=True)
+    names = ["workgroup start", "end of the K pass", "end of softmax / record", "end of the V pass", "end of the step",
+             "last wave at the first barrier", "first wave at the first barrier", "first barrier passed"]
+    out = {}
+    for i in (0, 6, 5, 7, 1, 2, 3, 4):
+        x = a[:, :, i] - t0
+        out[names[i]] = [round(float(x.mean()), 2), round(float(np.percentile(x, 10)), 2), round(float(np.percentile(x, 90)), 2)]
+    out["kernel span, first start to last end"] = round(float((a[:, :, 4].max(1) - a[:, :, 0].min(1)).mean()), 2)
+    return out
 
 
 def cpu_baseline(wl, Qw, K, V, dec_inputs, n_steps=200, max_seqs=8):
@@ -107,6 +135,9 @@ def main():
                          "workloads) and report it against the bf16 matrix-core peak")
     ap.add_argument("--no-stream-ref", action="store_true",
                     help="skip the plain streaming-read measurement reported as roofline.stream_read_GBs")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="after the timed region also run the diagnostics build of the fused kernel and report its phase "
+                         "time stamps (config.phase_clocks_us; a table on stderr)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -275,6 +306,19 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         times.append((ev0.elapsed_time(ev1) / 1e3, wall))
+    phases = None
+    if args.phase_clocks:
+        assert not args.per_layer, "--phase-clocks: whole-model launches only"
+        cursor = [W + max(1, args.repeats) * K_steps]
+
+        def run_some(n):
+            run(n, cursor[0])
+            cursor[0] += n
+        phases = phase_clocks(g, run_some, wl.n_units)
+        print(f"phase time stamps of the fused decode kernel, {wl.name}: us after the launch's first workgroup start "
+              f"(mean / p10 / p90 over units and 5 launches)", file=sys.stderr)
+        for k_, v_ in phases.items():
+            print(f"  {k_:40s} {v_}", file=sys.stderr)
     if args.calib_copy_mib > 0:
         src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -307,6 +351,7 @@ def main():
     A = algorithmic_bytes_per_step(wl)
     launches = K_steps * (nl if args.per_layer else 1)
     achieved = A / (sec / K_steps) / 1e9
+    traffic, traffic_src = (None, None) if (args.per_layer or wl.evict_every > 1 or args.fusion) else read_traffic(wl.name)
     res = {
         "metric": "decode steps/s incl. KV selection (B=32, 8B shape) on 1 GPU; % HBM roofline",
         "value": K_steps / sec, "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
@@ -322,9 +367,11 @@ def main():
                    "prefill_select_first_call_ms": pf[0],
                    **({"prefill_select_lse_ms": prefill_lse_ms} if prefill_lse_ms is not None else {}),
                    **({"prompt_attention": attend} if attend is not None else {}),
+                   "workgroups_per_unit": g.decode_plan(wl.batch * wl.n_kv_heads if args.per_layer else None)[0],
+                   **({"phase_clocks_us": phases} if phases is not None else {}),
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.per_layer or wl.evict_every > 1) else read_traffic(wl.name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "stream_read_GBs": stream_gbs,
                      "frac_of_stream_read": (achieved / stream_gbs) if stream_gbs else None,
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A * K_steps // launches,

@@ -31,7 +31,9 @@ int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* A plain read of `bytes` (multiple of 16) of device memory; every 16-byte piece is loaded once and
  * folded into sink[256] (device, uint32, xor-accumulated: zero it first if the value matters).  Times what the
- * device sustains when a kernel only streams: the practical ceiling next to the 8 TB/s of the data sheet. */
+ * device sustains when a kernel only streams: the practical ceiling next to the 8 TB/s of the data sheet.  Buffers
+ * of more than 208 MiB are read with non-temporal loads, as the decode kernels read what they do not keep in the
+ * memory-side cache. */
 int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream);
 
 /* How a decode launch over n_units units (all of the handle's, or one layer's) is laid out: 1 workgroup per unit

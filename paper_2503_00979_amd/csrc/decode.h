@@ -529,9 +529,9 @@ template <typename T, int D, int G, bool CLK>
 __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
-  // tile groups (K) and tiles (V) a wave keeps in flight.  Two of each (which needs groups of at most 512
-  // threads for the registers) was measured and brought nothing: the passes are not bound by the depth
-  // of a wave's request queue.
+  // tile groups (K) and tiles (V) a wave keeps in flight.  Two of each was measured on 512-thread groups and
+  // brought nothing (the passes are not bound by the depth of a wave's request queue); at 1024 threads two K
+  // groups do not fit the 128 registers (the head_dim 128 builds spill), so it stays at one.
   constexpr int KBUF = 1, VBUF = 1;
   extern __shared__ __align__(16) float smem[];
 

@@ -13,7 +13,9 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(uint4 *dst, const uint4
 
 // ---- plain read: every workgroup streams a contiguous share, 8 independent 16-byte loads per thread in flight,
 // everything folded into one word per workgroup (so that the loads stay); what the device sustains when a kernel
-// does nothing but stream
+// does nothing but stream.  STREAM: non-temporal loads, as the decode kernels use for what does not fit the
+// memory-side cache.
+template <bool STREAM>
 __global__ __launch_bounds__(1024) void calib_read_kernel(uint32_t *sink, const uint4 *src, size_t nvec, size_t per_block) {
   constexpr int UNR = 8;
   const size_t lo = (size_t)blockIdx.x * per_block, hi = lo + per_block < nvec ? lo + per_block : nvec;
@@ -23,12 +25,12 @@ __global__ __launch_bounds__(1024) void calib_read_kernel(uint32_t *sink, const 
   for (; i + (size_t)(UNR - 1) * NT < hi; i += (size_t)UNR * NT) {
     uint4 r[UNR];
 #pragma unroll
-    for (int k = 0; k < UNR; ++k) r[k] = src[i + (size_t)k * NT];
+    for (int k = 0; k < UNR; ++k) r[k] = ldg16<STREAM>(src + i + (size_t)k * NT);
 #pragma unroll
     for (int k = 0; k < UNR; ++k) acc ^= r[k].x ^ r[k].y ^ r[k].z ^ r[k].w;
   }
   for (; i < hi; i += NT) {
-    const uint4 v = src[i];
+    const uint4 v = ldg16<STREAM>(src + i);
     acc ^= v.x ^ v.y ^ v.z ^ v.w;
   }
 #pragma unroll

@@ -863,8 +863,13 @@ int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stre
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
   else (void)hipGetLastError();
   const size_t per_block = (nvec + (size_t)n_cu - 1) / (size_t)n_cu;
-  hipLaunchKernelGGL(calib_read_kernel, dim3(n_cu), dim3(1024), 0, (hipStream_t)stream, sink, (const uint4 *)src, nvec,
-                     per_block);
+  // beyond what the decode kernels would keep cache-resident the read streams with non-temporal loads, as they do
+  if (bytes > ((size_t)208 << 20))
+    hipLaunchKernelGGL(calib_read_kernel<true>, dim3(n_cu), dim3(1024), 0, (hipStream_t)stream, sink, (const uint4 *)src,
+                       nvec, per_block);
+  else
+    hipLaunchKernelGGL(calib_read_kernel<false>, dim3(n_cu), dim3(1024), 0, (hipStream_t)stream, sink, (const uint4 *)src,
+                       nvec, per_block);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }

@@ -17,7 +17,7 @@ def trace(db, nlast):
     c = sqlite3.connect(db)
     rows = list(c.execute(
         "select name,start,end,duration,grid_x,workgroup_x,lds_size,vgpr_count,accum_vgpr_count,scratch_size "
-        "from kernels where name like '%decode_fused_kernel%' order by start"))
+        "from kernels where name like '%decode_fused_kernel%' or name like '%decode_split_kernel%' order by start"))
     last = rows[-nlast:]
     d = [r[3] / 1e3 for r in last]
     gaps = [(last[i + 1][1] - last[i][2]) / 1e3 for i in range(len(last) - 1)]
@@ -26,6 +26,7 @@ def trace(db, nlast):
           f"agpr={last[0][8]} scratch={last[0][9]}")
     print(f"dispatches total={len(rows)}; steady-state sample = last {nlast} dispatches (the timed region)")
     print(f"duration us: mean={st.mean(d):.2f} median={st.median(d):.2f} min={min(d):.2f} max={max(d):.2f}")
+    print(f"start-to-start period us: mean={st.mean([(last[i + 1][1] - last[i][1]) / 1e3 for i in range(len(last) - 1)]):.2f}")
     print(f"gap between consecutive dispatches us: mean={st.mean(gaps):.2f} median={st.median(gaps):.2f}")
 
 
@@ -33,7 +34,7 @@ def pmc(db, nlast):
     c = sqlite3.connect(db)
     rows = c.execute(
         "select name, counter_name, dispatch_id, sum(counter_value), max(duration) from pmc_events "
-        "where name like '%decode_fused%' or name like '%calib_copy%' "
+        "where name like '%decode_fused%' or name like '%decode_split%' or name like '%calib_copy%' "
         "group by name, counter_name, dispatch_id order by dispatch_id")
     d = defaultdict(list)
     for name, cn, did, val, dur in rows:
