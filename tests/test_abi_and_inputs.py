@@ -107,3 +107,24 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_keep_all_layers_sizes_and_validation_on_host():
+    """Layers that keep every token (n_keep_all_layers): their K/V for max_prompt_len + max_new_tokens + R slots are
+    added to the cache, next to nothing to the recorded rows; bad combinations are refused with the reason."""
+    base = dict(n_layers=4, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, C_=256, R=32, fusion="sum", dtype="bf16",
+                max_prompt_len=4096, max_new_tokens=512)
+    c0, r0, _ = binding.morphkv_sizes(binding.make_config(**base))
+    c2, r2, _ = binding.morphkv_sizes(binding.make_config(**base, n_keep_all_layers=2))
+    sel2 = dict(base, n_layers=2)
+    cs, rs, _ = binding.morphkv_sizes(binding.make_config(**sel2))
+    n_keep = 4096 + 512 + 32
+    units = 2 * 2 * 2                                   # 2 layers x batch 2 x 2 KV heads
+    assert c2 - cs >= units * n_keep * 128 * 2 * 2      # K and V, bf16
+    assert c2 - cs <= units * (n_keep + 64) * (128 * 2 * 2 + 4) + (1 << 16)
+    assert r2 - rs < 1 << 20 and r0 > rs
+    for bad, word in ((dict(n_keep_all_layers=5), "n_keep_all_layers"), (dict(n_keep_all_layers=1, max_new_tokens=0), "max_new_tokens"),
+                      (dict(n_keep_all_layers=1, dtype="f32"), "bf16"), (dict(n_keep_all_layers=-1), "n_keep_all_layers")):
+        with pytest.raises(binding.MorphKVError) as e:
+            binding.morphkv_sizes(binding.make_config(**dict(base, **bad)))
+        assert e.value.code == binding.EINVAL and word in str(e.value)
