@@ -51,7 +51,7 @@ def read_traffic(name: str):
     return None, None
 
 
-def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8):
+def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8, dump=None):
     """Phase time stamps of the fused decode kernel (diagnostics build, bf16 head_dim 128): per unit, microseconds
     after the launch's first workgroup started; mean / p10 / p90 over units and sampled launches."""
     import numpy as np
@@ -64,6 +64,8 @@ def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8):
         acc.append(clk.cpu().numpy().astype(np.int64).copy())
     g.capture_phase_clocks(False)
     a = np.stack(acc)[1:] * 0.01          # 100 MHz clock -> us
+    if dump:
+        np.save(dump, a)                  # [launch, unit, stamp] for a look at which units end late
     t0 = a[:, :, 0].min(1, keepdims=True)
     names = ["workgroup start", "end of the K pass", "end of softmax / record", "end of the V pass", "end of the step",
              "last wave at the first barrier", "first wave at the first barrier", "first barrier passed"]
@@ -138,6 +140,9 @@ def main():
     ap.add_argument("--phase-clocks", action="store_true",
                     help="after the timed region also run the diagnostics build of the fused kernel and report its phase "
                          "time stamps (config.phase_clocks_us; a table on stderr)")
+    ap.add_argument("--phase-clocks-dump", default=None,
+                    help="with --phase-clocks: also save the raw time stamps [launch, unit, stamp] (us) to this .npy file")
+    ap.add_argument("--phase-clocks-launches", type=int, default=5, help="launches sampled by --phase-clocks")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region also run 4 plain copies of this many MiB (yardstick for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -314,9 +319,9 @@ def main():
         def run_some(n):
             run(n, cursor[0])
             cursor[0] += n
-        phases = phase_clocks(g, run_some, wl.n_units)
+        phases = phase_clocks(g, run_some, wl.n_units, launches=args.phase_clocks_launches, dump=args.phase_clocks_dump)
         print(f"phase time stamps of the fused decode kernel, {wl.name}: us after the launch's first workgroup start "
-              f"(mean / p10 / p90 over units and 5 launches)", file=sys.stderr)
+              f"(mean / p10 / p90 over units and {args.phase_clocks_launches} launches)", file=sys.stderr)
         for k_, v_ in phases.items():
             print(f"  {k_:40s} {v_}", file=sys.stderr)
     if args.calib_copy_mib > 0:
