@@ -85,7 +85,9 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
  * MORPHKV_SPLIT_BPS (bf16: a positive value splits every unit over several workgroups of that many 32-slot blocks
  * each; unset or 0 = only units that one workgroup cannot hold are split),
  * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel; raised where the
- * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least) and
+ * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least),
+ * MORPHKV_REBUILD_WAVES (1..16: how many waves of a unit's workgroup share the per-step rebuild of score aggregates;
+ * rounding of sums may differ in the last bit between values, the retained sets stay within the tie tolerance) and
  * MORPHKV_CACHE_BUDGET_MB (bf16 caches; default 208: how much of the handle's K/V is read with ordinary loads
  * and so stays in the device's 256 MB memory-side cache from step to step; the rest is streamed with
  * non-temporal loads that leave that cache alone). */

@@ -55,6 +55,7 @@ struct DecodeParams {
                            // fused or selected; the token leaving the window is appended to the older tokens
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
+  int32_t rb_waves;        // fused kernel: at most this many waves of a workgroup rebuild the columns whose turn it is
   int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)
   int32_t io_u0;           // unit whose rows come first in q, k_new, v_new and out (u0 when the step's tensors
                            // are one layer's own, 0 when they cover the whole model)
@@ -179,24 +180,32 @@ __device__ inline void wave_argmin(float &f, int &p, int &c) {
   }
 }
 
-// One wave rebuilds the aggregate state of the columns whose turn it is at the start of step p
+// A wave rebuilds the aggregate state of some of the columns whose turn it is at the start of step p
 // (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1.  Results stay in LDS:
 //   stage[i*cpt + cc] = f(rows of steps p-1-i .. p-1) of column c0+cc   (i = 0..R-2), to be stored to
 //                       sfx row (p-2-i) mod R by the whole workgroup later;
 //   turn[cc]          = f(all R-1 rows): the old part of this step's score for that column.
 // The columns are dealt out in groups of gw to the rebuilding waves (group k to wave k mod nrw).  Within
 // a group lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc), which it
-// loads in batches of RB and scans one after the other.  gw is chosen so that a chunk is two batches at
-// most: the chain of dependent loads is what the rest of the workgroup waits for at the end of the K pass.
-constexpr int RB = 16;  // rows per lane and batch
-// columns per group: 64 lanes / gw columns = row chunks, each at most 2*RB rows
-__host__ __device__ inline int turn_group_width(int R) {
+// loads as one batch and scans on their way into LDS; the chunks' totals are then carried over by lane shuffles.
+// gw is chosen (a) so that a chunk fits one batch (R - 1 <= 64 batches always does) and (b), in the fused kernel, so
+// small that each of the waves meant to rebuild (DecodeParams::rb_waves) gets a group: the rebuild is a chain of
+// dependent steps that the rest of the workgroup waits for at the end of the K pass.  Many waves with short chunks
+// shorten the chain; but every wave that takes part runs the whole of this code, and the four waves of a SIMD
+// share its issue slots, so a unit with little else to do is better off with two waves.
+constexpr int RB = 8;  // rows per lane and batch in the fused kernel
+// columns per group: 64 lanes / gw columns = row chunks, each at most `rows` rows
+__host__ __device__ inline int turn_group_width(int R, int rows) {
   int gw = WAVE;
-  while (gw > 1 && (R - 1 + WAVE / gw - 1) / (WAVE / gw) > 2 * RB) gw >>= 1;
+  while (gw > 1 && (R - 1 + WAVE / gw - 1) / (WAVE / gw) > rows) gw >>= 1;
   return gw;
 }
-// RBT = rows per lane and batch: RB where registers are short; 2 * RB takes a whole chunk in one batch, i.e. one
-// round trip to memory
+// ... and narrow enough that cps columns make a group for each of NW waves, if there are that many columns
+__host__ __device__ inline int turn_group_width(int R, int rows, int cps, int NW) {
+  int gw = turn_group_width(R, rows);
+  while (gw > 1 && (cps + gw - 1) / gw < NW) gw >>= 1;
+  return gw;
+}
 template <int RBT> struct TurnRebuildT {
   int lane, p, R, rs, cpt, fusion, c0, ncol, r_top, gw, gstride, g0;
   const float *ringu;
@@ -206,13 +215,13 @@ template <int RBT> struct TurnRebuildT {
 
   // k-th of nrw rebuilding waves
   __device__ inline void init(int lane_, int p_, int wm1, int n_snap, int R_, int rs_, int cps, int cpt_,
-                              int fusion_, const float *ringu_, int k, int nrw) {
+                              int fusion_, const float *ringu_, int k, int nrw, int gw_) {
     lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_;
     r_top = wm1;  // (p-1) mod R: ring row of row i = 0
     c0 = wm1 * cps;
     ncol = n_snap - c0;
     ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
-    gw = turn_group_width(R);
+    gw = gw_;
     g0 = k * gw;
     gstride = nrw * gw;
   }
@@ -228,61 +237,83 @@ template <int RBT> struct TurnRebuildT {
     Lc = (R - 1 + Q - 1) >> (6 - lg2);  // Q = 64 >> lg2
     i0 = min(q * Lc, R - 1); i1 = min(i0 + Lc, R - 1);
   }
-  // rows i0+b .. i0+b+RB-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
+  // rows i0+b .. i0+b+RBT-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
   __device__ inline void load(int b, float (&v)[RBT]) const {
     // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is ignored
-    // when the batch is consumed, so issuing it is straight-line code that waits for nothing
+    // when the batch is consumed, so issuing it is straight-line code that waits for nothing.  Past the end of
+    // a short chunk the chunk's last row is asked for again: the same cache line, no new request to memory.
     const int ib = i0 + b;
     int r0 = r_top - ib;  // ib < R
     r0 += r0 < 0 ? R : 0;
     const unsigned coff = (unsigned)(colok ? c : c0);
+    const int klast = Lc - 1 - b > 0 ? Lc - 1 - b : 0;
 #pragma unroll
     for (int k = 0; k < RBT; ++k) {
-      int r = r0 - k;       // rows of the chunk wrap at most once; past its end any row will do
+      int r = r0 - (k < klast ? k : klast);
       r += r < 0 ? R : 0;
       r = r < 0 ? 0 : r;
       v[k] = ringu[(unsigned)(r * rs) + coff];
     }
-
   }
   __device__ inline void begin(float (&v)[RBT]) {
     if (ncol > g0) { group(g0); load(0, v); }
   }
   __device__ inline void finish(float (&v)[RBT], float *stage, float *turn) {
     if (ncol <= g0) return;
-    int b = 0;
-    float acc = 0.f;
     while (true) {
-      float *st = stage + cg + cc;
-      const int ib = i0 + b;
+      // the lane's chunk, scanned.  A chunk of one short batch waits in registers for its carry; a longer one
+      // (RBT > 8, or R - 1 > 64 batches: several batches a chunk) goes to LDS as it is scanned
+      const int nv = i1 - i0;
+      const bool inreg = RBT <= 8 && Lc <= RBT;  // the same for all lanes
+      float *st = stage + cg + cc + i0 * cpt;
+      float acc = 0.f;
+      if (inreg) {
 #pragma unroll
-      for (int k = 0; k < RBT; ++k)
-        if (ib + k < i1) {
-          acc = fuse2(fusion, acc, v[k]);
-          st[(ib + k) * cpt] = acc;
+        for (int k = 0; k < RBT; ++k)
+          if (k < nv) {
+            acc = fuse2(fusion, acc, v[k]);
+            v[k] = acc;
+          }
+      } else {
+        for (int b = 0;;) {
+#pragma unroll
+          for (int k = 0; k < RBT; ++k)
+            if (b + k < nv) {
+              acc = fuse2(fusion, acc, v[k]);
+              st[(b + k) * cpt] = acc;
+            }
+          b += RBT;
+          if (b >= Lc) break;
+          load(b, v);
         }
-      b += RBT;
-      if (b >= Lc) {
-        // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
-        float incl = acc;
-        for (int s = CP; s < WAVE; s <<= 1) {
-          const float o = __shfl_up(incl, s);
-          if (lane >= s) incl = fuse2(fusion, incl, o);
-        }
-        float carry = __shfl_up(incl, CP);
-        if (q == 0) carry = 0.f;
-        const float total = __shfl(incl, (Q - 1) * CP + cc);
-        if (q > 0) {
-#pragma unroll 8
-          for (int i = i0; i < i1; ++i) st[i * cpt] = fuse2(fusion, st[i * cpt], carry);
-        }
-        if (q == 0) turn[cg + cc] = total;
-        if (cg + gstride >= ncol) break;
-        group(cg + gstride);
-        b = 0;
-        acc = 0.f;
       }
-      load(b, v);
+      // chunk totals -> carry into each chunk (exclusive scan over q), and the total over all rows
+      float incl = acc;
+      for (int s = CP; s < WAVE; s <<= 1) {
+        const float o = __shfl_up(incl, s);
+        if (lane >= s) incl = fuse2(fusion, incl, o);
+      }
+      float carry = __shfl_up(incl, CP);
+      if (q == 0) carry = 0.f;
+      if (q == Q - 1) turn[cg + cc] = incl;
+      if (inreg) {
+#pragma unroll
+        for (int k = 0; k < RBT; ++k)
+          if (k < nv) st[k * cpt] = fuse2(fusion, v[k], carry);
+      } else if (q > 0) {
+        // eight values are read back before any is written: one LDS round trip for the eight, not one each
+        for (int kb = 0; kb < nv; kb += 8) {
+          float t[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) t[j] = kb + j < nv ? st[(kb + j) * cpt] : 0.f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (kb + j < nv) st[(kb + j) * cpt] = fuse2(fusion, t[j], carry);
+        }
+      }
+      if (cg + gstride >= ncol) break;
+      group(cg + gstride);
+      load(0, v);
     }
   }
 };
@@ -669,15 +700,16 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       if (a < R - 1 && win_full) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
     }
   }
-  // ---- the last waves rebuild the columns whose turn it is (one wave per group of columns, at most half
-  // of the waves)
+  // ---- the waves rebuild the columns whose turn it is, a group of columns each
   TurnRebuild tr;
   float rbv[RB];
-  const int tgw = turn_group_width(R);
+  const int rbw = P.rb_waves < NW ? (P.rb_waves < 1 ? 1 : P.rb_waves) : NW;
+  const int tgw = turn_group_width(R, RB, cps, rbw);
   int nrw = (cps + tgw - 1) / tgw;
-  nrw = nrw > NW / 2 ? NW / 2 : nrw;
+  nrw = nrw > rbw ? rbw : nrw;
   if (wave >= NW - nrw) {
-    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
+    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw, tgw);
+    tr.begin(rbv);  // its rows are on their way while the wave works off its first tile group
   }
 
   // ---- self logit (every lane ends up with all G values)
@@ -742,11 +774,8 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   lds_barrier();  // the tile counter is initialised
   if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 7] = wall_clock64();
 
-  // ---- the last waves first rebuild the columns whose turn it is, then join the K pass
-  if (wave >= NW - nrw) {
-    tr.begin(rbv);
-    tr.finish(rbv, stage, turn);
-  }
+  // ---- rebuild of the columns whose turn it is, then the rest of the K pass
+  if (wave >= NW - nrw) tr.finish(rbv, stage, turn);
 
   // ---- K pass, the rest
   if constexpr (L::tiled) {

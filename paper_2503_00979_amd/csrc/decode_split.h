@@ -29,6 +29,7 @@
 namespace mkv {
 
 constexpr int SPLIT_NT = 256, SPLIT_NW = SPLIT_NT / WAVE;
+constexpr int SPLIT_RB = 32;  // rows per lane of the rebuild: a lane's whole chunk in one batch
 constexpr int SPLIT_MAX = 32;  // workgroups per unit at most
 
 // agent-scope (sc1) accesses to the workspace
@@ -187,14 +188,14 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     if (a < R - 1 && win_full && !keep) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
   }
   // the rebuild's loads (one batch: a lane's whole chunk of rows) go out now, are consumed after the K loop
-  TurnRebuildT<2 * RB> tr;
-  float rbv[2 * RB];
-  const int tgw = turn_group_width(R);
+  TurnRebuildT<SPLIT_RB> tr;
+  float rbv[SPLIT_RB];
+  const int tgw = turn_group_width(R, SPLIT_RB);
   int nrw = (cps + tgw - 1) / tgw;
   nrw = nrw > NW / 2 ? NW / 2 : nrw;
   const bool rebuilds = wave >= NW - nrw && !keep;
   if (rebuilds) {
-    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw);
+    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw, tgw);
     tr.begin(rbv);
   }
   // ---- logits of the share

@@ -252,6 +252,7 @@ struct morphkv_handle {
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
   int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
+  int rb_waves;       // waves of a workgroup that rebuild aggregates (see decode.h); MORPHKV_REBUILD_WAVES overrides
   bool keep_all;      // this handle's layers keep every token (Appendix A.6)
   // A configuration whose first layers keep every token is two handles: this one for the layers that select, and
   // `keep` for the first keep->cfg.n_layers layers; every call goes to both with its tensors split by layer
@@ -279,6 +280,7 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.zig = (int32_t)(h->steps & 1u);
   P.nt_k = h->nt_k;
   P.nt_v = h->nt_v;
+  P.rb_waves = h->rb_waves;
   P.sp_w = (float *)(h->ring + L.offSpW);
   P.sp_part = (float *)(h->ring + L.offSpPart);
   P.sp_cnt = (int32_t *)(h->ring + L.offSpCnt);
@@ -535,6 +537,16 @@ static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool 
       h->nt_k = (int)(fk * kgroups + 0.5);
       h->nt_v = (int)((fv > 1.0 ? 1.0 : fv) * vtiles + 0.5);
     }
+  }
+  // How many waves of a workgroup rebuild aggregates (any number is correct; measured on this device): all of
+  // them where the K pass is long enough to hide that every wave then runs the rebuild's code, few where it is not
+  {
+    const int kgroups = (h->L.n_pad / 16 + 1) / 2;
+    h->rb_waves = kgroups >= 64 ? (cfg->R <= 128 ? 16 : 8) : kgroups >= 32 ? 4 : 2;
+  }
+  if (const char *e = std::getenv("MORPHKV_REBUILD_WAVES")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 16) h->rb_waves = v;
   }
   if (const char *e = std::getenv("MORPHKV_DECODE_THREADS")) {
     const int v = std::atoi(e);
