@@ -555,8 +555,11 @@ __device__ __forceinline__ void compact_and_commit(const StepTail<T> &c, uint4 k
   }
 }
 
-// CLK: the diagnostics build that stores phase time stamps to P.dbgT; the product build carries none of it
-template <typename T, int D, int G, bool CLK>
+// CLK: the diagnostics build that stores phase time stamps to P.dbgT; the product build carries none of it.
+// COARSE: the build for selection every T > 1 steps (Appendix A.5).  The every-step build carries none of that code:
+// its scalars alone cost the kernel fifty registers that the compiler then keeps in vector lanes, and every wave
+// pays for moving them there and back.
+template <typename T, int D, int G, bool CLK, bool COARSE>
 __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
@@ -593,7 +596,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   float *shf = (float *)(sh + 16);        // [16] 0: weight of the new row on the token leaving the window;
                                           //      1..8: logits of the token against its own key; 9: its score
   // selection every T > 1 steps only:
-  const int Tev = P.T;
+  const int Tev = COARSE ? P.T : 1;
   float *Fl = shf + 16;                   // [CsP] fused score per older-token slot
   int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP] its position
   float *colw = (float *)(Pl + (Tev > 1 ? CsP : 0));      // [NW][R] a column of the R rows per wave, oldest first
@@ -613,7 +616,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   const int32_t *meta = P.meta + (size_t)u * META;
   const int n_snap = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
   const int gen_step = p - meta[4] + 1;                  // the new token is this sequence's gen_step-th generated one
-  const bool sel_step = P.T > 1 && gen_step % P.T == 0;  // coarse schedule: a step at which a selection may run
+  const bool sel_step = COARSE && P.T > 1 && gen_step % P.T == 0;  // coarse schedule: a step at which a selection may run
 
   // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
   // depends on the unit's state (the addresses do not)
@@ -1198,7 +1201,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   // ---- selection among more than C+1 candidates (coarse schedule), compaction, commit: shared with the split kernel
   StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w, cum, fusion, Tev,
                  sh, shf, Fl, Pl, colw, lists, best2, colv, ringu, sfxu, nwu, posu, knew, vnew};
-  coarse_select_and_move<T, D>(tc);
+  if constexpr (COARSE) coarse_select_and_move<T, D>(tc);
   compact_and_commit<T, D, CLK>(tc);
 }
 
@@ -1207,13 +1210,13 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 // there is lost for waves that skipped the branch (seen: the fp32 d=64 G=8 build moved only 16 of a key's 256
 // bytes at compaction).  So no build may spill vector registers: the bf16 builds fit 128 registers (1024-thread
 // groups); the fp32 builds, which keep G x 4 products per lane in flight, get 256 (groups of at most 512).
-template <typename T, int D, int G, bool CLK = false>
+template <typename T, int D, int G, bool CLK, bool COARSE>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {
-  decode_fused_body<T, D, G, CLK>(P);
+  decode_fused_body<T, D, G, CLK, COARSE>(P);
 }
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool COARSE>
 __global__ __launch_bounds__(512) void decode_fused_kernel_512(DecodeParams P) {
-  decode_fused_body<T, D, G, false>(P);
+  decode_fused_body<T, D, G, false, COARSE>(P);
 }
 
 }  // namespace mkv

@@ -1,4 +1,5 @@
-// Fused decode step, bf16 caches (MFMA path): the product builds for head_dim 64 / 128 and group sizes 1..8.
+// Fused decode step, bf16 caches (MFMA path), selection at every step: the product builds for head_dim 64 / 128
+// and group sizes 1..8.
 #include "host.h"
 #include "decode.h"
 
@@ -6,13 +7,13 @@ namespace mkv {
 namespace {
 template <int D, int G>
 int launch(const DecodeParams &P, const DecodeLaunch &L) {
-  hipLaunchKernelGGL((decode_fused_kernel<bf16_t, D, G, false>), dim3(L.n_units), dim3(L.threads), L.lds, L.stream, P);
+  hipLaunchKernelGGL((decode_fused_kernel<bf16_t, D, G, false, false>), dim3(L.n_units), dim3(L.threads), L.lds, L.stream, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }
 template <int D, int G>
 int lds_limit(size_t lds) {
-  HIP_TRY(hipFuncSetAttribute((const void *)decode_fused_kernel<bf16_t, D, G, false>,
+  HIP_TRY(hipFuncSetAttribute((const void *)decode_fused_kernel<bf16_t, D, G, false, false>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   return MORPHKV_OK;
 }

@@ -1,5 +1,5 @@
-// Fused decode step, fp32 caches (plain FMA path; small and toy configurations): head_dim 64 / 128, group
-// sizes 1..8.  These builds keep G x 4 products per lane in flight and get 256 registers: workgroups of at most
+// Fused decode step, fp32 caches (plain FMA path; small and toy configurations), selection at every step: head_dim 64 / 128,
+// group sizes 1..8.  These builds keep G x 4 products per lane in flight and get 256 registers: workgroups of at most
 // 512 threads.
 #include "host.h"
 #include "decode.h"
@@ -8,13 +8,13 @@ namespace mkv {
 namespace {
 template <int D, int G>
 int launch(const DecodeParams &P, const DecodeLaunch &L) {
-  hipLaunchKernelGGL((decode_fused_kernel_512<float, D, G>), dim3(L.n_units), dim3(L.threads), L.lds, L.stream, P);
+  hipLaunchKernelGGL((decode_fused_kernel_512<float, D, G, false>), dim3(L.n_units), dim3(L.threads), L.lds, L.stream, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }
 template <int D, int G>
 int lds_limit(size_t lds) {
-  HIP_TRY(hipFuncSetAttribute((const void *)decode_fused_kernel_512<float, D, G>,
+  HIP_TRY(hipFuncSetAttribute((const void *)decode_fused_kernel_512<float, D, G, false>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   return MORPHKV_OK;
 }

@@ -39,20 +39,26 @@ struct DecodeLaunch {
   int threads;     // per workgroup
   size_t lds;      // dynamic LDS bytes
   bool clocks;     // the build that stores phase time stamps (diagnostics)
+  bool coarse;     // the build for selection every T > 1 steps
   hipStream_t stream;
 };
 
-// fused decode step, one workgroup per unit (decode_bf16.hip, decode_bf16_clk.hip, decode_f32.hip)
+// fused decode step, one workgroup per unit (decode_bf16.hip, decode_bf16_coarse.hip, decode_bf16_clk.hip,
+// decode_f32.hip, decode_f32_coarse.hip); the clocks build takes any selection schedule
 int launch_decode_bf16_product(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
+int launch_decode_bf16_coarse(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
 int launch_decode_bf16_clocks(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
 int launch_decode_f32(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
+int launch_decode_f32_coarse(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
 // the same step with S workgroups per unit (decode_split.hip); L.threads is ignored (fixed by the kernel)
 int launch_decode_split(int D, int G, const DecodeParams &P, const DecodeLaunch &L, int S);
 int decode_lds_limit_split(int D, int G, size_t lds);
 // raise the kernels' dynamic-LDS limit on the current device
 int decode_lds_limit_bf16_product(int D, int G, size_t lds);
+int decode_lds_limit_bf16_coarse(int D, int G, size_t lds);
 int decode_lds_limit_bf16_clocks(int D, int G, size_t lds);
 int decode_lds_limit_f32(int D, int G, size_t lds);
+int decode_lds_limit_f32_coarse(int D, int G, size_t lds);
 
 // selection over the prompt (prefill_bf16.hip, prefill_f32.hip); the two steps both element types share
 // (top-C select, aggregate state of the columns) live in prefill_f32.hip

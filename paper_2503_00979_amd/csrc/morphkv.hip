@@ -359,6 +359,7 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   DecodeLaunch L{};
   L.n_units = n_units;
   L.clocks = P.dbgT != nullptr;
+  L.coarse = P.T > 1;
   L.stream = st;
   // (the kernels' dynamic-LDS limits were raised when the handle was made, on the device current then)
   const SplitPlan pl = handle_plan(h, n_units);
@@ -379,9 +380,10 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   if (h->min_lds > L.lds && h->min_lds <= 160 * 1024) L.lds = h->min_lds;
   if (f32) {
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for bf16 caches with head_dim 128 only");
-    return launch_decode_f32(D, G, P, L);
+    return L.coarse ? launch_decode_f32_coarse(D, G, P, L) : launch_decode_f32(D, G, P, L);
   }
-  return L.clocks ? launch_decode_bf16_clocks(D, G, P, L) : launch_decode_bf16_product(D, G, P, L);
+  if (L.clocks) return launch_decode_bf16_clocks(D, G, P, L);
+  return L.coarse ? launch_decode_bf16_coarse(D, G, P, L) : launch_decode_bf16_product(D, G, P, L);
 }
 
 // raises the decode kernels' dynamic-LDS limit for this handle's configuration on the current device (once, at
@@ -404,8 +406,10 @@ int dispatch_lds_limit(const morphkv_handle *h, size_t lds, size_t lds_split) {
   if (lds <= cur) return MORPHKV_OK;
   if (f32) {
     if (const int rc = decode_lds_limit_f32(D, G, lds)) return rc;
+    if (const int rc = decode_lds_limit_f32_coarse(D, G, lds)) return rc;
   } else {
     if (const int rc = decode_lds_limit_bf16_product(D, G, lds)) return rc;
+    if (const int rc = decode_lds_limit_bf16_coarse(D, G, lds)) return rc;
     if (const int rc = decode_lds_limit_bf16_clocks(D, G, lds)) return rc;
   }
   cur = lds;
