@@ -55,7 +55,8 @@ struct DecodeParams {
                            // fused or selected; the token leaving the window is appended to the older tokens
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
-  int32_t rb_waves;        // fused kernel: at most this many waves of a workgroup rebuild the columns whose turn it is
+  int32_t rb_gw, rb_nrw;   // fused kernel: columns per group of the rebuild (turn_group_width) and the number of waves
+                           // that rebuild, worked out by the host for the launch's workgroup size
   int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)
   int32_t io_u0;           // unit whose rows come first in q, k_new, v_new and out (u0 when the step's tensors
                            // are one layer's own, 0 when they cover the whole model)
@@ -189,7 +190,7 @@ __device__ inline void wave_argmin(float &f, int &p, int &c) {
 // a group lanes are (column cc, row chunk q): a lane owns the contiguous rows [q*Lc, (q+1)*Lc), which it
 // loads as one batch and scans on their way into LDS; the chunks' totals are then carried over by lane shuffles.
 // gw is chosen (a) so that a chunk fits one batch (R - 1 <= 64 batches always does) and (b), in the fused kernel, so
-// small that each of the waves meant to rebuild (DecodeParams::rb_waves) gets a group: the rebuild is a chain of
+// small that each of the waves meant to rebuild (DecodeParams::rb_nrw) gets a group: the rebuild is a chain of
 // dependent steps that the rest of the workgroup waits for at the end of the K pass.  Many waves with short chunks
 // shorten the chain; but every wave that takes part runs the whole of this code, and the four waves of a SIMD
 // share its issue slots, so a unit with little else to do is better off with two waves.
@@ -228,8 +229,8 @@ template <int RBT> struct TurnRebuildT {
   __device__ inline void group(int cg_) {
     cg = cg_;
     const int nc = ncol - cg < gw ? ncol - cg : gw;
-    CP = 1; lg2 = 0;
-    while (CP < nc) { CP <<= 1; ++lg2; }
+    lg2 = nc <= 1 ? 0 : 32 - __builtin_clz(nc - 1);
+    CP = 1 << lg2;
     Q = WAVE >> lg2;
     cc = lane & (CP - 1); q = lane >> lg2;
     colok = cc < nc;
@@ -570,6 +571,8 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   extern __shared__ __align__(16) float smem[];
 
   const int u = blockIdx.x + P.u0, tid = threadIdx.x, NT = blockDim.x, NW = NT / WAVE;
+  // (the wave's index stays a per-lane value: as a scalar it turns the waves' branches into jumps, which was
+  // measured slower by a microsecond per launch although it saves vector instructions)
   const int wave = tid / WAVE, lane = tid % WAVE;
   const int Cs = P.Cs, CsP = P.CsP, R = P.R, n_pad = P.n_pad, cps = P.cps, cpt = P.cpt;
   // Running-sum policy (fusion 2, the accumulated score of H2O): a column's score is the sum of everything recorded
@@ -706,10 +709,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   // ---- the waves rebuild the columns whose turn it is, a group of columns each
   TurnRebuild tr;
   float rbv[RB];
-  const int rbw = P.rb_waves < NW ? (P.rb_waves < 1 ? 1 : P.rb_waves) : NW;
-  const int tgw = turn_group_width(R, RB, cps, rbw);
-  int nrw = (cps + tgw - 1) / tgw;
-  nrw = nrw > rbw ? rbw : nrw;
+  const int tgw = P.rb_gw, nrw = P.rb_nrw;
   if (wave >= NW - nrw) {
     tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw, tgw);
     tr.begin(rbv);  // its rows are on their way while the wave works off its first tile group

@@ -280,7 +280,6 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.zig = (int32_t)(h->steps & 1u);
   P.nt_k = h->nt_k;
   P.nt_v = h->nt_v;
-  P.rb_waves = h->rb_waves;
   P.sp_w = (float *)(h->ring + L.offSpW);
   P.sp_part = (float *)(h->ring + L.offSpPart);
   P.sp_cnt = (int32_t *)(h->ring + L.offSpCnt);
@@ -377,13 +376,21 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   if (f32 && L.threads > 512) L.threads = 512;  // fp32 builds: 256 registers a lane, groups of at most 512 threads
   L.lds = decode_lds_bytes(P.n_pad, G, D, L.threads, P.R, P.cps, P.CsP, P.T);
   if (L.lds > 160 * 1024) return fail(MORPHKV_EINVAL, "C + R = %d needs %zu bytes of LDS (limit 163840)", P.n, L.lds);
+  // the rebuild's shape for this workgroup size: columns per group, waves that take part
+  DecodeParams PF = P;
+  {
+    const int NW = L.threads / WAVE, rbw = h->rb_waves < NW ? h->rb_waves : NW;
+    PF.rb_gw = turn_group_width(P.R, RB, P.cps, rbw);
+    const int groups = (P.cps + PF.rb_gw - 1) / PF.rb_gw;
+    PF.rb_nrw = groups < rbw ? groups : rbw;
+  }
   if (h->min_lds > L.lds && h->min_lds <= 160 * 1024) L.lds = h->min_lds;
   if (f32) {
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for bf16 caches with head_dim 128 only");
-    return L.coarse ? launch_decode_f32_coarse(D, G, P, L) : launch_decode_f32(D, G, P, L);
+    return L.coarse ? launch_decode_f32_coarse(D, G, PF, L) : launch_decode_f32(D, G, PF, L);
   }
-  if (L.clocks) return launch_decode_bf16_clocks(D, G, P, L);
-  return L.coarse ? launch_decode_bf16_coarse(D, G, P, L) : launch_decode_bf16_product(D, G, P, L);
+  if (L.clocks) return launch_decode_bf16_clocks(D, G, PF, L);
+  return L.coarse ? launch_decode_bf16_coarse(D, G, PF, L) : launch_decode_bf16_product(D, G, PF, L);
 }
 
 // raises the decode kernels' dynamic-LDS limit for this handle's configuration on the current device (once, at
