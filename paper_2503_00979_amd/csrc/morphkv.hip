@@ -336,9 +336,18 @@ int decode_threads(const morphkv_handle *h, int U) {
   if (U >= 8 * cu && h->cfg.R <= 512) return 128;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
-  // few units: the launch is a latency chain, and for a cache under 1024 slots 16 waves only add to its
-  // barriers (c4 layer by layer, 544 slots: 594 -> 555 us per step)
-  return h->L.n_pad < 1024 ? 512 : 1024;
+  // few units: the launch is a chain of latencies and of instructions that every wave issues (the four waves of a
+  // SIMD share its issue slots), so: as few waves as take the cache's tile groups of 32 slots in the same number of
+  // rounds as 16 waves would (c4 layer by layer, 17 groups: 9 waves, 515 -> 483 us per step; c2, 34 groups: 12
+  // waves, 14.1 -> 13.7 us).  Long caches stream: all 16 waves.
+  const int groups = h->L.n_pad / 32;
+  if (h->cfg.dtype != MORPHKV_DTYPE_BF16) return h->L.n_pad < 1024 ? 512 : 1024;
+  if (groups > 48) return 1024;
+  const int rounds = (groups + 15) / 16;
+  int nw = 4;
+  while ((groups + nw - 1) / nw > rounds) ++nw;
+  while (4 * 64 * nw < h->cfg.R - 1 && nw < 16) ++nw;  // (the leaving token's column: at most 4 rows a thread)
+  return 64 * nw;
 }
 
 // does the fused kernel's LDS-resident weight array fit (priced for its largest workgroup)?
