@@ -112,7 +112,7 @@ inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, 
 }
 
 __device__ inline bool slot_valid(int j, int n_snap, int Cs, int nwin) {
-  return j < n_snap || (j >= Cs && j < Cs + nwin);
+  return j < n_snap || (unsigned)(j - Cs) < (unsigned)nwin;  // (one comparison for Cs <= j < Cs + nwin)
 }
 
 // 16-byte global load; STREAM: with the non-temporal hint (the line is not kept in the caches it passes)
@@ -161,6 +161,16 @@ __device__ inline float wave_max_dpp(float v) {
   v = fmaxf(v, dpp_mov<DPP_XOR1>(v)); v = fmaxf(v, dpp_mov<DPP_XOR2>(v));
   v = fmaxf(v, dpp_mov<DPP_HALF_MIRROR>(v)); v = fmaxf(v, dpp_mov<DPP_MIRROR>(v));
   return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
+}
+// maximum over the lanes l, l ^ 16, l ^ 32, l ^ 48 (same column of the four rows of 16), in every lane: the two
+// row-swap instructions of this device give a lane its partner row's value without a trip through LDS
+__device__ inline float max_over_rows(float v) {
+  const int b = __builtin_bit_cast(int, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(b, b, false, false);   // a[0]: even row's value, a[1]: odd row's
+  v = fmaxf(__builtin_bit_cast(float, (int)a[0]), __builtin_bit_cast(float, (int)a[1]));
+  const int c = __builtin_bit_cast(int, v);
+  const auto d = __builtin_amdgcn_permlane32_swap(c, c, false, false);   // d[0]: lower half's value, d[1]: upper's
+  return fmaxf(__builtin_bit_cast(float, (int)d[0]), __builtin_bit_cast(float, (int)d[1]));
 }
 // eviction candidate order: does (of, op) go before (f, p)?  smaller score first, on equal score the
 // higher position
@@ -738,9 +748,11 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   }
   // ---- K pass, first part: each wave works off the tile group it asked for at the very start and asks
   // for a second one, all before the workgroup's first barrier (late waves do not hold the others up)
-  float mx[G];
+  // running maximum of the logits: per head on the FMA path (a lane sees every head of its rows); on the MFMA
+  // path a lane only ever sees the head lane & 15, so one value does
+  float mx[L::tiled ? 1 : G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) mx[g] = -INFINITY;
+  for (int g = 0; g < (L::tiled ? 1 : G); ++g) mx[g] = -INFINITY;
   [[maybe_unused]] const int head = lane & 15, kq = lane >> 4;
   auto process_kgroup = [&](const uint4 (&src)[TU][KBc], int grp) {
     const int gidx = zig ? kngrp - 1 - grp : grp;
@@ -760,9 +772,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
             const int j = tile * 16 + 4 * kq + i;
             l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
           }
-          const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
-#pragma unroll
-          for (int g = 0; g < G; ++g) mx[g] = g == head ? fmaxf(mx[g], m4) : mx[g];
+          mx[0] = fmaxf(fmaxf(mx[0], fmaxf(l4[0], l4[1])), fmaxf(l4[2], l4[3]));
           *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
         }
       }
@@ -873,10 +883,16 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     }
   }
   // a lane saw only some heads / rows: combine across the wave
+  if constexpr (L::tiled) {
+    // lanes l, l + 16, l + 32, l + 48 hold the same head
+    const float v = max_over_rows(mx[0]);
+    if (lane < G) red[wave * 8 + lane] = v;
+  } else {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float v = wave_max_dpp(mx[g]);
-    if (lane == 0) red[wave * 8 + g] = v;
+    for (int g = 0; g < G; ++g) {
+      const float v = wave_max_dpp(mx[g]);
+      if (lane == 0) red[wave * 8 + g] = v;
+    }
   }
 
 #pragma unroll
