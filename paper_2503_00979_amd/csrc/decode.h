@@ -172,6 +172,15 @@ __device__ inline float max_over_rows(float v) {
   const auto d = __builtin_amdgcn_permlane32_swap(c, c, false, false);   // d[0]: lower half's value, d[1]: upper's
   return fmaxf(__builtin_bit_cast(float, (int)d[0]), __builtin_bit_cast(float, (int)d[1]));
 }
+__device__ inline float sum_over_rows(float v) {
+  const int b = __builtin_bit_cast(int, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+  v = __builtin_bit_cast(float, (int)a[0]) + __builtin_bit_cast(float, (int)a[1]);
+  const int c = __builtin_bit_cast(int, v);
+  const auto d = __builtin_amdgcn_permlane32_swap(c, c, false, false);
+  return __builtin_bit_cast(float, (int)d[0]) + __builtin_bit_cast(float, (int)d[1]);
+}
+constexpr int DPP_ROW_ROR8 = 0x128;  // lane l of a row of 16 reads lane (l + 8) mod 16
 // eviction candidate order: does (of, op) go before (f, p)?  smaller score first, on equal score the
 // higher position
 __device__ inline bool cand_before(float f, int p, float of, int op) { return of < f || (of == f && op > p); }
@@ -180,15 +189,24 @@ template <int CTRL> __device__ inline void argmin_step(float &f, int &p, int &c)
   const int op = dpp_mov_i<CTRL>(p), oc = dpp_mov_i<CTRL>(c);
   if (cand_before(f, p, of, op)) { f = of; p = op; c = oc; }
 }
+// the candidate that goes first among a lane's row partners (SWAP32: the two halves of the wave, else the even and
+// the odd row of each half); every lane ends up with the winner
+template <bool SWAP32> __device__ inline void argmin_rows(float &f, int &p, int &c) {
+  const int fb = __builtin_bit_cast(int, f);
+  const auto F = SWAP32 ? __builtin_amdgcn_permlane32_swap(fb, fb, false, false) : __builtin_amdgcn_permlane16_swap(fb, fb, false, false);
+  const auto Pp = SWAP32 ? __builtin_amdgcn_permlane32_swap(p, p, false, false) : __builtin_amdgcn_permlane16_swap(p, p, false, false);
+  const auto Cc = SWAP32 ? __builtin_amdgcn_permlane32_swap(c, c, false, false) : __builtin_amdgcn_permlane16_swap(c, c, false, false);
+  const float f0 = __builtin_bit_cast(float, (int)F[0]), f1 = __builtin_bit_cast(float, (int)F[1]);
+  const bool second = cand_before(f0, (int)Pp[0], f1, (int)Pp[1]);
+  f = second ? f1 : f0;
+  p = second ? (int)Pp[1] : (int)Pp[0];
+  c = second ? (int)Cc[1] : (int)Cc[0];
+}
 __device__ inline void wave_argmin(float &f, int &p, int &c) {
   argmin_step<DPP_XOR1>(f, p, c); argmin_step<DPP_XOR2>(f, p, c);
   argmin_step<DPP_HALF_MIRROR>(f, p, c); argmin_step<DPP_MIRROR>(f, p, c);
-#pragma unroll
-  for (int m = 16; m <= 32; m <<= 1) {
-    const float of = __shfl_xor(f, m);
-    const int op = __shfl_xor(p, m), oc = __shfl_xor(c, m);
-    if (cand_before(f, p, of, op)) { f = of; p = op; c = oc; }
-  }
+  argmin_rows<false>(f, p, c);
+  argmin_rows<true>(f, p, c);
 }
 
 // A wave rebuilds the aggregate state of some of the columns whose turn it is at the start of step p
@@ -932,8 +950,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     float v = -INFINITY;
     if ((lane >> 3) < NW) v = red[lane];
     if ((lane >> 3) + 8 < NW) v = fmaxf(v, red[lane + 64]);
-#pragma unroll
-    for (int m = 8; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+    v = max_over_rows(fmaxf(v, dpp_mov<DPP_ROW_ROR8>(v)));  // over the lanes of equal head: l, l ^ 8, l ^ 16, l ^ 32
 #pragma unroll
     for (int g = 0; g < G; ++g) M[g] = fmaxf(selfl[g], lane_bcast(v, g));
   }
@@ -962,8 +979,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     float v = 0.f;
     if ((lane >> 3) < NW) v = red2[lane];
     if ((lane >> 3) + 8 < NW) v += red2[lane + 64];
-#pragma unroll
-    for (int m = 8; m < WAVE; m <<= 1) v += __shfl_xor(v, m);
+    v = sum_over_rows(v + dpp_mov<DPP_ROW_ROR8>(v));
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float es = exp2_native(selfl[g] - M[g]);
