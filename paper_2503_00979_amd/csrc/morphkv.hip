@@ -158,6 +158,18 @@ SplitPlan plan_split(int n_pad, int G, int D, int R, int cps, int CsP, int T, bo
   if (bps < bps_min) bps = bps_min;
   if (bps < 1) bps = 1;
   SplitPlan pl{(nblk + bps - 1) / bps, bps};
+  if (force_bps <= 0 && n_units < N_CU_REF && pl.S > 1) {
+    // The shares' limit may have raised the number of workgroups to one that does not go evenly over the compute
+    // units (64 units of 16 k slots: 5 workgroups each = 320 on 256 units, and the launch takes as long as 512
+    // would): then the next number that does, if it is in reach
+    int g = n_units, r = N_CU_REF;
+    while (r) { const int t = g % r; g = r; r = t; }
+    const int m = N_CU_REF / g, S2 = (pl.S + m - 1) / m * m;
+    if (S2 != pl.S && S2 <= SPLIT_MAX && S2 <= 2 * pl.S) {
+      bps = (nblk + S2 - 1) / S2;
+      pl = SplitPlan{(nblk + bps - 1) / bps, bps};
+    }
+  }
   if (pl.S < 2 && fused_fits) return one;
   if (bps > bps_lds || decode_split_lds_bytes(bps, G, D, R, cps, CsP, T) > 160 * 1024) return SplitPlan{0, 0};  // does not fit
   return pl;
@@ -176,9 +188,9 @@ BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
   // rebuilt aggregates go out as one run of cps floats per sfx row: runs that are whole 128-byte lines (else
   // 64, 32 .. bytes) keep partial-line writes away from HBM, which cost several us per step on c3-sized
   // caches when the run was 17 floats.  Rounded up as far as the LDS staging area (R x cps floats) allows.
-  const int cps0 = (L.Cs + c->R - 1) / c->R;
+  const int cps0 = keep_all ? 1 : (L.Cs + c->R - 1) / c->R;  // (a layer that keeps every token rebuilds nothing)
   L.cps = cps0;
-  for (int a = 32; a > 1; a >>= 1) {
+  for (int a = keep_all ? 1 : 32; a > 1; a >>= 1) {
     const int cand = (cps0 + a - 1) / a * a;
     const size_t stage = (size_t)c->R * turn_cols_padded(cand) * 4;
     if (stage <= 32 * 1024 &&

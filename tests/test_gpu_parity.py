@@ -293,6 +293,20 @@ def test_keep_all_layers_over_a_16k_token_run(oracle_lib):
     assert rep.evictions == steps * 2 * 2
 
 
+def test_keep_all_layer_of_40k_tokens(oracle_lib):
+    """A layer that keeps every token of a 40000-token prompt (10 workgroups a unit) next to a selecting layer: such a
+    layer rebuilds no aggregates, so its workgroups need no LDS for them and its length is bounded by the shares alone."""
+    steps = 48
+    wl = inputs.small_workload(40100, L=2, B=1, M=4, Mkv=1, d=128, dtype="bf16", C=512, R=128, fusion="max",
+                               prompt_lens=(40000,), steps=steps, max_new_tokens=steps, n_keep_all_layers=1)
+    ls = _lockstep(wl, DEV, gen_device=DEV).prefill()
+    rep = ls.run(steps, check_every=8)
+    _report("keep_40k", rep)
+    pos, n = ls.gpu.export_positions()
+    assert int(n[0]) == 40000 + steps - 128        # older tokens of the first layer: nothing dropped
+    assert int(n[1]) == 512
+
+
 @pytest.mark.parametrize("T", [1, 4])
 def test_per_layer_calls(T, oracle_lib):
     """One call per layer, as a model's attention layers make them, gives what the whole-model call gives."""
