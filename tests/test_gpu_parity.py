@@ -388,14 +388,16 @@ def test_comparison_policies(case, oracle_lib):
         assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
 
 
+@pytest.mark.parametrize("T", [1, 3])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("G", range(1, 9))
-def test_every_kernel_instantiation(dtype, d, G, oracle_lib):
-    """One short lock-step run per (element type, head dimension, group size): each is a kernel build of its own,
-    with its own register allocation (a build that spilled registers once moved only part of a key)."""
+def test_every_kernel_instantiation(dtype, d, G, T, oracle_lib):
+    """One short lock-step run per (element type, head dimension, group size, every-step or coarse schedule): each is a
+    kernel build of its own, with its own register allocation (a build that spilled registers once moved only part of
+    a key)."""
     wl = inputs.small_workload(555, L=1, B=2, M=G, Mkv=1, d=d, dtype=dtype, C=20, R=6, fusion="sum",
-                               prompt_lens=(50, 9), steps=30)
+                               prompt_lens=(50, 9), steps=30, evict_every=T)
     rep = _lockstep(wl, DEV).prefill().run(wl.steps, check_every=1)
     assert rep.evictions > 0
 
