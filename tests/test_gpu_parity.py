@@ -197,6 +197,30 @@ def test_split_kernel_forced(case, bps, oracle_lib, monkeypatch):
         assert rep.near_ties_decode == 0 and rep.exact_ties_decode > 0
 
 
+REBUILD = [
+    # (R - 1 rows, columns per step) of different shapes: chunks of 1..8 rows, one or several groups a wave
+    ("c2ish", dict(L=1, B=2, M=8, Mkv=2, d=128, dtype="bf16", C=1024, R=64, fusion="max", prompt_lens=(2000, 1100), steps=70)),
+    ("short_rows", dict(L=1, B=1, M=4, Mkv=1, d=128, dtype="bf16", C=700, R=9, fusion="sum", prompt_lens=(900,), steps=30)),
+    ("long_rows_g7", dict(L=1, B=1, M=7, Mkv=1, d=128, dtype="bf16", C=600, R=300, fusion="sum", prompt_lens=(1500,), steps=310)),
+]
+
+
+@pytest.mark.parametrize("threads", [256, 576, 1024])
+@pytest.mark.parametrize("waves", [1, 3, 16])
+@pytest.mark.parametrize("case", REBUILD, ids=[c[0] for c in REBUILD])
+def test_rebuild_shapes(case, waves, threads, oracle_lib, monkeypatch):
+    """The per-step rebuild of score aggregates in every shape the host may choose for it (waves that take part,
+    threads per unit: they set columns per group, rows per lane and groups per wave), over a full rotation of the
+    window, every step against the oracle with the scores captured."""
+    name, kw = case
+    monkeypatch.setenv("MORPHKV_REBUILD_WAVES", str(waves))
+    monkeypatch.setenv("MORPHKV_DECODE_THREADS", str(threads))
+    wl = inputs.small_workload(16000 + REBUILD.index(case), **kw)
+    rep = _lockstep(wl, DEV, capture_scores=True).prefill().run(wl.steps, check_every=1)
+    _report(f"rebuild_{name}_w{waves}_t{threads}", rep)
+    assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
+
+
 def test_split_kernel_per_layer_calls_at_c4_size(oracle_lib, monkeypatch):
     """c4 called layer by layer, as a model calls it: 64 units a launch, here spread over 4 workgroups a unit; the
     oracle follows one sequence through all 32 layers."""
