@@ -25,17 +25,21 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 
 
-def algorithmic_bytes_per_step(wl) -> int:
+def algorithmic_bytes_per_step(wl, keep_tokens: float = 0.0) -> int:
     """Bytes the method must move per decode step in steady state (per unit, times U):
     K and V of the C+R resident tokens read once; the new row of recorded weights written;
     the score state (one aggregate row read, the running aggregate read and written);
     q, k_new, v_new in, the new token's K/V written, fp32 output; one K/V row moved and one
-    column of the R rows moved on compaction."""
+    column of the R rows moved on compaction.  Units of layers that keep every token (Appendix A.6) read the K
+    and V of the `keep_tokens` tokens they hold and write the new token's; they have no score state."""
     d, s, G, R = wl.head_dim, wl.elem_bytes, wl.G, wl.R
     C = wl.C + (wl.evict_every - 1) / 2.0   # older tokens held, averaged over the T steps between selections
     n = C + R
     per_unit = (2 * n * d * s) + 4 * n + 12 * (C + 1) + (G + 4) * d * s + 4 * G * d + 4 * d * s + 8 * R
-    return int(per_unit * wl.n_units)
+    upl = wl.batch * wl.n_kv_heads
+    k = getattr(wl, "n_keep_all_layers", 0)
+    per_keep_unit = 2 * keep_tokens * d * s + (G + 4) * d * s + 4 * G * d + 2 * d * s
+    return int(per_unit * (wl.n_layers - k) * upl + per_keep_unit * k * upl)
 
 
 def read_traffic(name: str):
@@ -127,6 +131,9 @@ def main():
                     help="override the workload's fusion; cumsum = the running-sum comparison policy (H2O's score)")
     ap.add_argument("--evict-every", type=int, default=1,
                     help="T of the coarse schedule (Appendix A.5): selection at every T-th step")
+    ap.add_argument("--keep-all-layers", type=int, default=0,
+                    help="the first K layers keep every token (Appendix A.6: selective layer retention); their caches "
+                         "grow during the run, the bytes are priced at their mean length over the timed region")
     ap.add_argument("--prefill-repeats", type=int, default=3,
                     help="prefill_select is run this many times on the same prompts (it rewrites all state); the "
                          "median is reported as prefill_select_ms")
@@ -163,6 +170,13 @@ def main():
         import dataclasses
         wl = dataclasses.replace(wl, evict_every=args.evict_every, fusion=args.fusion or wl.fusion)
     K_steps, W = args.steps, args.warmup
+    if args.keep_all_layers:
+        import dataclasses
+        assert wl.dtype == "bf16" and 0 < args.keep_all_layers <= wl.n_layers and args.no_cpu_baseline, \
+            "--keep-all-layers: bf16 workloads, with --no-cpu-baseline"
+        fill = max(0, max(wl.C + wl.R - n for n in wl.prompt_lens))
+        wl = dataclasses.replace(wl, n_keep_all_layers=args.keep_all_layers,
+                                 max_new_tokens=fill + W + max(1, args.repeats) * K_steps + 64)
 
     # ---- setup (untimed): prompts, prompt-time selection, run until every cache is full
     g = binding.MorphKV.from_workload(wl, dev)
@@ -353,10 +367,14 @@ def main():
     dev_s, wall_s = times[len(times) // 2]
     sec = max(dev_s, 0.0)                      # HIP events on the launch stream bracket exactly the K kernels
     ms_per_step = sec / K_steps * 1e3
-    A = algorithmic_bytes_per_step(wl)
-    launches = K_steps * (nl if args.per_layer else 1)
+    # (layers that keep everything: tokens held at the middle of the timed region, mean over the batch)
+    keep_tokens = (sum(wl.prompt_lens) / len(wl.prompt_lens) + fill_steps + W + max(1, args.repeats) * K_steps / 2.0
+                   if args.keep_all_layers else 0.0)
+    A = algorithmic_bytes_per_step(wl, keep_tokens)
+    launches = K_steps * (nl if args.per_layer else (2 if 0 < args.keep_all_layers < nl else 1))
     achieved = A / (sec / K_steps) / 1e9
-    traffic, traffic_src = (None, None) if (args.per_layer or wl.evict_every > 1 or args.fusion) else read_traffic(wl.name)
+    traffic, traffic_src = ((None, None) if (args.per_layer or wl.evict_every > 1 or args.fusion or args.keep_all_layers)
+                            else read_traffic(wl.name))
     res = {
         "metric": "decode steps/s incl. KV selection (B=32, 8B shape) on 1 GPU; % HBM roofline",
         "value": K_steps / sec, "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
@@ -365,6 +383,8 @@ def main():
         "config": {"workload": f"{wl.name}: L={wl.n_layers} B={wl.batch} M={wl.n_q_heads} M'={wl.n_kv_heads} "
                                f"d={wl.head_dim} C={wl.C} R={wl.R} fusion={wl.fusion} {wl.dtype}, steady state"
                                + (f", selection every {wl.evict_every} steps" if wl.evict_every > 1 else "")
+                               + (f", first {args.keep_all_layers} layers keep every token (about {keep_tokens:.0f} each "
+                                  f"during the timed steps)" if args.keep_all_layers else "")
                                + (f", {nl} launches per step (one per layer)" if args.per_layer else "")
                                + (", two steps per HIP graph replay" if args.graph else ""),
                    "units": wl.n_units, "fill_steps": fill_steps, "repeats": args.repeats,
@@ -372,14 +392,17 @@ def main():
                    "prefill_select_first_call_ms": pf[0],
                    **({"prefill_select_lse_ms": prefill_lse_ms} if prefill_lse_ms is not None else {}),
                    **({"prompt_attention": attend} if attend is not None else {}),
-                   "workgroups_per_unit": g.decode_plan(wl.batch * wl.n_kv_heads if args.per_layer else None)[0],
+                   "workgroups_per_unit": g.decode_plan(wl.batch * wl.n_kv_heads if args.per_layer else
+                                                       (nl - args.keep_all_layers) * wl.batch * wl.n_kv_heads
+                                                       if 0 < args.keep_all_layers < nl else None)[0],
                    **({"phase_clocks_us": phases} if phases is not None else {}),
                    "pct_hbm_roofline": 100.0 * achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "stream_read_GBs": stream_gbs,
                      "frac_of_stream_read": (achieved / stream_gbs) if stream_gbs else None,
-                     "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": A * K_steps // launches,
+                     "kernel": "decode_fused_kernel" + (" + decode_split_kernel" if args.keep_all_layers else ""),
+                     "algorithmic_bytes_per_launch": A * K_steps // launches,
                      "avg_launch_us": sec / launches * 1e6},
     }
     if not args.no_cpu_baseline:

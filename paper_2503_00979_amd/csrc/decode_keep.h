@@ -1,0 +1,236 @@
+// Decode step of a layer that keeps every token (Appendix A.6, selective layer retention): attention of the new
+// token over everything the unit holds, then the token leaving the window joins the older tokens.  Nothing is
+// recorded, fused or selected in such a layer, so no weight has to outlive the tile it was computed for: the
+// softmax runs ONLINE (running maximum and sum per head, the output accumulators rescaled when the maximum
+// moves), a block of 32 slots goes K tiles -> logits -> weights -> V tile -> output without ever being written
+// down, and the cache's length is bounded by nothing but the memory the caller gave.
+//
+// One workgroup of KEEP_NT threads per unit; a wave takes the blocks wave, wave + NW, ... of the unit's resident
+// slots (older tokens [0, n_snap), window [Cs, Cs + nwin)) with its own (maximum, sum, output); the waves'
+// results are merged through LDS at the end (Eq.1: softmax over all resident tokens and the token itself).
+// bf16 caches in MFMA tile order (Layout<bf16_t, D>), like the fused kernel.
+#pragma once
+#include "decode.h"
+
+namespace mkv {
+
+constexpr int KEEP_NT = 512, KEEP_NW = KEEP_NT / WAVE;
+constexpr int KEEP_PS = 36;  // floats per head row of a wave's weight staging tile (32 slots + 4: rows start 4 banks apart)
+
+// dynamic LDS of decode_keep_kernel
+inline size_t decode_keep_lds_bytes(int G, int D) {
+  return ((size_t)KEEP_NW * 16 * KEEP_PS /*weights of a block per wave*/ + (size_t)KEEP_NW * 16 /*rescale factors*/ +
+          2 * (size_t)KEEP_NW * 16 /*maxima, sums*/ + (size_t)KEEP_NW * G * D /*outputs*/ + 16 + 16) * 4;
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
+  using T = bf16_t;
+  using L = Layout<T, D>;
+  constexpr int NT = KEEP_NT, NW = KEEP_NW, KB = L::KB, CB = L::CB;
+  extern __shared__ __align__(16) float smem[];
+
+  const int u = blockIdx.x + P.u0, uio = u - P.io_u0, tid = threadIdx.x;
+  const int wave = tid / WAVE, lane = tid % WAVE, head = lane & 15, kq = lane >> 4;
+  const int Cs = P.Cs, R = P.R, n_pad = P.n_pad;
+
+  float *stg = smem + (size_t)wave * 16 * KEEP_PS;            // [16][KEEP_PS] this wave's weights of one block
+  float *scw = smem + (size_t)NW * 16 * KEEP_PS + wave * 16;  // [16] this wave's rescale factors
+  float *mW = smem + (size_t)NW * 16 * KEEP_PS + NW * 16;     // [NW][16] maxima
+  float *zW = mW + NW * 16;                                   // [NW][16] sums
+  float *OW = zW + NW * 16;                                   // [NW][G][D] outputs
+  int *sh = (int *)(OW + (size_t)NW * G * D);                 // [16] 2: dest slot; 3: evicted; 4: new n_snap
+  float *shf = (float *)(sh + 16);                            // [16] 1..8: logits of the token against its own key
+
+  const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
+  const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
+  const T *qb = (const T *)P.q + (size_t)uio * G * D;
+  const T *knew = (const T *)P.k_new + (size_t)uio * D;
+  const T *vnew = (const T *)P.v_new + (size_t)uio * D;
+  int32_t *posu = P.pos + (size_t)u * n_pad;
+
+  const int32_t *meta = P.meta + (size_t)u * META;
+  const int n_snap = meta[0], p = meta[1], w = meta[3];
+  const int nwin = p < R ? p : R;
+  const bool win_full = p >= R;
+
+  // ---- the blocks of 32 slots that hold resident tokens: older tokens, then what the window adds beyond them
+  const int nb_old = (n_snap + 31) >> 5;
+  int wb0 = Cs >> 5;
+  const int wb1 = nwin > 0 ? (Cs + nwin + 31) >> 5 : wb0;
+  if (wb0 < nb_old) wb0 = nb_old;
+  const int total = nb_old + (wb1 > wb0 ? wb1 - wb0 : 0);
+  const bool zig = P.zig != 0;
+  auto block_of = [&](int i) {
+    const int ii = zig ? total - 1 - i : i;
+    return ii < nb_old ? ii : wb0 + (ii - nb_old);
+  };
+
+  uint4 ka[2][KB], vb[CB];
+  auto load_k = [&](int blk) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        const T *a = Kb + ((size_t)(2 * blk + t) * KB + kb) * 512 + lane * 8;
+        ka[t][kb] = blk < P.nt_k ? ldg16<true>(a) : ldg16<false>(a);
+      }
+  };
+  auto load_v = [&](int blk) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      const T *a = Vb + ((size_t)blk * CB + cb) * 512 + lane * 8;
+      vb[cb] = blk < P.nt_v ? ldg16<true>(a) : ldg16<false>(a);
+    }
+  };
+  if (wave < total) {
+    const int blk = block_of(wave);
+    load_k(blk);
+    load_v(blk);
+  }
+  // query fragments: B operand of the K product, 32 channels x 16 heads (heads >= G are zero)
+  bf16x8_t qfr[KB];
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    uint4 r = {0u, 0u, 0u, 0u};
+    if (head < G) r = *(const uint4 *)(qb + (size_t)head * D + kb * 32 + kq * 8);
+    qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
+  }
+
+  // ---- the wave's blocks: running maximum m and sum zp of the lane's head (m is the same in the four lanes of a
+  // head, zp is the lane's own part), output acc[cb][i] of head 4 kq + i and channel cb * 16 + (lane & 15)
+  float m = -INFINITY, zp = 0.f;
+  f32x4_t acc[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  for (int i = wave; i < total; i += NW) {
+    const int blk = block_of(i);
+    // logits of the block's 32 slots: lane holds slots t*16 + 4 kq + e (t = 0, 1; e = 0..3) of its head
+    float l[8];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t][kb]), qfr[kb], c, 0, 0, 0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = blk * 32 + t * 16 + 4 * kq + e;
+        l[4 * t + e] = slot_valid(j, n_snap, Cs, nwin) ? c[e] * P.scale_log2 : -INFINITY;
+      }
+    }
+    // the K registers are free: the next block's K tiles are asked for now
+    const bool more = i + NW < total;
+    const int nblk = more ? block_of(i + NW) : 0;
+    if (more) load_k(nblk);
+
+    float bmax = fmaxf(fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])), fmaxf(fmaxf(l[4], l[5]), fmaxf(l[6], l[7])));
+    bmax = max_over_rows(bmax);
+    const float m_new = fmaxf(m, bmax);
+    if (__ballot(m_new > m) != 0ull) {
+      // the maximum of some head moved: what has been summed so far is rescaled.  The output accumulators of
+      // this lane belong to the heads 4 kq .. 4 kq + 3: their factors come through LDS
+      const float sc = m == -INFINITY ? 0.f : exp2_native(m - m_new);
+      zp *= sc;
+      if (kq == 0) scw[head] = sc;
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+      const float4 s4 = *(const float4 *)(scw + 4 * kq);
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        acc[cb][0] *= s4.x; acc[cb][1] *= s4.y; acc[cb][2] *= s4.z; acc[cb][3] *= s4.w;
+      }
+      m = m_new;
+    }
+    float pw[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pw[e] = l[e] == -INFINITY ? 0.f : exp2_native(l[e] - m);
+      zp += pw[e];
+    }
+    // weights into the order the V product wants them: lane (head, kq) needs the slots 8 kq .. 8 kq + 7
+    *(float4 *)(stg + head * KEEP_PS + 4 * kq) = make_float4(pw[0], pw[1], pw[2], pw[3]);
+    *(float4 *)(stg + head * KEEP_PS + 16 + 4 * kq) = make_float4(pw[4], pw[5], pw[6], pw[7]);
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    const float4 x = *(const float4 *)(stg + head * KEEP_PS + 8 * kq);
+    const float4 y = *(const float4 *)(stg + head * KEEP_PS + 8 * kq + 4);
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    const float pv[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+    bf16x8_t ahi, alo;  // bf16 hi + lo parts, so that the product keeps ~16 bits of the weight
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const __bf16 h = (__bf16)pv[e];
+      ahi[e] = h;
+      alo[e] = (__bf16)(pv[e] - (float)h);
+    }
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, vb[cb]);
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi, bv, acc[cb], 0, 0, 0);
+      acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo, bv, acc[cb], 0, 0, 0);
+    }
+    if (more) load_v(nblk);
+  }
+
+  // ---- the token's logits against its own key: wave 0, the key as slot 0 of one more tile (as in the fused kernel)
+  if (wave == 0) {
+    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      uint4 a = {0u, 0u, 0u, 0u};
+      if (head == 0) a = *(const uint4 *)(knew + kb * 32 + kq * 8);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), qfr[kb], c, 0, 0, 0);
+    }
+    if (lane < G) shf[1 + lane] = c[0] * P.scale_log2;  // lanes 0..15 (kq = 0): slot 0, head = lane
+  }
+  // ---- the wave's results
+  const float zs = sum_over_rows(zp);
+  if (kq == 0) { mW[wave * 16 + head] = m; zW[wave * 16 + head] = zs; }
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int g = 4 * kq + e;
+      if (g < G) OW[(size_t)(wave * G + g) * D + cb * 16 + head] = acc[cb][e];
+    }
+  if (tid == 0) {
+    // every token is kept: the one leaving the window joins the older tokens (the host has made sure there is room)
+    sh[2] = win_full ? n_snap : -1;
+    sh[3] = -1;
+    sh[4] = n_snap + (win_full ? 1 : 0);
+    sh[5] = 0;
+  }
+  __syncthreads();
+
+  // ---- merge of the waves and the token itself (Eq.1), output
+  for (int idx = tid; idx < G * D; idx += NT) {
+    const int g = idx / D, ch = idx % D;
+    const float ls = shf[1 + g];
+    float M = ls;
+#pragma unroll
+    for (int x = 0; x < NW; ++x) M = fmaxf(M, mW[x * 16 + g]);
+    const float es = exp2_native(ls - M);
+    float Z = es;
+    float o = es * __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+#pragma unroll
+    for (int x = 0; x < NW; ++x) {
+      const float mx = mW[x * 16 + g];
+      const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);
+      Z = fmaf(f, zW[x * 16 + g], Z);
+      o = fmaf(f, OW[(size_t)(x * G + g) * D + ch], o);
+    }
+    P.out[((size_t)uio * G + g) * D + ch] = o / Z;
+  }
+  // every wave has read the window slot's K and V (it still holds the token that leaves the window) before the
+  // tail moves that token and writes the new one there: the barrier above.  The tail: shared with the other kernels
+  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, P.CsP, R, n_pad, P.cps, n_snap, p, w, false, 0, 1,
+                 sh, shf, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, posu, knew, vnew};
+  compact_and_commit<T, D, false>(tc);
+}
+
+}  // namespace mkv

@@ -264,6 +264,7 @@ struct morphkv_handle {
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
   int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
+  int keep_kernel;    // MORPHKV_KEEP_KERNEL: 0 choose, 1 the split kernel, 2 the online-softmax kernel (layers that keep all)
   int rb_waves;       // waves of a workgroup that rebuild aggregates (see decode.h); MORPHKV_REBUILD_WAVES overrides
   bool keep_all;      // this handle's layers keep every token (Appendix A.6)
   // A configuration whose first layers keep every token is two handles: this one for the layers that select, and
@@ -387,6 +388,12 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   if (pl.S > 1 || h->keep_all) {
     // a cache beyond the fused kernel's LDS, a layer that keeps every token, or on request: the split kernel
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
+    // ... except that launches with enough units to fill the device run a layer that keeps every token in the
+    // kernel made for it (online softmax, one workgroup per unit; measured: even with the split kernel at 96-128
+    // units, 1.3-1.7x faster from 192 on, 1.2-2x slower at 32-64 units with long caches, where only the split
+    // kernel reaches every compute unit)
+    if (h->keep_all && h->L.sp_force <= 0 && (h->keep_kernel == 2 || (h->keep_kernel == 0 && n_units >= 160)))
+      return launch_decode_keep(D, G, P, L);
     DecodeParams PS = P;
     PS.sp_bps = pl.bps;
     L.threads = SPLIT_NT;
@@ -576,6 +583,8 @@ static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool 
     const int kgroups = (h->L.n_pad / 16 + 1) / 2;
     h->rb_waves = kgroups >= 64 ? (cfg->R <= 128 ? 16 : 8) : kgroups >= 32 ? 4 : 2;
   }
+  h->keep_kernel = 0;
+  if (const char *e = std::getenv("MORPHKV_KEEP_KERNEL")) h->keep_kernel = !std::strcmp(e, "split") ? 1 : !std::strcmp(e, "stream") ? 2 : 0;
   if (const char *e = std::getenv("MORPHKV_REBUILD_WAVES")) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 16) h->rb_waves = v;

@@ -265,13 +265,17 @@ KEEP = [
 ]
 
 
+@pytest.mark.parametrize("kernel", ["split", "stream"])
 @pytest.mark.parametrize("entry", ["window", "attend", "per_layer"])
 @pytest.mark.parametrize("case", KEEP, ids=[c[0] for c in KEEP])
-def test_keep_all_layers(case, entry, oracle_lib):
+def test_keep_all_layers(case, entry, kernel, oracle_lib, monkeypatch):
     """One handle, the first layers without MorphKV (every token kept, attention only), the others selecting as
     configured: outputs of every layer, retained sets, evictions against the layered oracle, every step; through the
-    window entry, the entry fused with the prompt's attention pass, and layer-by-layer decode calls."""
+    window entry, the entry fused with the prompt's attention pass, and layer-by-layer decode calls; the layers that
+    keep everything in each of their two kernels (several workgroups a unit with a merge / one workgroup a unit with an
+    online softmax)."""
     name, kw = case
+    monkeypatch.setenv("MORPHKV_KEEP_KERNEL", kernel)
     wl = inputs.small_workload(15000 + KEEP.index(case), **kw)
     ls = _lockstep(wl, DEV, use_attend=entry == "attend", per_layer=entry == "per_layer",
                    capture_scores=wl.evict_every == 1 and wl.n_keep_all_layers < wl.n_layers).prefill()
@@ -294,10 +298,12 @@ def test_keep_all_layers(case, entry, oracle_lib):
         assert e.value.code == binding.ESTATE
 
 
-def test_keep_all_layers_over_a_16k_token_run(oracle_lib):
+@pytest.mark.parametrize("kernel", ["split", "stream"])
+def test_keep_all_layers_over_a_16k_token_run(kernel, oracle_lib, monkeypatch):
     """L = 4 with layers 0-1 keeping every token of a 15000-token prompt and 1100 generated tokens (16.1 k slots, far
     beyond what one workgroup's LDS holds), layers 2-3 at C = 2048, R = 128: every step against the layered oracle."""
     from paper_2503_00979_amd import binding
+    monkeypatch.setenv("MORPHKV_KEEP_KERNEL", kernel)
     steps = 1100
     wl = inputs.small_workload(15100, L=4, B=1, M=8, Mkv=2, d=128, dtype="bf16", C=2048, R=128, fusion="sum",
                                prompt_lens=(15000,), steps=steps, max_new_tokens=steps, n_keep_all_layers=2)
@@ -317,9 +323,11 @@ def test_keep_all_layers_over_a_16k_token_run(oracle_lib):
     assert rep.evictions == steps * 2 * 2
 
 
-def test_keep_all_layer_of_40k_tokens(oracle_lib):
+@pytest.mark.parametrize("kernel", ["split", "stream"])
+def test_keep_all_layer_of_40k_tokens(kernel, oracle_lib, monkeypatch):
     """A layer that keeps every token of a 40000-token prompt (10 workgroups a unit) next to a selecting layer: such a
     layer rebuilds no aggregates, so its workgroups need no LDS for them and its length is bounded by the shares alone."""
+    monkeypatch.setenv("MORPHKV_KEEP_KERNEL", kernel)
     steps = 48
     wl = inputs.small_workload(40100, L=2, B=1, M=4, Mkv=1, d=128, dtype="bf16", C=512, R=128, fusion="max",
                                prompt_lens=(40000,), steps=steps, max_new_tokens=steps, n_keep_all_layers=1)
