@@ -5,7 +5,7 @@
 // moves), a block of 32 slots goes K tiles -> logits -> weights -> V tile -> output without ever being written
 // down, and the cache's length is bounded by nothing but the memory the caller gave.
 //
-// One workgroup of KEEP_NT threads per unit; a wave takes the blocks wave, wave + NW, ... of the unit's resident
+// One workgroup of 256 or 512 threads per unit; a wave takes the blocks wave, wave + NW, ... of the unit's resident
 // slots (older tokens [0, n_snap), window [Cs, Cs + nwin)) with its own (maximum, sum, output); the waves'
 // results are merged through LDS at the end (Eq.1: softmax over all resident tokens and the token itself).
 // bf16 caches in MFMA tile order (Layout<bf16_t, D>), like the fused kernel.
@@ -14,20 +14,22 @@
 
 namespace mkv {
 
-constexpr int KEEP_NT = 512, KEEP_NW = KEEP_NT / WAVE;
+constexpr int KEEP_NT = 512;  // threads of a workgroup (256 works too and was measured no faster)
 constexpr int KEEP_PS = 36;  // floats per head row of a wave's weight staging tile (32 slots + 4: rows start 4 banks apart)
 
-// dynamic LDS of decode_keep_kernel
-inline size_t decode_keep_lds_bytes(int G, int D) {
-  return ((size_t)KEEP_NW * 16 * KEEP_PS /*weights of a block per wave*/ + (size_t)KEEP_NW * 16 /*rescale factors*/ +
-          2 * (size_t)KEEP_NW * 16 /*maxima, sums*/ + (size_t)KEEP_NW * G * D /*outputs*/ + 16 + 16) * 4;
+// dynamic LDS of decode_keep_kernel launched with `threads` threads a workgroup
+inline size_t decode_keep_lds_bytes(int G, int D, int threads) {
+  const size_t NW = (size_t)threads / WAVE;
+  return (NW * 16 * KEEP_PS /*weights of a block per wave*/ + NW * 16 /*rescale factors*/ + 2 * NW * 16 /*maxima, sums*/ +
+          NW * G * D /*outputs*/ + 16 + 16) * 4;
 }
 
 template <int D, int G>
 __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   using T = bf16_t;
   using L = Layout<T, D>;
-  constexpr int NT = KEEP_NT, NW = KEEP_NW, KB = L::KB, CB = L::CB;
+  constexpr int KB = L::KB, CB = L::CB;
+  const int NT = blockDim.x, NW = NT / WAVE;
   extern __shared__ __align__(16) float smem[];
 
   const int u = blockIdx.x + P.u0, uio = u - P.io_u0, tid = threadIdx.x;
@@ -212,12 +214,10 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
     const int g = idx / D, ch = idx % D;
     const float ls = shf[1 + g];
     float M = ls;
-#pragma unroll
     for (int x = 0; x < NW; ++x) M = fmaxf(M, mW[x * 16 + g]);
     const float es = exp2_native(ls - M);
     float Z = es;
     float o = es * __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
-#pragma unroll
     for (int x = 0; x < NW; ++x) {
       const float mx = mW[x * 16 + g];
       const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);

@@ -7,7 +7,7 @@ namespace mkv {
 namespace {
 template <int D, int G>
 int launch(const DecodeParams &P, const DecodeLaunch &L) {
-  hipLaunchKernelGGL((decode_keep_kernel<D, G>), dim3(L.n_units), dim3(KEEP_NT), decode_keep_lds_bytes(G, D), L.stream, P);
+  hipLaunchKernelGGL((decode_keep_kernel<D, G>), dim3(L.n_units), dim3(L.threads), decode_keep_lds_bytes(G, D, L.threads), L.stream, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }

@@ -18,6 +18,7 @@
 #include "host.h"
 #include "decode.h"
 #include "decode_split.h"
+#include "decode_keep.h"
 #include "prefill.h"
 #include "prompt_attn.h"
 #include "misc_kernels.h"
@@ -392,8 +393,12 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
     // kernel made for it (online softmax, one workgroup per unit; measured: even with the split kernel at 96-128
     // units, 1.3-1.7x faster from 192 on, 1.2-2x slower at 32-64 units with long caches, where only the split
     // kernel reaches every compute unit)
-    if (h->keep_all && h->L.sp_force <= 0 && (h->keep_kernel == 2 || (h->keep_kernel == 0 && n_units >= 160)))
+    if (h->keep_all && h->L.sp_force <= 0 && (h->keep_kernel == 2 || (h->keep_kernel == 0 && n_units >= 160))) {
+      // (workgroups of 256 threads, three to a compute unit, were measured even with one of 512 on launches of many
+      // units: the override is for tests)
+      L.threads = h->force_threads == 256 || h->force_threads == 512 ? h->force_threads : KEEP_NT;
       return launch_decode_keep(D, G, P, L);
+    }
     DecodeParams PS = P;
     PS.sp_bps = pl.bps;
     L.threads = SPLIT_NT;
