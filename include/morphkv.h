@@ -86,8 +86,9 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
  * each; unset or 0 = only units that one workgroup cannot hold are split),
  * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel; raised where the
  * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least),
- * MORPHKV_KEEP_KERNEL ("split" / "stream": which of the two kernels runs the layers that keep every token; unset =
- * by the number of units in the launch), MORPHKV_REBUILD_WAVES (1..16: how many waves of a unit's workgroup share the per-step rebuild of score aggregates;
+ * MORPHKV_KEEP_KERNEL ("split": layers that keep every token run in the split kernel instead of the kernel made for
+ * them), MORPHKV_KEEP_SHARES (1..32: workgroups per unit of that kernel; unset = by the number of units in the
+ * launch), MORPHKV_REBUILD_WAVES (1..16: how many waves of a unit's workgroup share the per-step rebuild of score aggregates;
  * rounding of sums may differ in the last bit between values, the retained sets stay within the tie tolerance) and
  * MORPHKV_CACHE_BUDGET_MB (bf16 caches; default 208: how much of the handle's K/V is read with ordinary loads
  * and so stays in the device's 256 MB memory-side cache from step to step; the rest is streamed with

@@ -5,12 +5,16 @@
 // moves), a block of 32 slots goes K tiles -> logits -> weights -> V tile -> output without ever being written
 // down, and the cache's length is bounded by nothing but the memory the caller gave.
 //
-// One workgroup of 256 or 512 threads per unit; a wave takes the blocks wave, wave + NW, ... of the unit's resident
-// slots (older tokens [0, n_snap), window [Cs, Cs + nwin)) with its own (maximum, sum, output); the waves'
-// results are merged through LDS at the end (Eq.1: softmax over all resident tokens and the token itself).
+// S workgroups of 256 or 512 threads per unit (grid S x units); the waves of a unit's workgroups take the blocks of
+// its resident slots (older tokens [0, n_snap), window [Cs, Cs + nwin)) in turn, each with its own (maximum, sum,
+// output); a workgroup's waves are merged through LDS (Eq.1: softmax over all resident tokens and the token
+// itself).  With S > 1 -- launches of few units, so that every compute unit gets a share -- each workgroup leaves
+// its merged (maximum, sum, output) in the split kernel's workspace with agent-scope stores, counts in, and the
+// last one to arrive merges the S records and finishes the step (the protocol of decode_split.h).
 // bf16 caches in MFMA tile order (Layout<bf16_t, D>), like the fused kernel.
 #pragma once
 #include "decode.h"
+#include "decode_split.h"  // the workspace accesses at agent scope, SPLIT_MAX, the layout of a workgroup's record
 
 namespace mkv {
 
@@ -21,7 +25,7 @@ constexpr int KEEP_PS = 36;  // floats per head row of a wave's weight staging t
 inline size_t decode_keep_lds_bytes(int G, int D, int threads) {
   const size_t NW = (size_t)threads / WAVE;
   return (NW * 16 * KEEP_PS /*weights of a block per wave*/ + NW * 16 /*rescale factors*/ + 2 * NW * 16 /*maxima, sums*/ +
-          NW * G * D /*outputs*/ + 16 + 16) * 4;
+          NW * G * D /*outputs*/ + 16 + 16 + 2 * SPLIT_MAX * 8 /*the workgroups' maxima and sums*/) * 4;
 }
 
 template <int D, int G>
@@ -32,7 +36,7 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   const int NT = blockDim.x, NW = NT / WAVE;
   extern __shared__ __align__(16) float smem[];
 
-  const int u = blockIdx.x + P.u0, uio = u - P.io_u0, tid = threadIdx.x;
+  const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y + P.u0, uio = u - P.io_u0, tid = threadIdx.x;
   const int wave = tid / WAVE, lane = tid % WAVE, head = lane & 15, kq = lane >> 4;
   const int Cs = P.Cs, R = P.R, n_pad = P.n_pad;
 
@@ -43,6 +47,8 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   float *OW = zW + NW * 16;                                   // [NW][G][D] outputs
   int *sh = (int *)(OW + (size_t)NW * G * D);                 // [16] 2: dest slot; 3: evicted; 4: new n_snap
   float *shf = (float *)(sh + 16);                            // [16] 1..8: logits of the token against its own key
+  float *msl = shf + 16;                                      // [SPLIT_MAX][8] the workgroups' maxima (S > 1)
+  float *zsl = msl + SPLIT_MAX * 8;                           // [SPLIT_MAX][8] ... and sums
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -85,8 +91,10 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
       vb[cb] = blk < P.nt_v ? ldg16<true>(a) : ldg16<false>(a);
     }
   };
-  if (wave < total) {
-    const int blk = block_of(wave);
+  // block i of the unit goes to workgroup (i / NW) mod S, wave i mod NW
+  const int i0 = s * NW + wave, istep = S * NW;
+  if (i0 < total) {
+    const int blk = block_of(i0);
     load_k(blk);
     load_v(blk);
   }
@@ -106,7 +114,7 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  for (int i = wave; i < total; i += NW) {
+  for (int i = i0; i < total; i += istep) {
     const int blk = block_of(i);
     // logits of the block's 32 slots: lane holds slots t*16 + 4 kq + e (t = 0, 1; e = 0..3) of its head
     float l[8];
@@ -123,8 +131,8 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
       }
     }
     // the K registers are free: the next block's K tiles are asked for now
-    const bool more = i + NW < total;
-    const int nblk = more ? block_of(i + NW) : 0;
+    const bool more = i + istep < total;
+    const int nblk = more ? block_of(i + istep) : 0;
     if (more) load_k(nblk);
 
     float bmax = fmaxf(fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])), fmaxf(fmaxf(l[4], l[5]), fmaxf(l[6], l[7])));
@@ -209,22 +217,83 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   }
   __syncthreads();
 
-  // ---- merge of the waves and the token itself (Eq.1), output
-  for (int idx = tid; idx < G * D; idx += NT) {
-    const int g = idx / D, ch = idx % D;
-    const float ls = shf[1 + g];
-    float M = ls;
-    for (int x = 0; x < NW; ++x) M = fmaxf(M, mW[x * 16 + g]);
-    const float es = exp2_native(ls - M);
-    float Z = es;
-    float o = es * __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
-    for (int x = 0; x < NW; ++x) {
-      const float mx = mW[x * 16 + g];
-      const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);
-      Z = fmaf(f, zW[x * 16 + g], Z);
-      o = fmaf(f, OW[(size_t)(x * G + g) * D + ch], o);
+  constexpr int PART = 2 * G + G * D;
+  if (S == 1) {
+    // ---- merge of the waves and the token itself (Eq.1), output
+    for (int idx = tid; idx < G * D; idx += NT) {
+      const int g = idx / D, ch = idx % D;
+      const float ls = shf[1 + g];
+      float M = ls;
+      for (int x = 0; x < NW; ++x) M = fmaxf(M, mW[x * 16 + g]);
+      const float es = exp2_native(ls - M);
+      float Z = es;
+      float o = es * __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+      for (int x = 0; x < NW; ++x) {
+        const float mx = mW[x * 16 + g];
+        const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);
+        Z = fmaf(f, zW[x * 16 + g], Z);
+        o = fmaf(f, OW[(size_t)(x * G + g) * D + ch], o);
+      }
+      P.out[((size_t)uio * G + g) * D + ch] = o / Z;
     }
-    P.out[((size_t)uio * G + g) * D + ch] = o / Z;
+  } else {
+    // ---- this workgroup's record: its waves merged at their common maximum (no token of its own yet)
+    const __amdgpu_buffer_rsrc_t part = ws_rsrc(P.sp_part + ((size_t)u * P.sp_smax) * PART, (uint32_t)P.sp_smax * PART * 4u);
+    for (int idx = tid; idx < G * D; idx += NT) {
+      const int g = idx / D, ch = idx % D;
+      float M = -INFINITY;
+      for (int x = 0; x < NW; ++x) M = fmaxf(M, mW[x * 16 + g]);
+      float Z = 0.f, o = 0.f;
+      for (int x = 0; x < NW; ++x) {
+        const float mx = mW[x * 16 + g];
+        const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);
+        Z = fmaf(f, zW[x * 16 + g], Z);
+        o = fmaf(f, OW[(size_t)(x * G + g) * D + ch], o);
+      }
+      ws_store1(part, (uint32_t)(s * PART + 2 * G + idx), o);
+      if (ch == 0) {
+        ws_store1(part, (uint32_t)(s * PART + g), M);
+        ws_store1(part, (uint32_t)(s * PART + G + g), Z);
+      }
+    }
+    // count in: every thread waits until its stores have been acknowledged, then one thread bumps the unit's
+    // counter; the last workgroup of the unit carries on
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) sh[6] = atomicAdd(&P.sp_cnt[u], 1);
+    __syncthreads();
+    if (sh[6] != S - 1) return;
+    for (int i = tid; i < S * G; i += NT) {
+      const int ss = i / G, g = i - ss * G;
+      msl[ss * 8 + g] = ws_load1(part, (uint32_t)(ss * PART + g));
+      zsl[ss * 8 + g] = ws_load1(part, (uint32_t)(ss * PART + G + g));
+    }
+    if (tid == 0) P.sp_cnt[u] = 0;  // for the unit's next step
+    __syncthreads();
+    // ---- merge of the workgroups and the token itself (Eq.1), output; the records are asked for eight at a time
+    for (int idx = tid; idx < G * D; idx += NT) {
+      const int g = idx / D, ch = idx % D;
+      const float ls = shf[1 + g];
+      float M = ls;
+      for (int ss = 0; ss < S; ++ss) M = fmaxf(M, msl[ss * 8 + g]);
+      const float es = exp2_native(ls - M);
+      float Z = es;
+      float o = es * __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+      for (int s0 = 0; s0 < S; s0 += 8) {
+        float ob[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ob[k] = s0 + k < S ? ws_load1(part, (uint32_t)((s0 + k) * PART + 2 * G + idx)) : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (s0 + k < S) {
+            const float mx = msl[(s0 + k) * 8 + g];
+            const float f = mx == -INFINITY ? 0.f : exp2_native(mx - M);
+            Z = fmaf(f, zsl[(s0 + k) * 8 + g], Z);
+            o = fmaf(f, ob[k], o);
+          }
+      }
+      P.out[((size_t)uio * G + g) * D + ch] = o / Z;
+    }
   }
   // every wave has read the window slot's K and V (it still holds the token that leaves the window) before the
   // tail moves that token and writes the new one there: the barrier above.  The tail: shared with the other kernels

@@ -1,4 +1,4 @@
-// Decode step of layers that keep every token (Appendix A.6), one workgroup per unit with an online softmax
+// Decode step of layers that keep every token (Appendix A.6), S workgroups per unit with an online softmax
 // (bf16 caches): head_dim 64 / 128, group sizes 1..8.
 #include "host.h"
 #include "decode_keep.h"
@@ -6,15 +6,15 @@
 namespace mkv {
 namespace {
 template <int D, int G>
-int launch(const DecodeParams &P, const DecodeLaunch &L) {
-  hipLaunchKernelGGL((decode_keep_kernel<D, G>), dim3(L.n_units), dim3(L.threads), decode_keep_lds_bytes(G, D, L.threads), L.stream, P);
+int launch(const DecodeParams &P, const DecodeLaunch &L, int S) {
+  hipLaunchKernelGGL((decode_keep_kernel<D, G>), dim3(S, L.n_units), dim3(L.threads), decode_keep_lds_bytes(G, D, L.threads), L.stream, P);
   HIP_TRY(hipGetLastError());
   return MORPHKV_OK;
 }
 }  // namespace
 
-int launch_decode_keep(int D, int G, const DecodeParams &P, const DecodeLaunch &L) {
-  if (D == 128) { MKV_SWITCH_G(G, (launch<128, G_>(P, L))) }
-  MKV_SWITCH_G(G, (launch<64, G_>(P, L)))
+int launch_decode_keep(int D, int G, const DecodeParams &P, const DecodeLaunch &L, int S) {
+  if (D == 128) { MKV_SWITCH_G(G, (launch<128, G_>(P, L, S))) }
+  MKV_SWITCH_G(G, (launch<64, G_>(P, L, S)))
 }
 }  // namespace mkv

@@ -53,9 +53,9 @@ int launch_decode_f32_coarse(int D, int G, const DecodeParams &P, const DecodeLa
 // the same step with S workgroups per unit (decode_split.hip); L.threads is ignored (fixed by the kernel)
 int launch_decode_split(int D, int G, const DecodeParams &P, const DecodeLaunch &L, int S);
 int decode_lds_limit_split(int D, int G, size_t lds);
-// the step of layers that keep every token, one workgroup of L.threads (256 or 512) per unit, online softmax
+// the step of layers that keep every token, S workgroups of L.threads (256 or 512) per unit, online softmax
 // (decode_keep.hip); L.lds is ignored (follows from the threads)
-int launch_decode_keep(int D, int G, const DecodeParams &P, const DecodeLaunch &L);
+int launch_decode_keep(int D, int G, const DecodeParams &P, const DecodeLaunch &L, int S);
 // raise the kernels' dynamic-LDS limit on the current device
 int decode_lds_limit_bf16_product(int D, int G, size_t lds);
 int decode_lds_limit_bf16_coarse(int D, int G, size_t lds);

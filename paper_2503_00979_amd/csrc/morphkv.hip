@@ -176,6 +176,26 @@ SplitPlan plan_split(int n_pad, int G, int D, int R, int cps, int CsP, int T, bo
   return pl;
 }
 
+// Workgroups per unit of decode_keep_kernel (layers that keep every token) in a launch of n_units units: one from 160
+// units on; below that as many as give every compute unit a share, a number that goes evenly over the compute units
+// where one is in reach, and shares of 16 blocks of 32 slots at least when the layer is full.
+int keep_shares(int n_units, int n_pad) {
+  if (const char *e = std::getenv("MORPHKV_KEEP_SHARES")) {  // (tests, tuning)
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= SPLIT_MAX) return v;
+  }
+  if (n_units >= 160) return 1;
+  int S = (N_CU_REF + n_units - 1) / n_units;
+  int g = n_units, r = N_CU_REF;
+  while (r) { const int t = g % r; g = r; r = t; }
+  const int m = N_CU_REF / g, S2 = (S + m - 1) / m * m;
+  if (S2 <= 2 * S) S = S2;
+  const int cap = n_pad / 32 / 16;
+  if (S > cap) S = cap;
+  if (S > SPLIT_MAX) S = SPLIT_MAX;
+  return S < 1 ? 1 : S;
+}
+
 BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
   BufLayout L{};
   L.keep_all = keep_all;
@@ -227,6 +247,7 @@ BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
       const SplitPlan pl = plan_split(L.n_pad, L.G, c->head_dim, c->R, L.cps, L.CsP, c->evict_every > 0 ? c->evict_every : 1,
                                       true, units, L.sp_force, fits);
       if (pl.S > L.sp_smax) L.sp_smax = pl.S;
+      if (keep_all && keep_shares(units, L.n_pad) > L.sp_smax) L.sp_smax = keep_shares(units, L.n_pad);
     }
   }
   const bool sp = L.sp_smax > 1 || keep_all;  // (a keep-all layer runs in the split kernel even with one workgroup a unit)
@@ -265,7 +286,7 @@ struct morphkv_handle {
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
   int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
-  int keep_kernel;    // MORPHKV_KEEP_KERNEL: 0 choose, 1 the split kernel, 2 the online-softmax kernel (layers that keep all)
+  int keep_kernel;    // MORPHKV_KEEP_KERNEL: 1 = the split kernel for layers that keep all, else the online-softmax kernel
   int rb_waves;       // waves of a workgroup that rebuild aggregates (see decode.h); MORPHKV_REBUILD_WAVES overrides
   bool keep_all;      // this handle's layers keep every token (Appendix A.6)
   // A configuration whose first layers keep every token is two handles: this one for the layers that select, and
@@ -389,15 +410,15 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   if (pl.S > 1 || h->keep_all) {
     // a cache beyond the fused kernel's LDS, a layer that keeps every token, or on request: the split kernel
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
-    // ... except that launches with enough units to fill the device run a layer that keeps every token in the
-    // kernel made for it (online softmax, one workgroup per unit; measured: even with the split kernel at 96-128
-    // units, 1.3-1.7x faster from 192 on, 1.2-2x slower at 32-64 units with long caches, where only the split
-    // kernel reaches every compute unit)
-    if (h->keep_all && h->L.sp_force <= 0 && (h->keep_kernel == 2 || (h->keep_kernel == 0 && n_units >= 160))) {
+    // ... except that a layer that keeps every token runs in the kernel made for it (online softmax; one workgroup
+    // per unit from 160 units on, several with a merge below that)
+    if (h->keep_all && h->L.sp_force <= 0 && h->keep_kernel != 1) {
       // (workgroups of 256 threads, three to a compute unit, were measured even with one of 512 on launches of many
       // units: the override is for tests)
       L.threads = h->force_threads == 256 || h->force_threads == 512 ? h->force_threads : KEEP_NT;
-      return launch_decode_keep(D, G, P, L);
+      int S = keep_shares(n_units, P.n_pad);
+      if (S > h->L.sp_smax) S = h->L.sp_smax;
+      return launch_decode_keep(D, G, P, L, S);
     }
     DecodeParams PS = P;
     PS.sp_bps = pl.bps;

@@ -265,7 +265,7 @@ KEEP = [
 ]
 
 
-@pytest.mark.parametrize("kernel", ["split", "stream"])
+@pytest.mark.parametrize("kernel", ["split", "stream", "stream3"])
 @pytest.mark.parametrize("entry", ["window", "attend", "per_layer"])
 @pytest.mark.parametrize("case", KEEP, ids=[c[0] for c in KEEP])
 def test_keep_all_layers(case, entry, kernel, oracle_lib, monkeypatch):
@@ -273,9 +273,11 @@ def test_keep_all_layers(case, entry, kernel, oracle_lib, monkeypatch):
     configured: outputs of every layer, retained sets, evictions against the layered oracle, every step; through the
     window entry, the entry fused with the prompt's attention pass, and layer-by-layer decode calls; the layers that
     keep everything in each of their two kernels (several workgroups a unit with a merge / one workgroup a unit with an
-    online softmax)."""
+    online softmax, alone or three a unit with a merge)."""
     name, kw = case
-    monkeypatch.setenv("MORPHKV_KEEP_KERNEL", kernel)
+    monkeypatch.setenv("MORPHKV_KEEP_KERNEL", kernel[:6])
+    if kernel == "stream3":
+        monkeypatch.setenv("MORPHKV_KEEP_SHARES", "3")   # three workgroups a unit and a merge, also on these small caches
     wl = inputs.small_workload(15000 + KEEP.index(case), **kw)
     ls = _lockstep(wl, DEV, use_attend=entry == "attend", per_layer=entry == "per_layer",
                    capture_scores=wl.evict_every == 1 and wl.n_keep_all_layers < wl.n_layers).prefill()
