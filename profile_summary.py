@@ -34,7 +34,7 @@ def pmc(db, nlast):
     c = sqlite3.connect(db)
     rows = c.execute(
         "select name, counter_name, dispatch_id, sum(counter_value), max(duration) from pmc_events "
-        "where name like '%decode_fused%' or name like '%decode_split%' or name like '%calib_copy%' "
+        "where name like '%decode_fused%' or name like '%decode_split%' or name like '%decode_keep%' or name like '%calib_copy%' "
         "group by name, counter_name, dispatch_id order by dispatch_id")
     d = defaultdict(list)
     for name, cn, did, val, dur in rows:
