@@ -55,6 +55,8 @@ struct DecodeParams {
                            // fused or selected; the token leaving the window is appended to the older tokens
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
+  int32_t keep_cached_blocks;  // decode_keep_kernel: a unit's newest blocks of 32 slots that are read with ordinary loads
+                           // (meant to stay in the memory-side cache); older blocks stream with the non-temporal hint
   int32_t rb_gw, rb_nrw;   // fused kernel: columns per group of the rebuild (turn_group_width) and the number of waves
                            // that rebuild, worked out by the host for the launch's workgroup size
   int32_t u0;              // first unit of the launch (a launch may cover one layer's units only)

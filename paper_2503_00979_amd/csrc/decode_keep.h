@@ -73,6 +73,12 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
     const int ii = zig ? total - 1 - i : i;
     return ii < nb_old ? ii : wb0 + (ii - nb_old);
   };
+  // the newest blocks (as many as the handle's share of the memory-side cache holds per unit) are read with ordinary
+  // loads and stay there from step to step; the older ones stream past it
+  const int nwb = wb1 > wb0 ? wb1 - wb0 : 0;  // blocks of the window (beyond the older tokens' blocks)
+  const int thr_win = wb1 - P.keep_cached_blocks;
+  const int thr_old = nb_old - (P.keep_cached_blocks > nwb ? P.keep_cached_blocks - nwb : 0);
+  auto streams = [&](int blk) { return blk >= wb0 ? blk < thr_win : blk < thr_old; };
 
   uint4 ka[2][KB], vb[CB];
   auto load_k = [&](int blk) {
@@ -81,14 +87,14 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
         const T *a = Kb + ((size_t)(2 * blk + t) * KB + kb) * 512 + lane * 8;
-        ka[t][kb] = blk < P.nt_k ? ldg16<true>(a) : ldg16<false>(a);
+        ka[t][kb] = streams(blk) ? ldg16<true>(a) : ldg16<false>(a);
       }
   };
   auto load_v = [&](int blk) {
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       const T *a = Vb + ((size_t)blk * CB + cb) * 512 + lane * 8;
-      vb[cb] = blk < P.nt_v ? ldg16<true>(a) : ldg16<false>(a);
+      vb[cb] = streams(blk) ? ldg16<true>(a) : ldg16<false>(a);
     }
   };
   // block i of the unit goes to workgroup (i / NW) mod S, wave i mod NW

@@ -286,6 +286,7 @@ struct morphkv_handle {
   int force_threads;  // MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024): tuning override, 0 = choose
   size_t min_lds;     // MORPHKV_DECODE_MIN_LDS (bytes): tuning override, asks for at least this much LDS per group
   int nt_k, nt_v;     // K tile groups / V tiles per unit that stream past the caches (see decode.h)
+  int keep_cached_blocks;  // decode_keep_kernel: newest blocks of a unit that are read with ordinary loads
   int keep_kernel;    // MORPHKV_KEEP_KERNEL: 1 = the split kernel for layers that keep all, else the online-softmax kernel
   int rb_waves;       // waves of a workgroup that rebuild aggregates (see decode.h); MORPHKV_REBUILD_WAVES overrides
   bool keep_all;      // this handle's layers keep every token (Appendix A.6)
@@ -315,6 +316,7 @@ DecodeParams decode_params(const morphkv_handle *h) {
   P.zig = (int32_t)(h->steps & 1u);
   P.nt_k = h->nt_k;
   P.nt_v = h->nt_v;
+  P.keep_cached_blocks = h->keep_cached_blocks;
   P.sp_w = (float *)(h->ring + L.offSpW);
   P.sp_part = (float *)(h->ring + L.offSpPart);
   P.sp_cnt = (int32_t *)(h->ring + L.offSpCnt);
@@ -556,8 +558,9 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
 }
 
 // one handle over layers that all behave alike: cfg is the configuration of those layers alone
+// budget_share: this segment's part of the memory-side cache budget (the segments of a handle share it by layers)
 static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool keep_all, void *cache, void *scores_ring,
-                          void *scratch) {
+                          void *scratch, double budget_share) {
   *out = nullptr;
   morphkv_handle *h = new (std::nothrow) morphkv_handle();
   if (!h) return fail(MORPHKV_EINVAL, "out of host memory");
@@ -594,6 +597,10 @@ static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool 
   if (cfg->dtype == MORPHKV_DTYPE_BF16) {
     double budget_mb = 208.0;
     if (const char *e = std::getenv("MORPHKV_CACHE_BUDGET_MB")) budget_mb = std::atof(e);
+    budget_mb *= budget_share;
+    // (a layer that keeps every token is mostly headroom: its kernel applies the budget to what is resident --
+    // the newest keep_cached_blocks blocks of 32 slots of every unit are read with ordinary loads)
+    h->keep_cached_blocks = (int)std::min(1.0e9, budget_mb * 1048576.0 / ((double)h->L.U * 32.0 * cfg->head_dim * 4.0));
     const double half = (double)h->L.U * h->L.n_pad * cfg->head_dim * 2.0;  // bytes of K (= bytes of V) of the handle
     const double stream = 2.0 * half - budget_mb * 1048576.0;              // bytes that have to stream
     const int kgroups = (h->L.n_pad / 16 + 1) / 2, vtiles = h->L.n_pad / 32;
@@ -683,7 +690,7 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
   if (k > 0) {
     // the layers that keep every token come first in both buffers; the prompt-time workspace is shared (the two
     // parts of a call run one after the other on the caller's stream)
-    if (const int rc = create_segment(&hk, &ck, true, cache, scores_ring, scratch)) return rc;
+    if (const int rc = create_segment(&hk, &ck, true, cache, scores_ring, scratch, (double)k / cfg->n_layers)) return rc;
     cache_k = hk->L.cache_bytes;
     ring_k = hk->L.ring_bytes;
     if (k == cfg->n_layers) {
@@ -692,7 +699,8 @@ int morphkv_create(morphkv_handle **out, const morphkv_config *cfg, void *cache,
       return MORPHKV_OK;
     }
   }
-  if (const int rc = create_segment(&hs, &cs, false, (char *)cache + cache_k, (char *)scores_ring + ring_k, scratch)) {
+  if (const int rc = create_segment(&hs, &cs, false, (char *)cache + cache_k, (char *)scores_ring + ring_k, scratch,
+                                    (double)(cfg->n_layers - k) / cfg->n_layers)) {
     delete hk;
     return rc;
   }
