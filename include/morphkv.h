@@ -80,7 +80,8 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
  * stay valid until morphkv_destroy.  Ownership stays with the caller.
  * MORPHKV_EINVAL if C + R is beyond what the decode kernels can hold (the reason is in morphkv_last_error): fp32
  * caches keep one weight per (query head, slot) in LDS (C + R up to about 9 k slots at 4 heads a group); bf16
- * caches beyond that run with several workgroups per unit, up to about 130 k slots at 4 heads a group.
+ * caches beyond that run with several workgroups per unit, up to about 130 k slots at 4 heads a group; layers that
+ * keep every token (n_keep_all_layers) have no such bound.
  * Environment variables, read by morphkv_sizes and here, override tuning choices and never change results:
  * MORPHKV_SPLIT_BPS (bf16: a positive value splits every unit over several workgroups of that many 32-slot blocks
  * each; unset or 0 = only units that one workgroup cannot hold are split),

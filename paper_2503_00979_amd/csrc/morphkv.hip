@@ -409,21 +409,22 @@ int dispatch_decode(const morphkv_handle *h, const DecodeParams &P, int n_units,
   L.coarse = P.T > 1;
   L.stream = st;
   // (the kernels' dynamic-LDS limits were raised when the handle was made, on the device current then)
+  // a layer that keeps every token runs in the kernel made for it (online softmax; one or two workgroups per unit
+  // from 160 units on, several with a merge below that)
+  if (h->keep_all && h->L.sp_force <= 0 && h->keep_kernel != 1) {
+    if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
+    // (workgroups of 256 threads, three to a compute unit, were measured even with one of 512 on launches of many
+    // units: the override is for tests)
+    L.threads = h->force_threads == 256 || h->force_threads == 512 ? h->force_threads : KEEP_NT;
+    int S = keep_shares(n_units, P.n_pad);
+    if (S > h->L.sp_smax) S = h->L.sp_smax;
+    return launch_decode_keep(D, G, P, L, S);
+  }
   const SplitPlan pl = handle_plan(h, n_units);
   if (pl.S == 0) return fail(MORPHKV_EINVAL, "C + R = %d is too large for the decode kernels' LDS", P.n);
   if (pl.S > 1 || h->keep_all) {
-    // a cache beyond the fused kernel's LDS, a layer that keeps every token, or on request: the split kernel
+    // a cache beyond the fused kernel's LDS, or on request: the split kernel
     if (L.clocks) return fail(MORPHKV_EINVAL, "phase clocks are built for the fused kernel only");
-    // ... except that a layer that keeps every token runs in the kernel made for it (online softmax; one workgroup
-    // per unit from 160 units on, several with a merge below that)
-    if (h->keep_all && h->L.sp_force <= 0 && h->keep_kernel != 1) {
-      // (workgroups of 256 threads, three to a compute unit, were measured even with one of 512 on launches of many
-      // units: the override is for tests)
-      L.threads = h->force_threads == 256 || h->force_threads == 512 ? h->force_threads : KEEP_NT;
-      int S = keep_shares(n_units, P.n_pad);
-      if (S > h->L.sp_smax) S = h->L.sp_smax;
-      return launch_decode_keep(D, G, P, L, S);
-    }
     DecodeParams PS = P;
     PS.sp_bps = pl.bps;
     L.threads = SPLIT_NT;
@@ -640,6 +641,7 @@ static int create_segment(morphkv_handle **out, const morphkv_config *cfg, bool 
   size_t lds_max = 0, lds_split = 0;
   for (int units : {h->L.U, upl}) {
     const SplitPlan pl = handle_plan(h, units);
+    if (pl.S == 0 && h->keep_all) continue;  // (beyond the split kernel's shares: decode_keep_kernel has no such bound)
     if (pl.S == 0) {
       const int n = h->L.n;
       delete h;

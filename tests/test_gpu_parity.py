@@ -341,6 +341,19 @@ def test_keep_all_layer_of_40k_tokens(kernel, oracle_lib, monkeypatch):
     assert int(n[1]) == 512
 
 
+def test_keep_all_layer_of_150k_tokens(oracle_lib):
+    """A layer that keeps every token of a 150000-token prompt: beyond what the split kernel's shares can hold (32 x
+    ~4 k slots), no matter to the kernel with the online softmax, which keeps nothing per slot on chip."""
+    steps = 12
+    wl = inputs.small_workload(150100, L=2, B=1, M=4, Mkv=1, d=128, dtype="bf16", C=256, R=64, fusion="sum",
+                               prompt_lens=(150000,), steps=steps, max_new_tokens=steps, n_keep_all_layers=1)
+    ls = _lockstep(wl, DEV, gen_device=DEV).prefill()
+    rep = ls.run(steps, check_every=4)
+    _report("keep_150k", rep)
+    pos, n = ls.gpu.export_positions()
+    assert int(n[0]) == 150000 + steps - 64 and int(n[1]) == 256
+
+
 @pytest.mark.parametrize("T", [1, 4])
 def test_per_layer_calls(T, oracle_lib):
     """One call per layer, as a model's attention layers make them, gives what the whole-model call gives."""
