@@ -131,6 +131,8 @@ def main():
                     help="override the workload's fusion; cumsum = the running-sum comparison policy (H2O's score)")
     ap.add_argument("--evict-every", type=int, default=1,
                     help="T of the coarse schedule (Appendix A.5): selection at every T-th step")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="override the workload's number of layers (c4 with 1 layer = the launch a per-layer call makes)")
     ap.add_argument("--keep-all-layers", type=int, default=0,
                     help="the first K layers keep every token (Appendix A.6: selective layer retention); their caches "
                          "grow during the run, the bytes are priced at their mean length over the timed region")
@@ -170,6 +172,9 @@ def main():
         import dataclasses
         wl = dataclasses.replace(wl, evict_every=args.evict_every, fusion=args.fusion or wl.fusion)
     K_steps, W = args.steps, args.warmup
+    if args.layers:
+        import dataclasses
+        wl = dataclasses.replace(wl, n_layers=args.layers)
     if args.keep_all_layers:
         import dataclasses
         assert wl.dtype == "bf16" and 0 < args.keep_all_layers <= wl.n_layers and args.no_cpu_baseline, \
