@@ -55,7 +55,7 @@ def read_traffic(name: str):
     return None, None
 
 
-def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8, dump=None):
+def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8, dump=None, groups=1):
     """Phase time stamps of the fused decode kernel (diagnostics build, bf16 head_dim 128): per unit, microseconds
     after the launch's first workgroup started; mean / p10 / p90 over units and sampled launches."""
     import numpy as np
@@ -70,6 +70,8 @@ def phase_clocks(g, run_steps, n_units, launches=5, steps_per_launch_sample=8, d
     a = np.stack(acc)[1:] * 0.01          # 100 MHz clock -> us
     if dump:
         np.save(dump, a)                  # [launch, unit, stamp] for a look at which units end late
+    if groups > 1:                        # one launch per layer: every layer's units against their own launch's start
+        a = a.reshape(a.shape[0] * groups, n_units // groups, a.shape[2])
     t0 = a[:, :, 0].min(1, keepdims=True)
     names = ["workgroup start", "end of the K pass", "end of softmax / record", "end of the V pass", "end of the step",
              "last wave at the first barrier", "first wave at the first barrier", "first barrier passed"]
@@ -332,13 +334,13 @@ def main():
         times.append((ev0.elapsed_time(ev1) / 1e3, wall))
     phases = None
     if args.phase_clocks:
-        assert not args.per_layer, "--phase-clocks: whole-model launches only"
         cursor = [W + max(1, args.repeats) * K_steps]
 
         def run_some(n):
             run(n, cursor[0])
             cursor[0] += n
-        phases = phase_clocks(g, run_some, wl.n_units, launches=args.phase_clocks_launches, dump=args.phase_clocks_dump)
+        phases = phase_clocks(g, run_some, wl.n_units, launches=args.phase_clocks_launches, dump=args.phase_clocks_dump,
+                              groups=nl if args.per_layer else 1)
         print(f"phase time stamps of the fused decode kernel, {wl.name}: us after the launch's first workgroup start "
               f"(mean / p10 / p90 over units and {args.phase_clocks_launches} launches)", file=sys.stderr)
         for k_, v_ in phases.items():
