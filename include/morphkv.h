@@ -67,7 +67,8 @@ typedef struct morphkv_config {
   int32_t n_keep_all_layers; /* Appendix A.6 (selective layer retention): MorphKV is off in the first
                              n_keep_all_layers layers, which keep every token of the prompt and of the response
                              (max_prompt_len + max_new_tokens slots; attention only: nothing is recorded, fused or
-                             selected there); the other layers run as configured above.  0..n_layers; bf16 only */
+                             selected there); the other layers run as configured above.  0..n_layers; bf16 only;
+                             max_prompt_len + max_new_tokens + R <= 1048576 */
 } morphkv_config;
 
 typedef struct morphkv_handle morphkv_handle;

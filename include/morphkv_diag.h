@@ -37,7 +37,9 @@ int morphkv_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stream);
 
 /* How a decode launch over n_units units (all of the handle's, or one layer's) is laid out: 1 workgroup per unit
- * = the fused kernel; more = the split kernel, each workgroup on blocks_per_workgroup blocks of 32 slots. */
+ * = the fused kernel; more = the split kernel, each workgroup on blocks_per_workgroup blocks of 32 slots.  For a
+ * handle whose layers all keep every token: the workgroups per unit of the kernel made for those layers (1 or more)
+ * and the blocks each takes when the layer is full. */
 int morphkv_decode_plan(morphkv_handle *h, int32_t n_units, int32_t *workgroups_per_unit, int32_t *blocks_per_workgroup);
 
 #ifdef __cplusplus

@@ -93,7 +93,8 @@ struct BufLayout {
   size_t offRing, offSfx, offNw, offSpW, offSpPart, offSpCnt, ring_bytes;
   int sp_smax;     // most workgroups a unit is ever split over (1: the split kernel is never used, no workspace)
   int sp_force;    // MORPHKV_SPLIT_BPS: blocks per workgroup forced (tuning / tests), 0 = never split, -1 = choose
-  bool keep_all;   // layers that keep every token: no recorded rows, no aggregates; always the split kernel
+  bool keep_all;   // layers that keep every token: no recorded rows, no aggregates; decode_keep_kernel (or, on request,
+                   // the split kernel with one or more workgroups a unit)
   // scratch
   size_t offSrow, offStat, offF, offSel, offPlen, offLseW, scratch_bytes;
 };
@@ -128,6 +129,9 @@ int validate(const morphkv_config *c) {
   const long long U = (long long)c->n_layers * c->batch * c->n_kv_heads;
   if (U > 65535) return fail(MORPHKV_EINVAL, "too many units (layers*batch*kv_heads must be <= 65535)");
   if ((long long)c->C + c->R + (c->evict_every == 0 ? c->max_new_tokens : 0) > (1 << 20)) return fail(MORPHKV_EINVAL, "C + R too large");
+  if (c->n_keep_all_layers > 0 && (long long)c->max_prompt_len + c->max_new_tokens + c->R > (1 << 20))
+    return fail(MORPHKV_EINVAL, "n_keep_all_layers > 0: max_prompt_len + max_new_tokens + R = %lld slots per layer that keeps every token, "
+                "at most 1048576", (long long)c->max_prompt_len + c->max_new_tokens + c->R);
   return MORPHKV_OK;
 }
 
@@ -252,7 +256,7 @@ BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
       if (keep_all && keep_shares(units, L.n_pad) > L.sp_smax) L.sp_smax = keep_shares(units, L.n_pad);
     }
   }
-  const bool sp = L.sp_smax > 1 || keep_all;  // (a keep-all layer runs in the split kernel even with one workgroup a unit)
+  const bool sp = L.sp_smax > 1 || keep_all;  // (a layer that keeps every token always has the records and counters)
   L.offSpW = o; o = align_up(o + (sp && !keep_all ? U * (size_t)L.G * np * 4 : 0));
   L.offSpPart = o; o = align_up(o + (sp ? U * (size_t)L.sp_smax * split_part_floats(L.G, c->head_dim) * 4 : 0));
   L.offSpCnt = o; o = align_up(o + (sp ? U * 4 : 0));
@@ -968,7 +972,11 @@ int morphkv_calib_read(uint32_t *sink, const void *src, size_t bytes, void *stre
 int morphkv_decode_plan(morphkv_handle *h, int32_t n_units, int32_t *workgroups_per_unit, int32_t *blocks_per_workgroup) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   if (n_units < 1 || n_units > h->L.U) return fail(MORPHKV_EINVAL, "n_units %d outside 1..%d", n_units, h->L.U);
-  const SplitPlan pl = handle_plan(h, n_units);
+  SplitPlan pl = handle_plan(h, n_units);
+  if (h->keep_all && h->L.sp_force <= 0 && h->keep_kernel != 1) {  // decode_keep_kernel: shares interleaved block by block
+    pl.S = std::min(keep_shares(n_units, h->L.n_pad), h->L.sp_smax);
+    pl.bps = (h->L.n_pad / 32 + pl.S - 1) / pl.S;
+  }
   if (workgroups_per_unit) *workgroups_per_unit = pl.S;
   if (blocks_per_workgroup) *blocks_per_workgroup = pl.bps;
   return MORPHKV_OK;

@@ -124,7 +124,8 @@ def test_keep_all_layers_sizes_and_validation_on_host():
     assert c2 - cs <= units * (n_keep + 64) * (128 * 2 * 2 + 4) + (1 << 16)
     assert r2 - rs < 1 << 20 and r0 > rs
     for bad, word in ((dict(n_keep_all_layers=5), "n_keep_all_layers"), (dict(n_keep_all_layers=1, max_new_tokens=0), "max_new_tokens"),
-                      (dict(n_keep_all_layers=1, dtype="f32"), "bf16"), (dict(n_keep_all_layers=-1), "n_keep_all_layers")):
+                      (dict(n_keep_all_layers=1, dtype="f32"), "bf16"), (dict(n_keep_all_layers=-1), "n_keep_all_layers"),
+                      (dict(n_keep_all_layers=1, max_prompt_len=1 << 20), "1048576")):
         with pytest.raises(binding.MorphKVError) as e:
             binding.morphkv_sizes(binding.make_config(**dict(base, **bad)))
         assert e.value.code == binding.EINVAL and word in str(e.value)
