@@ -86,8 +86,8 @@ int morphkv_sizes(const morphkv_config *cfg, size_t *cache_bytes, size_t *ring_b
  * Environment variables, read by morphkv_sizes and here, override tuning choices and never change results:
  * MORPHKV_SPLIT_BPS (bf16: a positive value splits every unit over several workgroups of that many 32-slot blocks
  * each; unset or 0 = only units that one workgroup cannot hold are split),
- * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel; raised where the
- * window needs more), MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least),
+ * MORPHKV_DECODE_THREADS (multiple of 64 in 128..1024: threads per unit in the decode kernel),
+ * MORPHKV_DECODE_MIN_LDS (bytes of LDS to reserve per workgroup at least),
  * MORPHKV_KEEP_KERNEL ("split": layers that keep every token run in the split kernel instead of the kernel made for
  * them), MORPHKV_KEEP_SHARES (1..32: workgroups per unit of that kernel; unset = by the number of units in the
  * launch), MORPHKV_REBUILD_WAVES (1..16: how many waves of a unit's workgroup share the per-step rebuild of score aggregates;
@@ -173,11 +173,13 @@ int morphkv_decode_step_layer(morphkv_handle *h, int32_t layer, const void *q, c
                               float *out, void *stream /* hipStream_t */);
 
 /* Copies the retained positions to caller-owned DEVICE arrays (enqueued on the stream):
- *  pos    [U][Cs+R] int32, Cs = C+evict_every-1 (C+max_new_tokens when evict_every == 0): slots [0,Cs) = older tokens (-1 = empty), [Cs,Cs+R) =
- *         window slot (position mod R).  With n_keep_all_layers > 0 the rows are max(Cs, Ck) + R long, Ck =
- *         max_prompt_len + max_new_tokens being the older-token slots of a layer that keeps everything: a unit's row
- *         holds its own older-token slots, then its R window slots, then -1
- *  n_snap [U]      int32: older tokens currently held */
+ *  pos    [U][Cs+R] int32, Cs = C+evict_every-1 (C+max_new_tokens when evict_every == 0): the position of the token
+ *         each cache slot holds, -1 = free, in the cache's own order (a token keeps the slot it was written to
+ *         until it is evicted: Eq.7 decides by position who is "older", not by slot).  A unit's window are its R
+ *         largest positions, its older tokens all others.  With n_keep_all_layers > 0 the rows are max(Cs, Ck) + R
+ *         long, Ck = max_prompt_len + max_new_tokens being the older-token capacity of a layer that keeps
+ *         everything: a unit's row holds its own slots, then -1
+ *  n_snap [U]      int32: older tokens currently held (tokens that are not among the R most recent) */
 int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, void *stream);
 /* evicted [U] int32 device: position evicted by the last decode step, -1 if none (with evict_every > 1:
  * the first of them). */

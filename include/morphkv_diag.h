@@ -13,7 +13,9 @@ extern "C" {
 #endif
 
 /* Optional capture of the fused scores each decode step takes its decision on:
- * F device [U][Cs+1] fp32 (slot order; [Cs] = the token leaving the window), or NULL to stop.
+ * F device [U][n_pad] fp32, n_pad = Cs + R rounded up to a multiple of 32 (Cs as for morphkv_export_positions): the
+ * score of every eviction candidate -- a token older than the window that includes the new token -- at the slot
+ * morphkv_export_positions reported for it before the step; other elements are left as they are.  NULL to stop.
  * Costs 4 bytes written per older token per step while enabled. */
 int morphkv_capture_scores(morphkv_handle *h, float *F);
 

@@ -257,7 +257,8 @@ class MorphKV:
             _check(rc)
 
     def export_positions(self):
-        """(pos [U, C+R] int32, n_snap [U] int32) device tensors."""
+        """(pos [U, C+R] int32: the position each cache slot holds, in the cache's own order, -1 = free; n_snap [U] int32:
+        how many of a unit's tokens are older than its R most recent) device tensors."""
         pos = torch.empty(self.U, self.n, dtype=torch.int32, device=self.device)
         n_snap = torch.empty(self.U, dtype=torch.int32, device=self.device)
         _check(self.lib.morphkv_export_positions(self._h, _dev_ptr(pos), _dev_ptr(n_snap), self._stream()))
@@ -281,9 +282,10 @@ class MorphKV:
         return a.value, b.value
 
     def capture_scores(self, enable=True):
-        """Returns the [U, C+1] fp32 device tensor the next decode steps write their fused scores to."""
+        """Returns the [U, n_pad] fp32 device tensor the next decode steps write their fused scores to: one per cache
+        slot (the order of export_positions; n_pad = C + R slots rounded up to 32) that holds an eviction candidate."""
         if enable:
-            self._scoreF = torch.zeros(self.U, self.Cs + 1, dtype=torch.float32, device=self.device)
+            self._scoreF = torch.zeros(self.U, (self.Cs + self.cfg.R + 31) // 32 * 32, dtype=torch.float32, device=self.device)
             _check(self.lib.morphkv_capture_scores(self._h, _dev_ptr(self._scoreF)))
         else:
             _check(self.lib.morphkv_capture_scores(self._h, None))

@@ -6,10 +6,11 @@
 //   softmax  : exact max / sum over slots + the token itself; fp32 weights stay in LDS
 //   record   : S[j] = sum_g p_g[j] -> newest ring row; per-column running aggregate and fused score
 //   V pass   : O_g = sum_j p_g[j] V_j + p_g[self] v_new
-//   select   : evict argmin fused score among C older tokens + the token leaving the window
-//              (ties evict the higher position), or append while fewer than C are held
-//   compact  : token leaving the window takes the freed slot (K, V, position, its column of the R rows,
-//              its aggregate state); the new token takes the window slot.
+//   select   : evict argmin fused score among the tokens that are older than the window once the new one is in
+//              (ties evict the higher position), while more than C of them are held
+//   commit   : the new token takes the slot the eviction has freed (or the next unused one).  No token ever
+//              changes its slot: "older" is decided by position, every slot is a column of the score state
+//              from its occupant's birth, and rows recorded before that are masked where the column is rebuilt.
 //
 // Two data paths:
 //   bf16 : K and V live in MFMA-operand tile order (see Layout<bf16_t, D>) so that a wave reads 1 KB
@@ -25,7 +26,9 @@
 
 namespace mkv {
 
-constexpr int META = 8;  // per unit: n_snap, next_pos, last_evicted, next_pos mod R, prompt length, 3 unused
+// per unit: 0 slots in use (high-water mark: slots below it hold a token or are free again), 1 next position,
+// 2 last evicted position, 3 next position mod R, 4 prompt length, 5 free slots below the mark (coarse schedule), 2 unused
+constexpr int META = 8;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -35,24 +38,25 @@ struct DecodeParams {
   int32_t *pos;            // [U][n_pad]
   int32_t *meta;           // [U][META]
   float *ring;             // [U][R][n_pad]  recorded rows, row index = query position mod R
-  float *sfx;              // [U][R][CsP]    old-part aggregates (see column_scan)
+  float *sfx;              // [U][R][CsP]    old-part aggregates (see column_scan); CsP = n_pad: every slot is a column
   float *nw;               // [U][CsP]       new-part aggregates
   const void *q, *k_new, *v_new;
   float *out;
-  float *dbgF;             // nullable: [U][Cs+1]
+  float *dbgF;             // nullable: [U][n_pad] fused score of every eviction candidate, by slot
   long long *dbgT;         // nullable: [U][8] phase time stamps (diagnostics)
   int32_t Cs, CsP, R, n, n_pad, Mq, Mkv, fusion, cps, cpt;
   int32_t cpt_shift;       // log2(cpt) if cpt is a power of two, else -1
   int32_t C, T;            // older tokens kept by a selection; selection every T steps (Appendix A.5), Cs = C+T-1
   int32_t *evl;            // [U][T] positions evicted by the last step, -1 padded
+  int32_t *holes;          // [U][T] coarse schedule: slots below the high-water mark that are free (a stack, meta[5] deep)
   int32_t zig;             // parity of the step count: direction of the walk over the cache
   // split kernel only (decode_split.h): workspace of the partial results and the arrival counters
   float *sp_part;          // [U][sp_smax][2G + G*D] local maximum, local sum, partial output per workgroup
   float *sp_w;             // [U][G][n_pad] logits of the step
   int32_t *sp_cnt;         // [U] workgroups of the unit that have finished their share (0 between launches)
   int32_t sp_bps, sp_smax; // blocks of 32 slots per workgroup; record stride of sp_part
-  int32_t keep_all;        // split kernel only: a layer that keeps every token (Appendix A.6): nothing is recorded,
-                           // fused or selected; the token leaving the window is appended to the older tokens
+  int32_t keep_all;        // a layer that keeps every token (Appendix A.6): nothing is recorded, fused or selected;
+                           // every new token is appended
   int32_t nt_k, nt_v;      // K tile groups [0, nt_k) and V tiles [0, nt_v) of every unit are loaded with the
                            // non-temporal hint (they stream from HBM); the rest is meant to stay cache-resident
   int32_t keep_cached_blocks;  // decode_keep_kernel: a unit's newest blocks of 32 slots that are read with ordinary loads
@@ -105,17 +109,14 @@ __host__ __device__ inline int turn_cols_padded(int cps) {
 inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, int CsP, int T) {
   const size_t lg = (size_t)G * (n_pad + 4), om = (size_t)(NT / 64) * G * D;
   const size_t cpt = (size_t)turn_cols_padded(cps);
-  size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + (size_t)R /*colv*/ +
-              16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
-  if (T > 1)
-    fl += 2 * (size_t)CsP /*scores, positions*/ + (size_t)(NT / 64) * R /*a column per wave*/ + 2 * (size_t)T /*lists*/ +
-          2 * 3 * 16 /*per-wave minima, two sets*/;
+  size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + 16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
+  if (T > 1) fl += 2 * (size_t)CsP /*scores, positions*/ + 2 * 3 * 16 /*per-wave minima, two sets*/;
   return fl * 4;
 }
 
-__device__ inline bool slot_valid(int j, int n_snap, int Cs, int nwin) {
-  return j < n_snap || (unsigned)(j - Cs) < (unsigned)nwin;  // (one comparison for Cs <= j < Cs + nwin)
-}
+// slots below the high-water mark hold a token (or, under the coarse schedule, are free again: those are masked
+// by their position, -1, where the weights are formed)
+__device__ inline bool slot_valid(int j, int n_used) { return j < n_used; }
 
 // 16-byte global load; STREAM: with the non-temporal hint (the line is not kept in the caches it passes)
 template <bool STREAM> __device__ inline uint4 ldg16(const void *p) {
@@ -212,7 +213,9 @@ __device__ inline void wave_argmin(float &f, int &p, int &c) {
 }
 
 // A wave rebuilds the aggregate state of some of the columns whose turn it is at the start of step p
-// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1.  Results stay in LDS:
+// (phase (p-1) mod R) from the R-1 rows of steps p-R+1 .. p-1, of which those up to the step at which the column's
+// present token was born (its own position) count as zero: they hold weights of the slot's former occupant.
+// Results stay in LDS:
 //   stage[i*cpt + cc] = f(rows of steps p-1-i .. p-1) of column c0+cc   (i = 0..R-2), to be stored to
 //                       sfx row (p-2-i) mod R by the whole workgroup later;
 //   turn[cc]          = f(all R-1 rows): the old part of this step's score for that column.
@@ -240,17 +243,19 @@ __host__ __device__ inline int turn_group_width(int R, int rows, int cps, int NW
 template <int RBT> struct TurnRebuildT {
   int lane, p, R, rs, cpt, fusion, c0, ncol, r_top, gw, gstride, g0;
   const float *ringu;
+  const int32_t *posu;
   // current column group
   int cg, CP, lg2, Q, cc, q, c, Lc, i0, i1;
+  int age;  // rows 0 .. age-1 (steps p-1 .. p-age) are the present token's; 0 for a free slot
   bool colok;
 
   // k-th of nrw rebuilding waves
-  __device__ inline void init(int lane_, int p_, int wm1, int n_snap, int R_, int rs_, int cps, int cpt_,
-                              int fusion_, const float *ringu_, int k, int nrw, int gw_) {
-    lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_;
+  __device__ inline void init(int lane_, int p_, int wm1, int n_used, int R_, int rs_, int cps, int cpt_,
+                              int fusion_, const float *ringu_, const int32_t *posu_, int k, int nrw, int gw_) {
+    lane = lane_; p = p_; R = R_; rs = rs_; cpt = cpt_; fusion = fusion_; ringu = ringu_; posu = posu_;
     r_top = wm1;  // (p-1) mod R: ring row of row i = 0
     c0 = wm1 * cps;
-    ncol = n_snap - c0;
+    ncol = n_used - c0;
     ncol = ncol < 0 ? 0 : (ncol > cps ? cps : ncol);
     gw = gw_;
     g0 = k * gw;
@@ -269,10 +274,14 @@ template <int RBT> struct TurnRebuildT {
     i0 = min(q * Lc, R - 1); i1 = min(i0 + Lc, R - 1);
   }
   // rows i0+b .. i0+b+RBT-1 of this lane's chunk (a chunk is shorter than R rows: one wrap at most)
-  __device__ inline void load(int b, float (&v)[RBT]) const {
+  __device__ inline void load(int b, float (&v)[RBT]) {
     // every load is in bounds (row taken mod R, column clamped); what lies outside the chunk is ignored
     // when the batch is consumed, so issuing it is straight-line code that waits for nothing.  Past the end of
     // a short chunk the chunk's last row is asked for again: the same cache line, no new request to memory.
+    if (b == 0) {
+      const int pc = posu[colok ? c : c0];
+      age = pc < 0 ? 0 : p - 1 - pc;
+    }
     const int ib = i0 + b;
     int r0 = r_top - ib;  // ib < R
     r0 += r0 < 0 ? R : 0;
@@ -302,7 +311,7 @@ template <int RBT> struct TurnRebuildT {
 #pragma unroll
         for (int k = 0; k < RBT; ++k)
           if (k < nv) {
-            acc = fuse2(fusion, acc, v[k]);
+            acc = fuse2(fusion, acc, i0 + k < age ? v[k] : 0.f);
             v[k] = acc;
           }
       } else {
@@ -310,7 +319,7 @@ template <int RBT> struct TurnRebuildT {
 #pragma unroll
           for (int k = 0; k < RBT; ++k)
             if (b + k < nv) {
-              acc = fuse2(fusion, acc, v[k]);
+              acc = fuse2(fusion, acc, i0 + b + k < age ? v[k] : 0.f);
               st[(b + k) * cpt] = acc;
             }
           b += RBT;
@@ -350,238 +359,102 @@ template <int RBT> struct TurnRebuildT {
 };
 using TurnRebuild = TurnRebuildT<RB>;
 
-// One wave computes the aggregate state of a single column from its R row values colv[a] (row of step
-// p-R+1+a), as of the end of step p with rebuild point p0 (same result as column_scan), and stores it.
-__device__ inline void move_scan_wave(int lane, int p, int p0, int R, int fusion, const float *colv, float *sfx_col,
-                                      int CsP, float *nw_out) {
-  const int a0 = p0 - (p - R + 1);  // row index of the rebuild point, in [-1, R-2]
-  // new part: rows after the rebuild point
-  float nwv = 0.f;
-  for (int a = a0 + 1 + lane; a < R; a += WAVE) nwv = fuse2(fusion, nwv, colv[a]);
-  nwv = fusion == 0 ? wave_sum_dpp(nwv) : wave_max_dpp(nwv);
-  // old part: b = a0 - a counts back from the rebuild point; aggregate of rows a..a0 is stored in the sfx
-  // row (t-1) mod R with t = p-R+1+a, for a >= 1
-  float carry = 0.f;
-  int r = pmod(p - R + a0 - lane, R);
-  for (int b0 = 0; b0 < a0; b0 += WAVE) {
-    const int b = b0 + lane;
-    float x = b < a0 ? colv[a0 - b] : 0.f;
-#pragma unroll
-    for (int s = 1; s < WAVE; s <<= 1) {
-      const float o = __shfl_up(x, s);
-      if (lane >= s) x = fuse2(fusion, x, o);
-    }
-    x = fuse2(fusion, x, carry);
-    if (b < a0) sfx_col[(size_t)r * CsP] = x;
-    carry = __shfl(x, WAVE - 1);
-    r -= WAVE;
-    while (r < 0) r += R;
-  }
-  if (lane == 0) {
-    sfx_col[(size_t)pmod(p0, R) * CsP] = 0.f;
-    *nw_out = nwv;
-  }
-}
-
-// ---- the end of a step, shared by the fused kernel and the merging workgroup of the split kernel -------------
+// ---- the end of a step, shared by the fused kernel, the merging workgroup of the split kernel and the kernel of
+// the layers that keep every token ---------------------------------------------------------------------------
 // Everything the two functions below need of a workgroup's state.  LDS arrays (see the carve-up in the kernels):
-//   sh  [16] 2: dest slot of the token leaving the window (-1: none), 3: evicted position, 4: new n_snap,
-//            5: a selection among more than C+1 candidates is due, 6: movers
-//   shf [16] 9: fused score of the token leaving the window
-//   Fl, Pl [CsP] fused score and position per older-token slot, colw [NW][R], lists [2][T], best2 [2][3][16] (T > 1 only)
-//   colv [R] column of the token leaving the window, oldest row first
+//   sh  [16] 2: slot of the new token (-1: the first slot the selection below frees), 3: evicted position,
+//            4: new number of slots in use, 5: tokens a selection under the coarse schedule has to evict (0: none),
+//            6: new number of free slots below the mark
+//   Fl, Pl [CsP] fused score (+inf: not a candidate) and position per slot, best2 [2][3][16] (T > 1 only)
 template <typename T> struct StepTail {
   const DecodeParams &P;
-  int u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w;
-  bool cum;
-  int fusion, Tev;
+  int u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, Tev;
   int *sh;
-  float *shf, *Fl;
+  float *Fl;
   int *Pl;
-  float *colw;
-  int *lists;
-  float *best2, *colv, *ringu, *sfxu, *nwu;
+  float *best2, *nwu;
   int32_t *posu;
   const T *knew, *vnew;
 };
 
+// Selection of the C best of up to C+T older tokens (Eq.7 with the coarse schedule of Appendix A.5): the sh[5]
+// candidates with the smallest scores go (ties: the higher position goes).  Their slots become free: the new token
+// takes the first, the others wait on the unit's stack of free slots for the tokens of the next steps.
 template <typename T, int D>
-__device__ __forceinline__ void coarse_select_and_move(const StepTail<T> &c) {
+__device__ __forceinline__ void coarse_select(const StepTail<T> &c) {
   const DecodeParams &P = c.P;
-  const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane;
-  const int Cs = c.Cs, CsP = c.CsP, R = c.R, n_pad = c.n_pad, cps = c.cps, n_snap = c.n_snap, p = c.p, w = c.w;
-  const bool cum = c.cum;
-  const int fusion = c.fusion, Tev = c.Tev;
+  const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane, n_used = c.n_used, Tev = c.Tev;
   int *sh = c.sh;
-  float *shf = c.shf, *Fl = c.Fl, *colw = c.colw, *best2 = c.best2, *colv = c.colv;
-  int *Pl = c.Pl, *lists = c.lists;
-  float *ringu = c.ringu, *sfxu = c.sfxu, *nwu = c.nwu;
+  float *Fl = c.Fl, *best2 = c.best2;
+  int *Pl = c.Pl;
   int32_t *posu = c.posu;
-  const T *knew = c.knew, *vnew = c.vnew;
-  using L = Layout<T, D>;
-  constexpr int EPL = Elem<T>::EPL;
-  (void)NW; (void)cps; (void)n_snap; (void)cum; (void)fusion; (void)Fl; (void)Pl; (void)colw; (void)best2; (void)lists;
-  (void)colv; (void)sfxu; (void)nwu; (void)ringu; (void)knew; (void)vnew; (void)shf; (void)CsP; (void)lane; (void)wave;
-  // ---- selection of the C best of up to C+T older tokens (Eq.7 with the coarse schedule of Appendix A.5):
-  // the n_snap+1-C candidates with the smallest scores go (ties: the higher position goes), survivors
-  // beyond slot C and the token leaving the window move into the freed slots below C.
   if (Tev > 1) {
-    int32_t *evl = P.evl + (size_t)u * Tev;
-    const int n_ev = sh[5] ? n_snap + 1 - P.C : 0;  // 1..T at a selection step
+    int32_t *evl = P.evl + (size_t)u * Tev, *holes = P.holes + (size_t)u * Tev;
+    const int n_ev = sh[5];  // 1..T at a selection step
     if (tid >= n_ev && tid < Tev) evl[tid] = -1;
-    if (n_ev > 0) {
-      int *hole = lists, *msrc = lists + Tev;
-      const int wsl = Cs + w;
-      // n_ev rounds, each taking out the candidate that goes first.  Every wave works the round's result out
-      // for itself from the per-wave minima (two sets, used in turn: one barrier per round); slot j is read
-      // and, once taken, struck out by thread j mod NT only.
-      float fd = shf[9];  // score of the token leaving the window; +inf once it has been taken
-      int nh = 0;         // slots below C freed so far
-      for (int it = 0; it < n_ev; ++it) {
-        float f = INFINITY;
-        int bp = -1, bc = -1;
-        for (int j = tid; j < n_snap; j += NT) {
-          const float F = Fl[j];
-          const int pj = Pl[j];
-          if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
-        }
-        wave_argmin(f, bp, bc);
-        float *bF = best2 + (it & 1) * 48;
-        int *bPp = (int *)bF + 16, *bCc = (int *)bF + 32;
-        if (lane == 0) { bF[wave] = f; bPp[wave] = bp; bCc[wave] = bc; }
-        lds_barrier();
-        f = INFINITY; bp = -1; bc = -1;
-        if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
-        wave_argmin(f, bp, bc);
-        if (cand_before(f, bp, fd, p - R)) { bc = wsl; bp = p - R; fd = INFINITY; }
-        else if (bc % NT == tid) Fl[bc] = INFINITY;
-        if (tid == 0) {
-          evl[it] = bp;
-          if (it == 0) sh[3] = bp;
-          if (bc < P.C) hole[nh] = bc;
-        }
-        nh += bc < P.C;
+    // n_ev rounds, each taking out the candidate that goes first.  Every wave works the round's result out
+    // for itself from the per-wave minima (two sets, used in turn: one barrier per round); slot j is read
+    // and, once taken, struck out by thread j mod NT only.
+    for (int it = 0; it < n_ev; ++it) {
+      float f = INFINITY;
+      int bp = -1, bc = -1;
+      for (int j = tid; j < n_used; j += NT) {
+        const float F = Fl[j];
+        const int pj = Pl[j];
+        if (cand_before(f, bp, F, pj)) { f = F; bp = pj; bc = j; }
       }
-      lds_barrier();  // the last round's strike-out is visible
-      // movers = survivors at or above C, then the token leaving the window: as many as slots freed below C,
-      // at most T, listed by one wave
-      if (wave == 0) {
-        const int j = P.C + lane;  // n_snap - C <= T - 1 <= 63 candidates above C, then the window token
-        const bool mover = j < n_snap ? Fl[j] != INFINITY : (j == n_snap && fd != INFINITY);
-        const unsigned long long m = __ballot(mover);
-        if (mover) msrc[__popcll(m & ((1ull << lane) - 1ull))] = j < n_snap ? j : wsl;
-        if (lane == 0) sh[6] = nh;
+      wave_argmin(f, bp, bc);
+      float *bF = best2 + (it & 1) * 48;
+      int *bPp = (int *)bF + 16, *bCc = (int *)bF + 32;
+      if (lane == 0) { bF[wave] = f; bPp[wave] = bp; bCc[wave] = bc; }
+      lds_barrier();
+      f = INFINITY; bp = -1; bc = -1;
+      if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
+      wave_argmin(f, bp, bc);
+      if (bc >= 0 && bc % NT == tid) Fl[bc] = INFINITY;
+      if (tid == 0 && bc >= 0) {
+        evl[it] = bp;
+        posu[bc] = -1;
+        if (it == 0) { sh[3] = bp; sh[2] = bc; }
+        else holes[it - 1] = bc;
       }
-      __syncthreads();
-      const int nm = sh[6];
-      T *Kx = (T *)P.K + (size_t)u * n_pad * D;
-      T *Vx = (T *)P.V + (size_t)u * n_pad * D;
-      for (int m = wave; m < nm; m += NW) {
-        const int src = msrc[m], dst = hole[m];
-        float *cb = colw + (size_t)wave * R;
-        for (int a = lane; a < R; a += WAVE) {
-          int r = w + 1 + a;
-          r -= r >= R ? R : 0;
-          const float x = ringu[(size_t)r * n_pad + src];
-          cb[a] = x;
-          ringu[(size_t)r * n_pad + dst] = x;
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_wave_barrier();
-        if (cum && src != wsl) {
-          // a running sum reaches further back than the R rows: it moves with the token (the record phase's
-          // store of nw[src] is visible since the barrier after the V pass)
-          if (lane == 0) nwu[dst] = nwu[src];
-        } else {
-          move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dst / cps, R), R, fusion, cb, sfxu + dst, CsP,
-                         nwu + dst);
-        }
-        constexpr int PCSx = D / EPL;
-        if (lane < PCSx) *(uint4 *)(Kx + L::k_off(dst, lane * EPL)) = *(const uint4 *)(Kx + L::k_off(src, lane * EPL));
-        if constexpr (L::tiled) {
-          for (int ch = lane; ch < D; ch += WAVE) ((uint16_t *)Vx)[L::v_off(dst, ch)] = ((const uint16_t *)Vx)[L::v_off(src, ch)];
-        } else {
-          if (lane < PCSx) *(uint4 *)(Vx + L::v_off(dst, lane * EPL)) = *(const uint4 *)(Vx + L::v_off(src, lane * EPL));
-        }
-        if (lane == 0) posu[dst] = src == wsl ? p - R : Pl[src];
-      }
-      __syncthreads();  // movers have read their sources before slots are cleared / the window slot is rewritten
-      for (int j = P.C + tid; j < Cs; j += NT) posu[j] = -1;
     }
+    if (n_ev > 0) __syncthreads();  // the new token's slot is known to everybody
   }
 }
 
-// PRE: the caller has already loaded this thread's piece of the window slot's K row (kpre: threads 0 .. D/EPL-1) and
-// its element of the V row (vpre; bf16 caches: thread tid holds channel NT-1-tid, workgroups of at least D threads)
-template <typename T, int D, bool CLK, bool PRE = false>
-__device__ __forceinline__ void compact_and_commit(const StepTail<T> &c, uint4 kpre = uint4{0u, 0u, 0u, 0u},
-                                                   uint16_t vpre = 0) {
+// The new token takes its slot: K, V, position, an empty new-part aggregate (the slot's old part is ignored until
+// the column's next turn, see record4); the unit's counters move on.
+template <typename T, int D, bool CLK>
+__device__ __forceinline__ void commit_step(const StepTail<T> &c) {
   const DecodeParams &P = c.P;
-  const int u = c.u, tid = c.tid, NT = c.NT, NW = c.NW, wave = c.wave, lane = c.lane;
-  const int Cs = c.Cs, CsP = c.CsP, R = c.R, n_pad = c.n_pad, cps = c.cps, n_snap = c.n_snap, p = c.p, w = c.w;
-  const bool cum = c.cum;
-  const int fusion = c.fusion, Tev = c.Tev;
+  const int u = c.u, tid = c.tid, NT = c.NT, n_pad = c.n_pad, p = c.p, w = c.w;
   int *sh = c.sh;
-  float *shf = c.shf, *Fl = c.Fl, *colw = c.colw, *best2 = c.best2, *colv = c.colv;
-  int *Pl = c.Pl, *lists = c.lists;
-  float *ringu = c.ringu, *sfxu = c.sfxu, *nwu = c.nwu;
-  int32_t *posu = c.posu;
-  const T *knew = c.knew, *vnew = c.vnew;
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
-  (void)NW; (void)cps; (void)n_snap; (void)cum; (void)fusion; (void)Fl; (void)Pl; (void)colw; (void)best2; (void)lists;
-  (void)colv; (void)sfxu; (void)nwu; (void)ringu; (void)knew; (void)vnew; (void)shf; (void)CsP; (void)lane; (void)wave;
-  // ---- compaction: token p-R (window slot) -> freed slot `dest`; new token -> window slot
   const int dest = sh[2];
-  const int wslot = Cs + w;
   T *Kw_ = (T *)P.K + (size_t)u * n_pad * D;
   T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
   constexpr int PCS = D / EPL;  // 16-byte pieces per row
-  if (tid < PCS) {              // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
-    const int ch0 = tid * EPL;
-    uint4 *src = (uint4 *)(Kw_ + L::k_off(wslot, ch0));
-    if (dest >= 0) *(uint4 *)(Kw_ + L::k_off(dest, ch0)) = PRE ? kpre : *src;
-    *src = ((const uint4 *)knew)[tid];
-  }
+  if (tid < PCS)                // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
+    *(uint4 *)(Kw_ + L::k_off(dest, tid * EPL)) = ((const uint4 *)c.knew)[tid];
   if constexpr (L::tiled) {
     // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
-    for (int ch = NT - 1 - tid; ch < D; ch += NT) {
-      uint16_t *src = (uint16_t *)Vw_ + L::v_off(wslot, ch);
-      if (dest >= 0) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = PRE ? vpre : *src;
-      *src = ((const uint16_t *)vnew)[ch];
-    }
+    for (int ch = NT - 1 - tid; ch < D; ch += NT) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = ((const uint16_t *)c.vnew)[ch];
   } else {
-    if (tid >= 64 && tid < 64 + PCS) {
-      const int ch0 = (tid - 64) * EPL;
-      uint4 *src = (uint4 *)(Vw_ + L::v_off(wslot, ch0));
-      if (dest >= 0) *(uint4 *)(Vw_ + L::v_off(dest, ch0)) = *src;
-      *src = ((const uint4 *)vnew)[tid - 64];
-    }
-  }
-  if (dest >= 0 && P.keep_all) {
-    if (tid == 0) posu[dest] = p - R;  // no recorded rows, no aggregates to move
-  } else if (dest >= 0) {
-    if (wave == NW - 1) {
-      if (lane == 0) posu[dest] = p - R;
-      move_scan_wave(lane, p, cum ? p - R : last_rebuild_before(p, dest / cps, R), R, fusion, colv, sfxu + dest, CsP,
-                     nwu + dest);
-    } else {
-      const int stride = NT - WAVE;
-      int r = (w + 1 + tid) % R;
-      for (int a = tid; a < R; a += stride) {
-        ringu[(size_t)r * n_pad + dest] = colv[a];
-        r += stride;
-        while (r >= R) r -= R;
-      }
-    }
+    if (tid >= 64 && tid < 64 + PCS)
+      *(uint4 *)(Vw_ + L::v_off(dest, (tid - 64) * EPL)) = ((const uint4 *)c.vnew)[tid - 64];
   }
   if (tid == 0) {
-    posu[wslot] = p;
+    c.posu[dest] = p;
+    if (!P.keep_all) c.nwu[dest] = 0.f;
     int32_t *m = P.meta + (size_t)u * META;
     m[0] = sh[4];
     m[1] = p + 1;
     m[2] = sh[3];
+    const int R = P.R;
     m[3] = w + 1 == R ? 0 : w + 1;
+    m[5] = sh[6];
     if (CLK && P.dbgT) P.dbgT[(size_t)u * 8 + 4] = wall_clock64();
   }
 }
@@ -619,22 +492,18 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   float *lg = smem;                       // [G][lgs] logits -> exp -> weights; later [NW][G][D] output partials
   float *stage = lg + lgsz;               // [R][cpt] rebuilt aggregates on their way to the sfx rows
   float *turn = stage + (size_t)R * cpt;  // [cpt] old-part aggregate of the columns rebuilt this step
-  float *colv = turn + cpt;               // [R]   column of the token leaving the window, oldest row first
-  float *red = colv + R;                  // [16][8]
+  float *red = turn + cpt;                // [16][8]
   float *red2 = red + 16 * 8;             // [16][8]
   float *bestF = red2 + 16 * 8;           // [16]
   int *bestC = (int *)(bestF + 16);       // [16]
   int *bestP = bestC + 16;                // [16]
-  int *sh = bestP + 16;                   // [16] 0: K tile counter; 2: dest slot; 3: evicted; 4: new n_snap
-  float *shf = (float *)(sh + 16);        // [16] 0: weight of the new row on the token leaving the window;
-                                          //      1..8: logits of the token against its own key; 9: its score
+  int *sh = bestP + 16;                   // [16] 0: K tile counter; 2..6: see StepTail
+  float *shf = (float *)(sh + 16);        // [16] 1..8: logits of the token against its own key
   // selection every T > 1 steps only:
   const int Tev = COARSE ? P.T : 1;
-  float *Fl = shf + 16;                   // [CsP] fused score per older-token slot
+  float *Fl = shf + 16;                   // [CsP] fused score per slot (+inf: not a candidate)
   int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP] its position
-  float *colw = (float *)(Pl + (Tev > 1 ? CsP : 0));      // [NW][R] a column of the R rows per wave, oldest first
-  int *lists = (int *)(colw + (Tev > 1 ? NW * R : 0));    // [2][Tev]: freed slot below C, slot that moves there
-  float *best2 = (float *)(lists + 2 * Tev);              // [2][3][16] per-wave minima of the selection rounds
+  float *best2 = (float *)(Pl + (Tev > 1 ? CsP : 0));     // [2][3][16] per-wave minima of the selection rounds
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -647,8 +516,9 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 
   // the unit's state is asked for first and looked at only after the first K loads are on their way
   const int32_t *meta = P.meta + (size_t)u * META;
-  const int n_snap = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
+  const int n_used = meta[0], p = meta[1], w = meta[3];  // w = p mod R, kept by the kernel itself
   const int gen_step = p - meta[4] + 1;                  // the new token is this sequence's gen_step-th generated one
+  const int n_holes = COARSE ? meta[5] : 0;              // free slots below n_used (left by a selection that took several)
   const bool sel_step = COARSE && P.T > 1 && gen_step % P.T == 0;  // coarse schedule: a step at which a selection may run
 
   // ---- bf16 path: the first K tiles of every wave and the query fragments go out before anything that
@@ -690,11 +560,9 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     }
   }
 
-  const int nwin = p < R ? p : R;
   const int wm1 = w == 0 ? R - 1 : w - 1;  // (p-1) mod R
-  const bool win_full = p >= R;
   const int turn0 = wm1 * cps;             // first column rebuilt this step
-  int turn_n = n_snap - turn0;             // how many of them exist
+  int turn_n = n_used - turn0;             // how many of them exist
   turn_n = turn_n < 0 || cum ? 0 : (turn_n > cps ? cps : turn_n);
 
   float *ringu = P.ring + (size_t)u * R * n_pad;
@@ -715,33 +583,23 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   for (int i = 0; i < MAXQ; ++i) {
     const int j0 = 4 * (tid + i * NT);
     pn[i] = make_float4(0.f, 0.f, 0.f, 0.f); ps[i] = pn[i]; pp[i] = make_int4(-1, -1, -1, -1);
-    if (j0 < n_snap) {
+    if (j0 < n_used) {
       pn[i] = *(const float4 *)(nwu + j0);
       ps[i] = *(const float4 *)(sfxu + (size_t)w * CsP + j0);
       pp[i] = *(const int4 *)(posu + j0);
     }
   }
-
-  // ---- column of the token leaving the window (rows of steps p-R+1 .. p-1, oldest first): into registers
-  // now, into LDS after the K pass
-  constexpr int CVB = 4;  // R - 1 <= 1023 values over >= 256 threads (groups of 128: R <= 512, the host sees to it)
-  float cvr[CVB];
-  {
-#pragma unroll
-    for (int k = 0; k < CVB; ++k) {
-      const int a = tid + k * NT;  // row of step p-R+1+a lives in ring row (w+1+a) mod R
-      int r = w + 1 + a;
-      r -= r >= R ? R : 0;
-      cvr[k] = 0.f;
-      if (a < R - 1 && win_full) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
-    }
+  // the slot a free-slot stack hands to the new token, if there is one (coarse schedule)
+  int hole_top = -1;
+  if constexpr (COARSE) {
+    if (n_holes > 0) hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
   }
   // ---- the waves rebuild the columns whose turn it is, a group of columns each
   TurnRebuild tr;
   float rbv[RB];
   const int tgw = P.rb_gw, nrw = P.rb_nrw;
   if (wave >= NW - nrw) {
-    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw, tgw);
+    tr.init(lane, p, wm1, cum ? 0 : n_used, R, n_pad, cps, cpt, fusion, ringu, posu, NW - 1 - wave, nrw, tgw);
     tr.begin(rbv);  // its rows are on their way while the wave works off its first tile group
   }
 
@@ -790,7 +648,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int j = tile * 16 + 4 * kq + i;
-            l4[i] = slot_valid(j, n_snap, Cs, nwin) ? acc[i] * P.scale_log2 : -INFINITY;
+            l4[i] = slot_valid(j, n_used) ? acc[i] * P.scale_log2 : -INFINITY;
           }
           mx[0] = fmaxf(fmaxf(mx[0], fmaxf(l4[0], l4[1])), fmaxf(l4[2], l4[3]));
           *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
@@ -876,7 +734,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
       for (int i = 0; i < UNR; ++i) {
         const int j = tile * RPT + i * RPL + rowsub;
-        ok[i] = slot_valid(j, n_snap, Cs, nwin);
+        ok[i] = slot_valid(j, n_used);
         if (ok[i]) r[i] = ((const uint4 *)(Kb + (size_t)j * D))[chunk];
       }
 #pragma unroll
@@ -913,12 +771,6 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       const float v = wave_max_dpp(mx[g]);
       if (lane == 0) red[wave * 8 + g] = v;
     }
-  }
-
-#pragma unroll
-  for (int k = 0; k < CVB; ++k) {
-    const int a = tid + k * NT;
-    if (a < R - 1) colv[a] = cvr[k];
   }
 
   // ---- first V tile of this wave goes in flight now: it does not depend on the softmax
@@ -961,11 +813,20 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
     for (int jq = tid; jq < nq; jq += NT) {
+      // coarse schedule: slots a selection has freed and no token has taken yet still hold their old key; their
+      // weight is zero (the maximum above may include their logit: any reference does for a softmax)
+      [[maybe_unused]] int4 hp = make_int4(0, 0, 0, 0);
+      if constexpr (COARSE) {
+        if (n_holes > 0) hp = *(const int4 *)(posu + 4 * jq);
+      }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
         l.x = exp2_native(l.x - M[g]); l.y = exp2_native(l.y - M[g]); l.z = exp2_native(l.z - M[g]); l.w = exp2_native(l.w - M[g]);
+        if constexpr (COARSE) {
+          l.x = hp.x < 0 ? 0.f : l.x; l.y = hp.y < 0 ? 0.f : l.y; l.z = hp.z < 0 ? 0.f : l.z; l.w = hp.w < 0 ? 0.f : l.w;
+        }
         *pl = l;
         zs[g] += (l.x + l.y) + (l.z + l.w);
       }
@@ -994,7 +855,12 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   // ---- record the row, update per-column aggregates, fused scores, local argmin
   float bF = INFINITY;
   int bP = -1, bC = -1;
-  auto record4 = [&](int j0, float4 nw_old, float4 sfx_old, int4 pj4) {
+  // Every slot in use is a column.  Its old part (the sfx row) counts only if the column has had a turn since its
+  // token was born -- until then the row holds the former occupant's, and the new part alone is the whole window
+  // aggregate (none of the token's rows has expired yet: every column's turn comes once in any R steps).  A token is
+  // a candidate for eviction once it is older than the window that includes the new token: position <= p - R.
+  // (phi, rem) = (j0 / cps, j0 % cps): the phase of column j0 and where in its group of cps columns it sits.
+  auto record4 = [&](int j0, float4 nw_old, float4 sfx_old, int4 pj4, int phi, int rem) {
     float S[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -1005,45 +871,56 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       S[0] += l.x; S[1] += l.y; S[2] += l.z; S[3] += l.w;
     }
     stg16_stream(ringu + (size_t)w * n_pad + j0, make_float4(S[0], S[1], S[2], S[3]));
-    if (j0 < n_snap) {
+    if (j0 < n_used) {
       float nwo[4] = {nw_old.x, nw_old.y, nw_old.z, nw_old.w};
       const float sfo[4] = {sfx_old.x, sfx_old.y, sfx_old.z, sfx_old.w};
       const int pj[4] = {pj4.x, pj4.y, pj4.z, pj4.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = j0 + i;
-        float so = cum ? 0.f : sfo[i];
+        // steps since the column's last turn before this step, and rows recorded since its token was born
+        int d = wm1 - phi;
+        d += d < 0 ? R : 0;
+        const int age = p - 1 - pj[i];
+        float so = (cum || pj[i] < 0 || d > age) ? 0.f : sfo[i];
         if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
         nwo[i] = fuse2(fusion, nwo[i], S[i]);
-        if (j < n_snap) {
-          const float F = fuse2(fusion, so, nwo[i]);
-          if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-          if (sel_step) { Fl[j] = F; Pl[j] = pj[i]; }
-          if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
-        }
+        const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
+        const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
+        if (cand && P.dbgF) P.dbgF[(size_t)u * n_pad + j] = F;
+        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = pj[i]; }
+        if (cand && cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
+        ++rem;
+        if (rem == cps) { rem = 0; ++phi; }
       }
       stg16_stream(nwu + j0, make_float4(nwo[0], nwo[1], nwo[2], nwo[3]));
     }
-    if (Cs + w >= j0 && Cs + w < j0 + 4) {
-      const int i = Cs + w - j0;
-      shf[0] = i == 0 ? S[0] : i == 1 ? S[1] : i == 2 ? S[2] : S[3];
-    }
+  };
+  // phase of this thread's first column, and how it moves from one of its groups of 4 columns to the next
+  int cphi = (4 * tid) / cps, crem = (4 * tid) % cps;
+  const int qstep = (4 * NT) / cps, rstep = (4 * NT) % cps;
+  auto next_phase = [&]() {
+    cphi += qstep;
+    crem += rstep;
+    if (crem >= cps) { crem -= cps; ++cphi; }
   };
 #pragma unroll
   for (int i = 0; i < MAXQ; ++i) {
     const int jq = tid + i * NT;
-    if (jq < nq) record4(4 * jq, pn[i], ps[i], pp[i]);
+    if (jq < nq) record4(4 * jq, pn[i], ps[i], pp[i], cphi, crem);
+    next_phase();
   }
   for (int jq = tid + MAXQ * NT; jq < nq; jq += NT) {
     const int j0 = 4 * jq;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
     int4 pj = make_int4(-1, -1, -1, -1);
-    if (j0 < n_snap) {
+    if (j0 < n_used) {
       a = *(const float4 *)(nwu + j0);
       b = *(const float4 *)(sfxu + (size_t)w * CsP + j0);
       pj = *(const int4 *)(posu + j0);
     }
-    record4(j0, a, b, pj);
+    record4(j0, a, b, pj, cphi, crem);
+    next_phase();
   }
   wave_argmin(bF, bP, bC);
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
@@ -1067,42 +944,31 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 
   // ---- decision (wave 0, before its share of the V pass): needs only the scores
   if (wave == 0) {
-    float fd = 0.f;  // fused score of the token leaving the window
-    for (int a = lane; a < R; a += WAVE) {
-      const float v = a == R - 1 ? shf[0] : colv[a];
-      fd = fuse2(fusion, fd, v);
-    }
-    fd = fusion == 0 ? wave_sum_dpp(fd) : wave_max_dpp(fd);
     float f = INFINITY;
     int bp = -1, bc = -1;
     if (lane < NW) { f = bestF[lane]; bp = bestP[lane]; bc = bestC[lane]; }
     wave_argmin(f, bp, bc);
     if (lane == 0) {
-      colv[R - 1] = shf[0];
-      int dest = -1, evicted = -1, ns = n_snap, multi = 0;
-      if (win_full) {
-        // a selection is due at every T-th generation step, if more than C older tokens
-        // would be held; otherwise the token leaving the window is simply kept
-        const bool due = Tev > 1 ? (sel_step && n_snap + 1 > P.C) : n_snap >= Cs;
-        if (!due) {
-          dest = n_snap;
-          ns = n_snap + 1;
-        } else if (Tev > 1) {
-          multi = 1;  // top-C of up to C+T: done by the whole workgroup after the V pass
-          ns = P.C;
-        } else if (fd <= f) {  // tie: the token leaving the window has the higher position, it goes
-          evicted = p - R;
-        } else {
-          dest = bc;
-          evicted = bp;
+      // tokens older than the window once the new token is in
+      const int older = n_used - n_holes + 1 - (p + 1 < R ? p + 1 : R);
+      int dest = n_used, evicted = -1, nu = n_used + 1, multi = 0, nh = n_holes;
+      if (Tev > 1) {
+        // a selection is due at every T-th generation step, if more than C older tokens would be held; between
+        // selections the new token takes a slot an earlier selection has freed, while there is one
+        if (sel_step && older > P.C) {
+          multi = older - P.C;  // top-C of up to C+T: done by the whole workgroup after the V pass
+          dest = -1; nu = n_used; nh = multi - 1;
+        } else if (n_holes > 0) {
+          dest = hole_top; nu = n_used; nh = n_holes - 1;
         }
-        if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + Cs] = fd;
+      } else if (older > Cs) {
+        dest = bc; evicted = bp; nu = n_used;
       }
       sh[2] = dest;
       sh[3] = evicted;
-      sh[4] = ns;
+      sh[4] = nu;
       sh[5] = multi;
-      shf[9] = fd;
+      sh[6] = nh;
     }
   }
 
@@ -1180,7 +1046,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
       for (int i = 0; i < UNR; ++i) {
         const int j = tile * RPT + i * RPL + rowsub;
-        ok[i] = slot_valid(j, n_snap, Cs, nwin);
+        ok[i] = slot_valid(j, n_used);
         if (ok[i]) r[i] = ((const uint4 *)(Vb + (size_t)j * D))[chunk];
       }
 #pragma unroll
@@ -1214,7 +1080,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   }
   if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
   // full barrier: besides the output partials in LDS, every global store of the record phase has landed
-  // before the compaction below rewrites some of the same addresses (ring[w][dest], nw[dest], sfx[.][dest])
+  // before the commit below rewrites one of the same addresses (nw[dest])
   __syncthreads();
 
   // ---- output
@@ -1232,17 +1098,16 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     P.out[((size_t)uio * G + g) * D + ch] = o;
   }
 
-  // ---- selection among more than C+1 candidates (coarse schedule), compaction, commit: shared with the split kernel
-  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w, cum, fusion, Tev,
-                 sh, shf, Fl, Pl, colw, lists, best2, colv, ringu, sfxu, nwu, posu, knew, vnew};
-  if constexpr (COARSE) coarse_select_and_move<T, D>(tc);
-  compact_and_commit<T, D, CLK>(tc);
+  // ---- selection among more than C+1 candidates (coarse schedule), commit: shared with the split kernel
+  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, Tev, sh, Fl, Pl, best2, nwu, posu, knew, vnew};
+  if constexpr (COARSE) coarse_select<T, D>(tc);
+  commit_step<T, D, CLK>(tc);
 }
 
 // Register budgets.  The compiler version this is built with places spill stores at the top of the block
 // where the lanes of a skipped branch join again, BEFORE it restores their execution mask: a value spilled
 // there is lost for waves that skipped the branch (seen: the fp32 d=64 G=8 build moved only 16 of a key's 256
-// bytes at compaction).  So no build may spill vector registers: the bf16 builds fit 128 registers (1024-thread
+// bytes when it wrote a token into its slot).  So no build may spill vector registers: the bf16 builds fit 128 registers (1024-thread
 // groups); the fp32 builds, which keep G x 4 products per lane in flight, get 256 (groups of at most 512).
 template <typename T, int D, int G, bool CLK, bool COARSE>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(DecodeParams P) {

@@ -1,12 +1,12 @@
 // Decode step of a layer that keeps every token (Appendix A.6, selective layer retention): attention of the new
-// token over everything the unit holds, then the token leaving the window joins the older tokens.  Nothing is
+// token over everything the unit holds, then the token is appended.  Nothing is
 // recorded, fused or selected in such a layer, so no weight has to outlive the tile it was computed for: the
 // softmax runs ONLINE (running maximum and sum per head, the output accumulators rescaled when the maximum
 // moves), a block of 32 slots goes K tiles -> logits -> weights -> V tile -> output without ever being written
 // down, and the cache's length is bounded by nothing but the memory the caller gave.
 //
 // S workgroups of 256 or 512 threads per unit (grid S x units); the waves of a unit's workgroups take the blocks of
-// its resident slots (older tokens [0, n_snap), window [Cs, Cs + nwin)) in turn, each with its own (maximum, sum,
+// its slots in use in turn, each with its own (maximum, sum,
 // output); a workgroup's waves are merged through LDS (Eq.1: softmax over all resident tokens and the token
 // itself).  With S > 1 -- launches of few units, so that every compute unit gets a share -- each workgroup leaves
 // its merged (maximum, sum, output) in the split kernel's workspace with agent-scope stores, counts in, and the
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   float *mW = smem + (size_t)NW * 16 * KEEP_PS + NW * 16;     // [NW][16] maxima
   float *zW = mW + NW * 16;                                   // [NW][16] sums
   float *OW = zW + NW * 16;                                   // [NW][G][D] outputs
-  int *sh = (int *)(OW + (size_t)NW * G * D);                 // [16] 2: dest slot; 3: evicted; 4: new n_snap
+  int *sh = (int *)(OW + (size_t)NW * G * D);                 // [16] 2..6: see StepTail; 7: arrival count
   float *shf = (float *)(sh + 16);                            // [16] 1..8: logits of the token against its own key
   float *msl = shf + 16;                                      // [SPLIT_MAX][8] the workgroups' maxima (S > 1)
   float *zsl = msl + SPLIT_MAX * 8;                           // [SPLIT_MAX][8] ... and sums
@@ -58,27 +58,16 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
   int32_t *posu = P.pos + (size_t)u * n_pad;
 
   const int32_t *meta = P.meta + (size_t)u * META;
-  const int n_snap = meta[0], p = meta[1], w = meta[3];
-  const int nwin = p < R ? p : R;
-  const bool win_full = p >= R;
+  const int n_used = meta[0], p = meta[1], w = meta[3];
 
-  // ---- the blocks of 32 slots that hold resident tokens: older tokens, then what the window adds beyond them
-  const int nb_old = (n_snap + 31) >> 5;
-  int wb0 = Cs >> 5;
-  const int wb1 = nwin > 0 ? (Cs + nwin + 31) >> 5 : wb0;
-  if (wb0 < nb_old) wb0 = nb_old;
-  const int total = nb_old + (wb1 > wb0 ? wb1 - wb0 : 0);
+  // ---- the blocks of 32 slots that hold tokens
+  const int total = (n_used + 31) >> 5;
   const bool zig = P.zig != 0;
-  auto block_of = [&](int i) {
-    const int ii = zig ? total - 1 - i : i;
-    return ii < nb_old ? ii : wb0 + (ii - nb_old);
-  };
+  auto block_of = [&](int i) { return zig ? total - 1 - i : i; };
   // the newest blocks (as many as the handle's share of the memory-side cache holds per unit) are read with ordinary
   // loads and stay there from step to step; the older ones stream past it
-  const int nwb = wb1 > wb0 ? wb1 - wb0 : 0;  // blocks of the window (beyond the older tokens' blocks)
-  const int thr_win = wb1 - P.keep_cached_blocks;
-  const int thr_old = nb_old - (P.keep_cached_blocks > nwb ? P.keep_cached_blocks - nwb : 0);
-  auto streams = [&](int blk) { return blk >= wb0 ? blk < thr_win : blk < thr_old; };
+  const int thr = total - P.keep_cached_blocks;
+  auto streams = [&](int blk) { return blk < thr; };
 
   uint4 ka[2][KB], vb[CB];
   auto load_k = [&](int blk) {
@@ -133,7 +122,7 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int j = blk * 32 + t * 16 + 4 * kq + e;
-        l[4 * t + e] = slot_valid(j, n_snap, Cs, nwin) ? c[e] * P.scale_log2 : -INFINITY;
+        l[4 * t + e] = slot_valid(j, n_used) ? c[e] * P.scale_log2 : -INFINITY;
       }
     }
     // the K registers are free: the next block's K tiles are asked for now
@@ -215,11 +204,12 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
       if (g < G) OW[(size_t)(wave * G + g) * D + cb * 16 + head] = acc[cb][e];
     }
   if (tid == 0) {
-    // every token is kept: the one leaving the window joins the older tokens (the host has made sure there is room)
-    sh[2] = win_full ? n_snap : -1;
+    // every token is kept: the new one is appended (the host has made sure there is room)
+    sh[2] = n_used;
     sh[3] = -1;
-    sh[4] = n_snap + (win_full ? 1 : 0);
+    sh[4] = n_used + 1;
     sh[5] = 0;
+    sh[6] = 0;
   }
   __syncthreads();
 
@@ -266,9 +256,9 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
     // counter; the last workgroup of the unit carries on
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __syncthreads();
-    if (tid == 0) sh[6] = atomicAdd(&P.sp_cnt[u], 1);
+    if (tid == 0) sh[7] = atomicAdd(&P.sp_cnt[u], 1);
     __syncthreads();
-    if (sh[6] != S - 1) return;
+    if (sh[7] != S - 1) return;
     for (int i = tid; i < S * G; i += NT) {
       const int ss = i / G, g = i - ss * G;
       msl[ss * 8 + g] = ws_load1(part, (uint32_t)(ss * PART + g));
@@ -301,11 +291,9 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
       P.out[((size_t)uio * G + g) * D + ch] = o / Z;
     }
   }
-  // every wave has read the window slot's K and V (it still holds the token that leaves the window) before the
-  // tail moves that token and writes the new one there: the barrier above.  The tail: shared with the other kernels
-  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, P.CsP, R, n_pad, P.cps, n_snap, p, w, false, 0, 1,
-                 sh, shf, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, posu, knew, vnew};
-  compact_and_commit<T, D, false>(tc);
+  // the tail: shared with the other kernels
+  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, 1, sh, nullptr, nullptr, nullptr, nullptr, posu, knew, vnew};
+  commit_step<T, D, false>(tc);
 }
 
 }  // namespace mkv

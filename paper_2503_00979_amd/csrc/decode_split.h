@@ -13,7 +13,7 @@
 //   phase B (one workgroup per unit): global maximum M and sum Z from the S pairs (m_s, Z_s) and the token's own
 //     logit; weights p = exp2(l - M) / Z from the logits; out = sum_s O_s exp2(m_s - M) / Z + p_self v_new; then exactly what
 //     the fused kernel does after its softmax: record the group-summed row (Algorithm 1), update the aggregates,
-//     fused scores (Eq.4-6), eviction (Eq.7), compaction.  No weight is held in LDS in this phase, so C + R is
+//     fused scores (Eq.4-6), eviction (Eq.7), the new token into the freed slot.  No weight is held in LDS in this phase, so C + R is
 //     bounded by the workspace only.
 //
 // Nobody waits for anybody: the last arrival is found with one atomic counter per unit, so the grid needs no
@@ -57,13 +57,13 @@ __device__ inline float ws_load1(__amdgpu_buffer_rsrc_t r, uint32_t idx) {
 __host__ __device__ inline int split_part_floats(int G, int D) { return 2 * G + G * D; }
 
 // LDS bytes of decode_split_kernel (bps = blocks of 32 slots per workgroup): the share's logits, and beside them
-// what the end of the step needs (rebuilt aggregates, the leaving token's column, small arrays)
+// what the end of the step needs (rebuilt aggregates, small arrays)
 inline size_t decode_split_lds_bytes(int bps, int G, int D, int R, int cps, int CsP, int T) {
   const size_t cpt = (size_t)turn_cols_padded(cps);
   const size_t lgA = (size_t)G * (bps * 32 + 4), omA = (size_t)SPLIT_NW * G * D;
   const size_t a = (lgA > omA ? lgA : omA) + 2 * SPLIT_NW * 8 + 16;
-  size_t b = (size_t)R * cpt + cpt + R + 3 * 16 + 16 + 16 + 3 * SPLIT_MAX * 8 + 4 * 8;
-  if (T > 1) b += 2 * (size_t)CsP + (size_t)SPLIT_NW * R + 2 * (size_t)T + 2 * 3 * 16;
+  size_t b = (size_t)R * cpt + cpt + 3 * 16 + 16 + 16 + 3 * SPLIT_MAX * 8 + 4 * 8;
+  if (T > 1) b += 2 * (size_t)CsP + 2 * 3 * 16;
   return (a + b) * 4;
 }
 
@@ -103,8 +103,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   int *shi = (int *)(redB + NW * 8);         // [16]
   float *stage = (float *)(shi + 16);        // [R][cpt] rebuilt aggregates on their way to the sfx rows
   float *turn = stage + (size_t)R * cpt;     // [cpt]
-  float *colv = turn + cpt;                  // [R] column of the token leaving the window, oldest row first
-  float *bestF = colv + R;                   // [16]
+  float *bestF = turn + cpt;                 // [16]
   int *bestC = (int *)(bestF + 16);          // [16]
   int *bestP = bestC + 16;                   // [16]
   int *sh = bestP + 16;                      // [16]
@@ -118,9 +117,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   float *Mgl = sfl + 8;                      // [8] global maximum per head
   float *Fl = Mgl + 8;                                    // [CsP]   (T > 1 only, as the ones below)
   int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP]
-  float *colw = (float *)(Pl + (Tev > 1 ? CsP : 0));      // [NW][R]
-  int *lists = (int *)(colw + (Tev > 1 ? NW * R : 0));    // [2][Tev]
-  float *best2 = (float *)(lists + 2 * Tev);              // [2][3][16]
+  float *best2 = (float *)(Pl + (Tev > 1 ? CsP : 0));     // [2][3][16]
 
   // ================= phase A: this workgroup's share =================
   // A wave takes the blocks wave, wave + NW, .. of the share, NB of them in flight at a time (K tile pair and V tile
@@ -159,34 +156,24 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     qfr[kb] = __builtin_bit_cast(bf16x8_t, r);
   }
   const int32_t *meta = P.meta + (size_t)u * META;
-  const int n_snap = meta[0], p = meta[1], w = meta[3];
+  const int n_used = meta[0], p = meta[1], w = meta[3];
   const int gen_step = p - meta[4] + 1;
   const bool sel_step = P.T > 1 && gen_step % P.T == 0;
-  const int nwin = p < R ? p : R;
+  const int n_holes = P.T > 1 ? meta[5] : 0;  // free slots below n_used (coarse schedule)
   const int wm1 = w == 0 ? R - 1 : w - 1;
-  const bool win_full = p >= R;
   const int turn0 = wm1 * cps;
-  int turn_n = n_snap - turn0;
+  int turn_n = n_used - turn0;
   turn_n = turn_n < 0 || cum ? 0 : (turn_n > cps ? cps : turn_n);
   float *ringu = P.ring + (size_t)u * R * n_pad;
   float *sfxu = P.sfx + (size_t)u * R * CsP;
   float *nwu = P.nw + (size_t)u * CsP;
   int32_t *posu = P.pos + (size_t)u * n_pad;
 
-  // Whichever workgroup ends up merging needs the column of the token leaving the window and the rebuilt
-  // aggregates of this step's turn columns.  Nobody knows yet who that is, and both are chains of small
-  // gathers: every workgroup fetches them now, under its K/V loads (a few KB per workgroup, from L2 after the
-  // first), instead of the merging one alone after everybody else is done.
-  constexpr int CVB = 4;  // R - 1 <= 1023 values over 256 threads
-  float cvr[CVB];
-#pragma unroll
-  for (int k = 0; k < CVB; ++k) {
-    const int a = tid + k * NT;  // row of step p-R+1+a lives in ring row (w+1+a) mod R
-    int r = w + 1 + a;
-    r -= r >= R ? R : 0;
-    cvr[k] = 0.f;
-    if (a < R - 1 && win_full && !keep) cvr[k] = ringu[(unsigned)(r * n_pad + Cs + w)];
-  }
+  // Whichever workgroup ends up merging needs the rebuilt aggregates of this step's turn columns.  Nobody knows yet
+  // who that is, and the rebuild is a chain of small gathers: every workgroup does it now, under its K/V loads (a
+  // few KB per workgroup, from L2 after the first), instead of the merging one alone after everybody else is done.
+  int hole_top = -1;
+  if (n_holes > 0) hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
   // the rebuild's loads (one batch: a lane's whole chunk of rows) go out now, are consumed after the K loop
   TurnRebuildT<SPLIT_RB> tr;
   float rbv[SPLIT_RB];
@@ -195,7 +182,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   nrw = nrw > NW / 2 ? NW / 2 : nrw;
   const bool rebuilds = wave >= NW - nrw && !keep;
   if (rebuilds) {
-    tr.init(lane, p, wm1, cum ? 0 : n_snap, R, n_pad, cps, cpt, fusion, ringu, NW - 1 - wave, nrw, tgw);
+    tr.init(lane, p, wm1, cum ? 0 : n_used, R, n_pad, cps, cpt, fusion, ringu, posu, NW - 1 - wave, nrw, tgw);
     tr.begin(rbv);
   }
   // ---- logits of the share
@@ -218,7 +205,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
               const int j = blk * 32 + t * 16 + 4 * kq + x;
-              l4[x] = slot_valid(j, n_snap, Cs, nwin) ? acc[x] * P.scale_log2 : -INFINITY;
+              l4[x] = slot_valid(j, n_used) ? acc[x] * P.scale_log2 : -INFINITY;
             }
             const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
 #pragma unroll
@@ -235,11 +222,6 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   for (int g = 0; g < G; ++g) {
     const float v = wave_max_dpp(mx[g]);
     if (lane == 0) redA[wave * 8 + g] = v;
-  }
-#pragma unroll
-  for (int k = 0; k < CVB; ++k) {
-    const int a = tid + k * NT;
-    if (a < R - 1) colv[a] = cvr[k];
   }
   lds_barrier();
   // ---- local maximum, exponentials, local sum; the logits themselves go to the workspace: the merging workgroup
@@ -258,10 +240,15 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
     for (int jq = tid; jq < nsl / 4; jq += NT) {
+      // coarse schedule: slots a selection has freed and no token has taken yet still hold their old key: no weight
+      int4 hp = make_int4(0, 0, 0, 0);
+      if (n_holes > 0) hp = *(const int4 *)(posu + j0s + 4 * jq);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
+        l.x = hp.x < 0 ? -INFINITY : l.x; l.y = hp.y < 0 ? -INFINITY : l.y;
+        l.z = hp.z < 0 ? -INFINITY : l.z; l.w = hp.w < 0 ? -INFINITY : l.w;
         if (!keep) ws_store4(wts, (uint32_t)(g * n_pad + j0s + 4 * jq), l);
         l.x = exp2_native(l.x - mref[g]); l.y = exp2_native(l.y - mref[g]); l.z = exp2_native(l.z - mref[g]); l.w = exp2_native(l.w - mref[g]);
         *pl = l;
@@ -355,14 +342,13 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   if (tid < nq && !keep) {
 #pragma unroll
     for (int g = 0; g < G; ++g) lq[g] = ws_load4(wts, (uint32_t)(g * n_pad + 4 * tid));
-    if (4 * tid < n_snap) {
+    if (4 * tid < n_used) {
       nw0 = *(const float4 *)(nwu + 4 * tid);
       sf0 = *(const float4 *)(sfxu + (size_t)w * CsP + 4 * tid);
       pp0 = *(const int4 *)(posu + 4 * tid);
     }
   }
-  // partial outputs of the first SH workgroups, for the OPT output elements this thread owns; and this thread's piece
-  // of the window slot's K/V row, which the compaction at the end may have to move
+  // partial outputs of the first SH workgroups, for the OPT output elements this thread owns
   constexpr int SH = 8, OPT = (G * D + NT - 1) / NT;
   float ob[OPT][SH];
 #pragma unroll
@@ -372,13 +358,6 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
       const int idx = tid + x * NT;
       ob[x][ss] = (ss < S && idx < G * D) ? ws_load1(part, (uint32_t)(ss * PART + 2 * G + idx)) : 0.f;
     }
-  uint4 kpre = {0u, 0u, 0u, 0u};
-  uint16_t vpre = 0;
-  {
-    const int wslot = Cs + w;
-    if (tid < D / 8) kpre = *(const uint4 *)(Kb + L::k_off(wslot, tid * 8));
-    if (NT - 1 - tid < D) vpre = ((const uint16_t *)Vb)[L::v_off(wslot, NT - 1 - tid)];
-  }
   for (int i = tid; i < S * G; i += NT) {
     const int ss = i / G, g = i - ss * G;
     msl[ss * 8 + g] = ws_load1(part, (uint32_t)(ss * PART + g));
@@ -434,7 +413,8 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   // ---- record the row, update per-column aggregates, fused scores, local argmin (as the fused kernel does)
   float bF = INFINITY;
   int bP = -1, bC = -1;
-  auto record4 = [&](int j0, const float4 (&l4)[G], float4 nw_old, float4 sfx_old, int4 pj4) {
+  // (the same rules as in the fused kernel: see record4 in decode.h)
+  auto record4 = [&](int j0, const float4 (&l4)[G], float4 nw_old, float4 sfx_old, int4 pj4, int phi, int rem) {
     float S4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -443,30 +423,32 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
       S4[2] += exp2_native(l4[g].z - Mg) * ig; S4[3] += exp2_native(l4[g].w - Mg) * ig;
     }
     stg16_stream(ringu + (size_t)w * n_pad + j0, make_float4(S4[0], S4[1], S4[2], S4[3]));
-    if (j0 < n_snap) {
+    if (j0 < n_used) {
       float nwo[4] = {nw_old.x, nw_old.y, nw_old.z, nw_old.w};
       const float sfo[4] = {sfx_old.x, sfx_old.y, sfx_old.z, sfx_old.w};
       const int pj[4] = {pj4.x, pj4.y, pj4.z, pj4.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = j0 + i;
-        float so = cum ? 0.f : sfo[i];
+        int d = wm1 - phi;
+        d += d < 0 ? R : 0;
+        const int age = p - 1 - pj[i];
+        float so = (cum || pj[i] < 0 || d > age) ? 0.f : sfo[i];
         if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
         nwo[i] = fuse2(fusion, nwo[i], S4[i]);
-        if (j < n_snap) {
-          const float F = fuse2(fusion, so, nwo[i]);
-          if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + j] = F;
-          if (sel_step) { Fl[j] = F; Pl[j] = pj[i]; }
-          if (cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
-        }
+        const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
+        const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
+        if (cand && P.dbgF) P.dbgF[(size_t)u * n_pad + j] = F;
+        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = pj[i]; }
+        if (cand && cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
+        ++rem;
+        if (rem == cps) { rem = 0; ++phi; }
       }
       stg16_stream(nwu + j0, make_float4(nwo[0], nwo[1], nwo[2], nwo[3]));
     }
-    if (Cs + w >= j0 && Cs + w < j0 + 4) {
-      const int i = Cs + w - j0;
-      shf[0] = i == 0 ? S4[0] : i == 1 ? S4[1] : i == 2 ? S4[2] : S4[3];
-    }
   };
+  int cphi = (4 * tid) / cps, crem = (4 * tid) % cps;
+  const int qstep = (4 * NT) / cps, rstep = (4 * NT) % cps;
   for (int jq = tid; jq < nq && !keep; jq += NT) {
     // the next group's loads go out before this group's arithmetic
     const int jn = jq + NT;
@@ -475,13 +457,16 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     if (jn < nq) {
 #pragma unroll
       for (int g = 0; g < G; ++g) ln[g] = ws_load4(wts, (uint32_t)(g * n_pad + 4 * jn));
-      if (4 * jn < n_snap) {
+      if (4 * jn < n_used) {
         an = *(const float4 *)(nwu + 4 * jn);
         bn = *(const float4 *)(sfxu + (size_t)w * CsP + 4 * jn);
         pn = *(const int4 *)(posu + 4 * jn);
       }
     }
-    record4(4 * jq, lq, nw0, sf0, pp0);
+    record4(4 * jq, lq, nw0, sf0, pp0, cphi, crem);
+    cphi += qstep;
+    crem += rstep;
+    if (crem >= cps) { crem -= cps; ++cphi; }
 #pragma unroll
     for (int g = 0; g < G; ++g) lq[g] = ln[g];
     nw0 = an; sf0 = bn; pp0 = pn;
@@ -506,60 +491,48 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
 
   // ---- decision (wave 0)
   if (keep) {
-    // every token is kept: the one leaving the window joins the older tokens (the host has made sure there is room)
+    // every token is kept: the new one is appended (the host has made sure there is room)
     if (tid == 0) {
-      sh[2] = win_full ? n_snap : -1;
+      sh[2] = n_used;
       sh[3] = -1;
-      sh[4] = n_snap + (win_full ? 1 : 0);
+      sh[4] = n_used + 1;
       sh[5] = 0;
+      sh[6] = 0;
     }
   } else if (wave == 0) {
-    float fd = 0.f;
-    for (int a = lane; a < R; a += WAVE) {
-      const float v = a == R - 1 ? shf[0] : colv[a];
-      fd = fuse2(fusion, fd, v);
-    }
-    fd = fusion == 0 ? wave_sum_dpp(fd) : wave_max_dpp(fd);
     float f = INFINITY;
     int bp = -1, bc = -1;
     if (lane < NW) { f = bestF[lane]; bp = bestP[lane]; bc = bestC[lane]; }
     wave_argmin(f, bp, bc);
     if (lane == 0) {
-      colv[R - 1] = shf[0];
-      int dest = -1, evicted = -1, ns = n_snap, multi = 0;
-      if (win_full) {
-        const bool due = Tev > 1 ? (sel_step && n_snap + 1 > P.C) : n_snap >= Cs;
-        if (!due) {
-          dest = n_snap;
-          ns = n_snap + 1;
-        } else if (Tev > 1) {
-          multi = 1;
-          ns = P.C;
-        } else if (fd <= f) {  // tie: the token leaving the window has the higher position, it goes
-          evicted = p - R;
-        } else {
-          dest = bc;
-          evicted = bp;
+      const int older = n_used - n_holes + 1 - (p + 1 < R ? p + 1 : R);
+      int dest = n_used, evicted = -1, nu = n_used + 1, multi = 0, nh = n_holes;
+      if (Tev > 1) {
+        if (sel_step && older > P.C) {
+          multi = older - P.C;
+          dest = -1; nu = n_used; nh = multi - 1;
+        } else if (n_holes > 0) {
+          dest = hole_top; nu = n_used; nh = n_holes - 1;
         }
-        if (P.dbgF) P.dbgF[(size_t)u * (Cs + 1) + Cs] = fd;
+      } else if (older > Cs) {
+        dest = bc; evicted = bp; nu = n_used;
       }
       sh[2] = dest;
       sh[3] = evicted;
-      sh[4] = ns;
+      sh[4] = nu;
       sh[5] = multi;
-      shf[9] = fd;
+      sh[6] = nh;
     }
   }
 
   // full barrier: the decision is visible, and every global store of the record phase has landed before the
-  // compaction below rewrites some of the same addresses
+  // commit below rewrites one of the same addresses
   __syncthreads();
   if (tid == 0) P.sp_cnt[u] = 0;  // for the unit's next step
 
-  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, Cs, CsP, R, n_pad, cps, n_snap, p, w, cum, fusion, Tev,
-                 sh, shf, Fl, Pl, colw, lists, best2, colv, ringu, sfxu, nwu, posu, knew, vnew};
-  coarse_select_and_move<T, D>(tc);
-  compact_and_commit<T, D, false, true>(tc, kpre, vpre);
+  StepTail<T> tc{P, u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, Tev, sh, Fl, Pl, best2, nwu, posu, knew, vnew};
+  coarse_select<T, D>(tc);
+  commit_step<T, D, false>(tc);
 }
 
 }  // namespace mkv

@@ -39,12 +39,17 @@ __global__ __launch_bounds__(1024) void calib_read_kernel(uint32_t *sink, const 
 }
 
 // ---- exports
-// out rows are `row` long: the unit's n slots, then -1
+// out rows are `row` long: the unit's n slots (in the cache's own order, -1 = free), then -1; out_nsnap = how many of
+// the tokens are older than the window of the R most recent
 __global__ void export_positions_kernel(const int32_t *pos, const int32_t *meta, int32_t *out_pos,
-                                        int32_t *out_nsnap, int n, int n_pad, int row) {
+                                        int32_t *out_nsnap, int n, int n_pad, int row, int R) {
   const int u = blockIdx.y, i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < row) out_pos[(size_t)u * row + i] = i < n ? pos[(size_t)u * n_pad + i] : -1;
-  if (i == 0 && out_nsnap) out_nsnap[u] = meta[(size_t)u * META];
+  if (i == 0 && out_nsnap) {
+    const int32_t *m = meta + (size_t)u * META;
+    const int tokens = m[0] - m[5], p = m[1];
+    out_nsnap[u] = tokens - (p < R ? p : R);
+  }
 }
 __global__ void fill_i32_kernel(int32_t *dst, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

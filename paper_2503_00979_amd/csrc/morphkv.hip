@@ -88,7 +88,7 @@ int upload_ints(int32_t *dst, const int32_t *src, int n, hipStream_t st) {
 struct BufLayout {
   int U, G, Cs, CsP, n, n_pad, cps, cpt, esz;
   // cache
-  size_t offK, offV, offPos, offMeta, offEvl, cache_bytes;
+  size_t offK, offV, offPos, offMeta, offEvl, offHoles, cache_bytes;
   // scores_ring
   size_t offRing, offSfx, offNw, offSpW, offSpPart, offSpCnt, ring_bytes;
   int sp_smax;     // most workgroups a unit is ever split over (1: the split kernel is never used, no workspace)
@@ -210,18 +210,18 @@ BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
   L.Cs = c->C + (c->evict_every >= 1 ? c->evict_every - 1 : c->max_new_tokens);
   L.n = L.Cs + c->R;
   L.n_pad = (L.n + 31) / 32 * 32;  // K/V slot arrays are padded to whole tiles
-  L.CsP = (L.Cs + 31) / 32 * 32;   // row stride of the per-column state
+  L.CsP = L.n_pad;                 // row stride of the per-column state: every slot is a column
   // Columns rebuilt per step: at least ceil(Cs/R), so that every column's turn comes once in R steps.  The
   // rebuilt aggregates go out as one run of cps floats per sfx row: runs that are whole 128-byte lines (else
   // 64, 32 .. bytes) keep partial-line writes away from HBM, which cost several us per step on c3-sized
   // caches when the run was 17 floats.  Rounded up as far as the LDS staging area (R x cps floats) allows.
-  const int cps0 = keep_all ? 1 : (L.Cs + c->R - 1) / c->R;  // (a layer that keeps every token rebuilds nothing)
+  const int cps0 = keep_all ? 1 : (L.n + c->R - 1) / c->R;  // (a layer that keeps every token rebuilds nothing)
   L.cps = cps0;
   for (int a = keep_all ? 1 : 32; a > 1; a >>= 1) {
     const int cand = (cps0 + a - 1) / a * a;
     const size_t stage = (size_t)c->R * turn_cols_padded(cand) * 4;
     if (stage <= 32 * 1024 &&
-        decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, cand, (L.Cs + 31) / 32 * 32, c->evict_every) <= 160 * 1024) {
+        decode_lds_bytes(L.n_pad, L.G, c->head_dim, 1024, c->R, cand, L.n_pad, c->evict_every) <= 160 * 1024) {
       L.cps = cand;
       break;
     }
@@ -236,6 +236,7 @@ BufLayout make_layout(const morphkv_config *c, bool keep_all = false) {
   L.offPos = o; o = align_up(o + U * np * 4);
   L.offMeta = o; o = align_up(o + U * META * 4);
   L.offEvl = o; o = align_up(o + U * (size_t)(c->evict_every > 0 ? c->evict_every : 1) * 4);
+  L.offHoles = o; o = align_up(o + U * (size_t)(c->evict_every > 0 ? c->evict_every : 1) * 4);
   L.cache_bytes = o;
   o = 0;
   L.offRing = o; o = align_up(o + (keep_all ? 0 : U * R * np * 4));
@@ -319,6 +320,7 @@ DecodeParams decode_params(const morphkv_handle *h) {
   // selection at the prompt only: the kernel runs its every-step schedule on a cache that never fills up
   P.C = h->cfg.C; P.T = h->cfg.evict_every > 0 ? h->cfg.evict_every : 1;
   P.evl = (int32_t *)(h->cache + L.offEvl);
+  P.holes = (int32_t *)(h->cache + L.offHoles);
   P.zig = (int32_t)(h->steps & 1u);
   P.nt_k = h->nt_k;
   P.nt_v = h->nt_v;
@@ -368,15 +370,9 @@ PrefillParams prefill_params(const morphkv_handle *h, char *scratch_base, const 
 // threads per workgroup of the fused decode kernel: enough workgroups to cover the CUs several times
 // over -> small groups (several co-resident per CU); about one unit per CU -> one large group.
 int decode_threads(const morphkv_handle *h, int U) {
-  if (h->force_threads) {
-    // a thread keeps at most 4 of the R-1 rows of the leaving token's column: the override is raised until they fit
-    int nt = h->force_threads;
-    while (4 * nt < h->cfg.R - 1 && nt < 1024) nt += 64;
-    return nt;
-  }
+  if (h->force_threads) return h->force_threads;
   const int cu = h->n_cu > 0 ? h->n_cu : 256;
-  // (a thread keeps at most 4 of the R-1 rows of the leaving token's column: groups of 128 need R <= 512)
-  if (U >= 8 * cu && h->cfg.R <= 512) return 128;
+  if (U >= 8 * cu) return 128;
   if (U >= 4 * cu) return 256;
   if (U >= 2 * cu) return 512;
   // few units: the launch is a chain of latencies and of instructions that every wave issues (the four waves of a
@@ -389,7 +385,6 @@ int decode_threads(const morphkv_handle *h, int U) {
   const int rounds = (groups + 15) / 16;
   int nw = 4;
   while ((groups + nw - 1) / nw > rounds) ++nw;
-  while (4 * 64 * nw < h->cfg.R - 1 && nw < 16) ++nw;  // (the leaving token's column: at most 4 rows a thread)
   return 64 * nw;
 }
 
@@ -889,7 +884,7 @@ int morphkv_export_positions(morphkv_handle *h, int32_t *pos, int32_t *n_snap, v
     const BufLayout &L = g->L;
     hipLaunchKernelGGL(export_positions_kernel, dim3((row + 255) / 256, L.U), dim3(256), 0, (hipStream_t)stream,
                        (const int32_t *)(g->cache + L.offPos), (const int32_t *)(g->cache + L.offMeta), pos, n_snap,
-                       L.n, L.n_pad, row);
+                       L.n, L.n_pad, row, g->cfg.R);
     HIP_TRY(hipGetLastError());
     pos += (size_t)L.U * row;
     if (n_snap) n_snap += L.U;
@@ -933,7 +928,7 @@ int morphkv_export_evicted_list(morphkv_handle *h, int32_t *evicted, void *strea
 int morphkv_capture_scores(morphkv_handle *h, float *F) {
   if (!h) return fail(MORPHKV_EINVAL, "handle is null");
   // rows of layers that keep every token are left untouched (they never score anything)
-  h->dbgF = (F && h->keep) ? F + (size_t)h->keep->L.U * (h->L.Cs + 1) : F;
+  h->dbgF = (F && h->keep) ? F + (size_t)h->keep->L.U * h->L.n_pad : F;
   return MORPHKV_OK;
 }
 

@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256, 2) void prefill_pass_kernel(PrefillParams P) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float e = __builtin_amdgcn_exp2f(fmaf(acc[t][i], scale, -st.x));  // st.x = +inf: no such query, weight 0
-          if constexpr (MODE == PF_RING) e = (kpp[i] >= 0 && kpp[i] <= pj) ? e : 0.f;
+          if constexpr (MODE == PF_RING) e = (kpp[i] >= 0 && kpp[i] < pj) ? e : 0.f;  // rows after the token's own
           S[t][i] += e;
         }
       }
@@ -514,12 +514,17 @@ __global__ __launch_bounds__(64) void prefill_stats_from_lse_kernel(PrefillParam
   P.Sfin[((size_t)u * G + g) * R16 + j] = st;
 }
 
-// source prompt position of cache slot `slot` of a unit after prefill, -1 if empty
-__device__ inline int prefill_slot_source(const PrefillParams &P, int u, int slot, int N, int n_snap) {
-  if (slot < P.Cs) return slot < n_snap ? P.sel[(size_t)u * P.Cs + slot] : -1;
-  const int x = slot - P.Cs, R = P.R;
-  if (N >= R) return N - R + pmod(x - (N - R), R);
-  return x < N ? x : -1;
+// source prompt position of cache slot `slot` of a unit after prefill, -1 if empty: the n_old retained older tokens
+// first (ascending positions), the window's tokens after them (ascending), no gaps.  (A token never changes its
+// slot afterwards: the decode step writes a new token into the slot its eviction has freed.)
+__device__ inline int prefill_n_old(const PrefillParams &P, int N) {
+  const int o = N - (N < P.R ? N : P.R);
+  return o < P.C ? o : P.C;
+}
+__device__ inline int prefill_slot_source(const PrefillParams &P, int u, int slot, int N, int n_old) {
+  if (slot < n_old) return P.sel[(size_t)u * P.Cs + slot];
+  const int x = slot - n_old, Rw = N < P.R ? N : P.R;
+  return x < Rw ? N - Rw + x : -1;
 }
 
 // ---- P4a: gather K/V rows and positions into the cache slots (layout of the element type);
@@ -533,7 +538,7 @@ __global__ __launch_bounds__(256) void prefill_gather_kernel(PrefillParams P) {
   const int slot = blockIdx.x * SPB + tid / (2 * LPR), which = (tid / LPR) & 1, ck = tid % LPR;
   if (slot >= P.n_pad) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b];
-  const int n_snap = P.meta[(size_t)u * META];
+  const int n_snap = prefill_n_old(P, N);
   const int src = slot < P.n ? prefill_slot_source(P, u, slot, N, n_snap) : -1;
   if (which == 0 && ck == 0) P.pos[(size_t)u * P.n_pad + slot] = src;
   uint4 r = {0u, 0u, 0u, 0u};
@@ -565,7 +570,7 @@ __global__ __launch_bounds__(256) void prefill_gather_tiled_kernel(PrefillParams
   __shared__ int srcs[32];
   const int u = blockIdx.y, tid = threadIdx.x, slot0 = blockIdx.x * 32;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b];
-  const int n_snap = P.meta[(size_t)u * META];
+  const int n_snap = prefill_n_old(P, N);
   if (tid < 32) {
     const int slot = slot0 + tid;
     const int src = slot < P.n ? prefill_slot_source(P, u, slot, N, n_snap) : -1;

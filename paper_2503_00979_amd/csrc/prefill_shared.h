@@ -33,7 +33,7 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(PrefillParams P) {
   const int keep = n_old < P.C ? n_old : P.C;
   if (tid == 0) {
     int32_t *m = P.meta + (size_t)u * META;
-    m[0] = keep; m[1] = N; m[2] = -1; m[3] = N % R; m[4] = N;
+    m[0] = keep + Rw; m[1] = N; m[2] = -1; m[3] = N % R; m[4] = N; m[5] = 0;  // slots in use, next position, .., free slots
   }
   if (tid < P.T) P.evl[(size_t)u * P.T + tid] = -1;
   if (tid == 0 && P.sp_cnt) P.sp_cnt[u] = 0;
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
   const int u = blockIdx.y, col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= P.n_pad) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R, Rw = N < R ? N : R;
-  const int n_snap = P.meta[(size_t)u * META];
+  const int n_snap = prefill_n_old(P, N);
   const int src = col < P.n ? prefill_slot_source(P, u, col, N, n_snap) : -1;
   const float *Sr = P.Srow + (size_t)u * R * P.Nmax;
   float *ringu = P.ring + (size_t)u * R * P.n_pad;
@@ -116,22 +116,22 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(PrefillParams P) {
     float v = 0.f;
     if (j >= 0 && src >= 0) {
       const int pj = N - Rw + j;
-      if (src <= pj) v = Sr[(size_t)j * P.Nmax + src];
+      if (src < pj) v = Sr[(size_t)j * P.Nmax + src];  // rows after the token's own
     }
     ringu[(size_t)r * P.n_pad + col] = v;
   }
 }
 
-// ---- P5: aggregate state of every older-token column, as of the end of step N-1
+// ---- P5: aggregate state of every slot's column, as of the end of step N-1
 __global__ __launch_bounds__(256) void prefill_state_kernel(PrefillParams P) {
   const int u = blockIdx.y, c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= P.CsP) return;
   const int b = (u / P.Mkv) % P.B, N = P.plen[b], R = P.R;
-  const int n_snap = P.meta[(size_t)u * META];
+  const int n_snap = prefill_n_old(P, N);
   const float *ringu = P.ring + (size_t)u * R * P.n_pad;
   float *sfxu = P.sfx + (size_t)u * R * P.CsP;
   float nwv = 0.f;
-  if (c < n_snap) {
+  if (c < n_snap + (N < R ? N : R)) {  // every slot in use is a column (rows up to a token's own are zero in the recorded rows)
     const int p_end = N - 1;
     const int p0 = P.fusion == 2 ? p_end - R : last_rebuild_before(p_end, c / P.cps, R);  // running sum: no old part
     nwv = column_scan(

@@ -51,26 +51,24 @@ def _unit_map(wl, batch_index):
 
 
 def _gpu_sets(gpu, wl, umap):
+    """Per unit: the sorted positions of the older tokens and of the window's, from the exported slot positions.  A
+    token is in the window if it is among the R most recent positions of its sequence; slots are in no particular
+    order and -1 where free."""
     pos, n_snap = gpu.export_positions()
     pos = pos.cpu().numpy()[umap]
     n_snap = n_snap.cpu().numpy()[umap]
-    # older-token slots: more than C are held between coarse selections, or for good when selection is at the prompt only;
-    # a layer that keeps every token has max_prompt_len + max_new_tokens of them (its row: those, the window, then -1)
-    C_sel = wl.C + (wl.evict_every - 1 if wl.evict_every >= 1 else wl.max_new_tokens)
-    C_keep = wl.Nmax + wl.max_new_tokens
-    upl = wl.batch * wl.n_kv_heads
     snaps, wins = [], []
     for i in range(len(umap)):
-        C = C_keep if umap[i] // upl < wl.n_keep_all_layers else C_sel
-        assert np.all(pos[i, C + wl.R:] == -1)
-        s = pos[i, :C]
-        assert np.all(s[n_snap[i]:] == -1), "unused older-token slots must be empty"
-        assert np.all(s[:n_snap[i]] >= 0)
-        snaps.append(np.sort(s[:n_snap[i]]))
-        wv = pos[i, C:C + wl.R]
-        for x, pv in enumerate(wv):
-            assert pv == -1 or pv % wl.R == x, "window slot must be position mod R"
-        wins.append(np.sort(wv[wv >= 0]))
+        held = pos[i][pos[i] >= 0]
+        assert len(np.unique(held)) == len(held), "a position is held twice"
+        held = np.sort(held)
+        last = held[-1]
+        w = held[held > last - wl.R]
+        assert len(w) == min(wl.R, last + 1) and w[0] == last - len(w) + 1, "the window must hold the R most recent positions"
+        s = held[held <= last - wl.R]
+        assert len(s) == n_snap[i], "exported count of older tokens"
+        snaps.append(s)
+        wins.append(w)
     return snaps, wins, pos
 
 
@@ -223,19 +221,15 @@ class LockStep:
                 rep.near_ties_decode += 1
             decided[i] = e_gpu
             if Fg_all is not None:
-                # captured GPU scores are in slot order ([C] = the token leaving the window): look each slot's
-                # position up among the oracle's candidates
+                # captured GPU scores are in slot order: look each candidate slot's position up among the oracle's
                 Fg = Fg_all[self.umap[i]]
+                pb = pos_before[i]
+                slots = np.nonzero((pb >= 0) & (pb <= cp.max()))[0]
+                assert np.array_equal(np.sort(pb[slots]), np.sort(cp)), "candidates differ"
                 order = np.argsort(cp)
-                slots = pos_before[i, :wl.C]
-                at = order[np.searchsorted(cp[order], slots)]
-                assert np.array_equal(cp[at], slots)
-                rel = np.abs(Fg[:wl.C] - cF[at]) / np.maximum(np.abs(cF[at]), 1e-30)
-                dem = np.setdiff1d(cp, slots)
-                assert len(dem) == 1
-                Fd = cF[np.nonzero(cp == dem[0])[0][0]]
-                rel_d = abs(Fg[wl.C] - Fd) / max(abs(Fd), 1e-30)
-                rep.max_score_rel_err = max(rep.max_score_rel_err, float(rel.max()), float(rel_d))
+                at = order[np.searchsorted(cp[order], pb[slots])]
+                rel = np.abs(Fg[slots] - cF[at]) / np.maximum(np.abs(cF[at]), 1e-30)
+                rep.max_score_rel_err = max(rep.max_score_rel_err, float(rel.max()))
         self.oracle.decode_commit(decided)
         self.t += 1
         rep.steps += 1

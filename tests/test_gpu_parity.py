@@ -221,6 +221,17 @@ def test_rebuild_shapes(case, waves, threads, oracle_lib, monkeypatch):
     assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
 
 
+def test_small_workgroups_with_a_long_window(oracle_lib, monkeypatch):
+    """Workgroups of 128 threads (what launches of very many units get) with a window of more rows than four per
+    thread, over a full rotation of the window."""
+    monkeypatch.setenv("MORPHKV_DECODE_THREADS", "128")
+    wl = inputs.small_workload(16100, L=1, B=1, M=4, Mkv=1, d=128, dtype="bf16", C=500, R=600, fusion="sum",
+                               prompt_lens=(1500,), steps=610)
+    rep = _lockstep(wl, DEV, capture_scores=True).prefill().run(wl.steps, check_every=8)
+    _report("small_groups_long_window", rep)
+    assert rep.evictions > 0 and rep.max_score_rel_err <= 1e-5
+
+
 def test_split_kernel_per_layer_calls_at_c4_size(oracle_lib, monkeypatch):
     """c4 called layer by layer, as a model calls it: 64 units a launch, here spread over 4 workgroups a unit; the
     oracle follows one sequence through all 32 layers."""
