@@ -423,8 +423,8 @@ __device__ __forceinline__ void coarse_select(const StepTail<T> &c) {
   }
 }
 
-// The new token takes its slot: K, V, position, an empty new-part aggregate (the slot's old part is ignored until
-// the column's next turn, see record4); the unit's counters move on.
+// The new token takes its slot: K, V, position (the slot's aggregates are the former occupant's: record4 ignores
+// the new part at the next step and the old part until the column's next turn); the unit's counters move on.
 template <typename T, int D, bool CLK>
 __device__ __forceinline__ void commit_step(const StepTail<T> &c) {
   const DecodeParams &P = c.P;
@@ -447,7 +447,6 @@ __device__ __forceinline__ void commit_step(const StepTail<T> &c) {
   }
   if (tid == 0) {
     c.posu[dest] = p;
-    if (!P.keep_all) c.nwu[dest] = 0.f;
     int32_t *m = P.meta + (size_t)u * META;
     m[0] = sh[4];
     m[1] = p + 1;
@@ -884,6 +883,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
         const int age = p - 1 - pj[i];
         float so = (cum || pj[i] < 0 || d > age) ? 0.f : sfo[i];
         if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
+        if (pj[i] == p - 1) nwo[i] = 0.f;  // born at the last step: what is stored is the former occupant's
         nwo[i] = fuse2(fusion, nwo[i], S[i]);
         const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
         const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
@@ -1079,9 +1079,9 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     }
   }
   if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 3] = wall_clock64();
-  // full barrier: besides the output partials in LDS, every global store of the record phase has landed
-  // before the commit below rewrites one of the same addresses (nw[dest])
-  __syncthreads();
+  // the output partials are in LDS; every wave is done with K and V (the commit below writes into them).  Nothing
+  // the commit stores is an address the record phase has stored to: no wait for those stores
+  lds_barrier();
 
   // ---- output
   for (int idx = tid; idx < G * D; idx += NT) {

@@ -435,6 +435,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
         const int age = p - 1 - pj[i];
         float so = (cum || pj[i] < 0 || d > age) ? 0.f : sfo[i];
         if (j >= turn0 && j < turn0 + turn_n) { nwo[i] = 0.f; so = turn[j - turn0]; }
+        if (pj[i] == p - 1) nwo[i] = 0.f;  // born at the last step: what is stored is the former occupant's
         nwo[i] = fuse2(fusion, nwo[i], S4[i]);
         const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
         const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
@@ -525,9 +526,8 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
     }
   }
 
-  // full barrier: the decision is visible, and every global store of the record phase has landed before the
-  // commit below rewrites one of the same addresses
-  __syncthreads();
+  // the decision is visible (nothing the commit below stores is an address the record phase has stored to)
+  lds_barrier();
   if (tid == 0) P.sp_cnt[u] = 0;  // for the unit's next step
 
   StepTail<T> tc{P, u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, Tev, sh, Fl, Pl, best2, nwu, posu, knew, vnew};
