@@ -110,13 +110,30 @@ inline size_t decode_lds_bytes(int n_pad, int G, int D, int NT, int R, int cps, 
   const size_t lg = (size_t)G * (n_pad + 4), om = (size_t)(NT / 64) * G * D;
   const size_t cpt = (size_t)turn_cols_padded(cps);
   size_t fl = (lg > om ? lg : om) + (size_t)R * cpt /*stage*/ + cpt /*turn*/ + 16 * 8 * 2 + 16 * 3 + 16 + 8 + 16;
-  if (T > 1) fl += 2 * (size_t)CsP /*scores, positions*/ + 2 * 3 * 16 /*per-wave minima, two sets*/;
+  if (T > 1) fl += 2 * (size_t)CsP /*scores, positions*/ + 2 * 3 * 16 /*per-wave minima, two sets*/ + (size_t)n_pad / 32 /*free-slot bits*/;
   return fl * 4;
 }
 
 // slots below the high-water mark hold a token (or, under the coarse schedule, are free again: those are masked
-// by their position, -1, where the weights are formed)
+// through a bit map of the free slots, see free_slot_bits)
 __device__ inline bool slot_valid(int j, int n_used) { return j < n_used; }
+
+// Coarse schedule: the slots a selection has freed and no token has taken yet still hold their old keys.  Their
+// logits must not take part in the softmax at all (not even in its maximum), so the workgroup keeps one bit per slot
+// in LDS: thread i makes word i from the unit's list of free slots (at most T - 1 <= 63 entries, uniform loads).
+// The caller puts a barrier between this and the first use.
+__device__ inline void free_slot_bits(unsigned *bits, int n_pad, const int32_t *holes, int n_holes, int tid, int NT) {
+  for (int i = tid; i < n_pad / 32; i += NT) {
+    unsigned wbits = 0u;
+    for (int k = 0; k < n_holes; ++k) {
+      const int h = holes[k];
+      wbits |= (h >> 5) == i ? 1u << (h & 31) : 0u;
+    }
+    bits[i] = wbits;
+  }
+}
+// bit i of the result: slot j0 + i is free (j0 a multiple of 4)
+__device__ inline unsigned free_bits4(const unsigned *bits, int j0) { return (bits[j0 >> 5] >> (j0 & 31)) & 15u; }
 
 // 16-byte global load; STREAM: with the non-temporal hint (the line is not kept in the caches it passes)
 template <bool STREAM> __device__ inline uint4 ldg16(const void *p) {
@@ -503,6 +520,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   float *Fl = shf + 16;                   // [CsP] fused score per slot (+inf: not a candidate)
   int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP] its position
   float *best2 = (float *)(Pl + (Tev > 1 ? CsP : 0));     // [2][3][16] per-wave minima of the selection rounds
+  [[maybe_unused]] unsigned *hbits = (unsigned *)(best2 + 2 * 3 * 16);  // [n_pad / 32] one bit per free slot
 
   const T *Kb = (const T *)P.K + (size_t)u * n_pad * D;
   const T *Vb = (const T *)P.V + (size_t)u * n_pad * D;
@@ -591,7 +609,11 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   // the slot a free-slot stack hands to the new token, if there is one (coarse schedule)
   int hole_top = -1;
   if constexpr (COARSE) {
-    if (n_holes > 0) hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
+    if (n_holes > 0) {  // (the same for the whole workgroup)
+      hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
+      free_slot_bits(hbits, n_pad, P.holes + (size_t)u * Tev, n_holes, tid, NT);
+      lds_barrier();
+    }
   }
   // ---- the waves rebuild the columns whose turn it is, a group of columns each
   TurnRebuild tr;
@@ -648,6 +670,13 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
           for (int i = 0; i < 4; ++i) {
             const int j = tile * 16 + 4 * kq + i;
             l4[i] = slot_valid(j, n_used) ? acc[i] * P.scale_log2 : -INFINITY;
+          }
+          if constexpr (COARSE) {
+            if (n_holes > 0) {
+              const unsigned fb = free_bits4(hbits, tile * 16 + 4 * kq);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) l4[i] = (fb >> i) & 1u ? -INFINITY : l4[i];
+            }
           }
           mx[0] = fmaxf(fmaxf(mx[0], fmaxf(l4[0], l4[1])), fmaxf(l4[2], l4[3]));
           *(float4 *)(lg + (size_t)head * lgs + tile * 16 + 4 * kq) = make_float4(l4[0], l4[1], l4[2], l4[3]);
@@ -734,6 +763,9 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       for (int i = 0; i < UNR; ++i) {
         const int j = tile * RPT + i * RPL + rowsub;
         ok[i] = slot_valid(j, n_used);
+        if constexpr (COARSE) {
+          if (n_holes > 0 && ok[i]) ok[i] = !((hbits[j >> 5] >> (j & 31)) & 1u);
+        }
         if (ok[i]) r[i] = ((const uint4 *)(Kb + (size_t)j * D))[chunk];
       }
 #pragma unroll
@@ -812,20 +844,11 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
     for (int jq = tid; jq < nq; jq += NT) {
-      // coarse schedule: slots a selection has freed and no token has taken yet still hold their old key; their
-      // weight is zero (the maximum above may include their logit: any reference does for a softmax)
-      [[maybe_unused]] int4 hp = make_int4(0, 0, 0, 0);
-      if constexpr (COARSE) {
-        if (n_holes > 0) hp = *(const int4 *)(posu + 4 * jq);
-      }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
         l.x = exp2_native(l.x - M[g]); l.y = exp2_native(l.y - M[g]); l.z = exp2_native(l.z - M[g]); l.w = exp2_native(l.w - M[g]);
-        if constexpr (COARSE) {
-          l.x = hp.x < 0 ? 0.f : l.x; l.y = hp.y < 0 ? 0.f : l.y; l.z = hp.z < 0 ? 0.f : l.z; l.w = hp.w < 0 ? 0.f : l.w;
-        }
         *pl = l;
         zs[g] += (l.x + l.y) + (l.z + l.w);
       }

@@ -63,7 +63,7 @@ inline size_t decode_split_lds_bytes(int bps, int G, int D, int R, int cps, int 
   const size_t lgA = (size_t)G * (bps * 32 + 4), omA = (size_t)SPLIT_NW * G * D;
   const size_t a = (lgA > omA ? lgA : omA) + 2 * SPLIT_NW * 8 + 16;
   size_t b = (size_t)R * cpt + cpt + 3 * 16 + 16 + 16 + 3 * SPLIT_MAX * 8 + 4 * 8;
-  if (T > 1) b += 2 * (size_t)CsP + 2 * 3 * 16;
+  if (T > 1) b += 2 * (size_t)CsP + 2 * 3 * 16 + (size_t)CsP / 32;  // (CsP = n_pad: one bit per slot)
   return (a + b) * 4;
 }
 
@@ -118,6 +118,7 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   float *Fl = Mgl + 8;                                    // [CsP]   (T > 1 only, as the ones below)
   int *Pl = (int *)(Fl + (Tev > 1 ? CsP : 0));            // [CsP]
   float *best2 = (float *)(Pl + (Tev > 1 ? CsP : 0));     // [2][3][16]
+  unsigned *hbits = (unsigned *)(best2 + 2 * 3 * 16);     // [n_pad / 32] one bit per free slot (see free_slot_bits)
 
   // ================= phase A: this workgroup's share =================
   // A wave takes the blocks wave, wave + NW, .. of the share, NB of them in flight at a time (K tile pair and V tile
@@ -173,7 +174,11 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
   // who that is, and the rebuild is a chain of small gathers: every workgroup does it now, under its K/V loads (a
   // few KB per workgroup, from L2 after the first), instead of the merging one alone after everybody else is done.
   int hole_top = -1;
-  if (n_holes > 0) hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
+  if (n_holes > 0) {  // (the same for the whole workgroup)
+    hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
+    free_slot_bits(hbits, n_pad, P.holes + (size_t)u * Tev, n_holes, tid, NT);
+    lds_barrier();
+  }
   // the rebuild's loads (one batch: a lane's whole chunk of rows) go out now, are consumed after the K loop
   TurnRebuildT<SPLIT_RB> tr;
   float rbv[SPLIT_RB];
@@ -206,6 +211,11 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
             for (int x = 0; x < 4; ++x) {
               const int j = blk * 32 + t * 16 + 4 * kq + x;
               l4[x] = slot_valid(j, n_used) ? acc[x] * P.scale_log2 : -INFINITY;
+            }
+            if (n_holes > 0) {
+              const unsigned fb = free_bits4(hbits, blk * 32 + t * 16 + 4 * kq);
+#pragma unroll
+              for (int x = 0; x < 4; ++x) l4[x] = (fb >> x) & 1u ? -INFINITY : l4[x];
             }
             const float m4 = fmaxf(fmaxf(l4[0], l4[1]), fmaxf(l4[2], l4[3]));
 #pragma unroll
@@ -240,15 +250,10 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
 #pragma unroll
     for (int g = 0; g < G; ++g) zs[g] = 0.f;
     for (int jq = tid; jq < nsl / 4; jq += NT) {
-      // coarse schedule: slots a selection has freed and no token has taken yet still hold their old key: no weight
-      int4 hp = make_int4(0, 0, 0, 0);
-      if (n_holes > 0) hp = *(const int4 *)(posu + j0s + 4 * jq);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float4 *pl = (float4 *)(lg + (size_t)g * lgs + 4 * jq);
         float4 l = *pl;
-        l.x = hp.x < 0 ? -INFINITY : l.x; l.y = hp.y < 0 ? -INFINITY : l.y;
-        l.z = hp.z < 0 ? -INFINITY : l.z; l.w = hp.w < 0 ? -INFINITY : l.w;
         if (!keep) ws_store4(wts, (uint32_t)(g * n_pad + j0s + 4 * jq), l);
         l.x = exp2_native(l.x - mref[g]); l.y = exp2_native(l.y - mref[g]); l.z = exp2_native(l.z - mref[g]); l.w = exp2_native(l.w - mref[g]);
         *pl = l;
