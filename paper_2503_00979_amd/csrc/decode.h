@@ -18,9 +18,9 @@
 //          arithmetic free next to the HBM stream -- the bound stays HBM.
 //   fp32 : row-major K/V, plain fp32 FMAs (small/toy configurations).
 //
-// Timeline of a workgroup: the HBM stream (K tiles, then V tiles) is the critical path; the last wave
-// spends the start of the K pass rebuilding the aggregate state of the columns whose turn it is; the
-// first V tile of every wave is already in flight while the softmax runs.
+// Timeline of a workgroup: the HBM stream (K tiles, then V tiles) is the critical path; some waves (the
+// host says how many) spend the start of the K pass rebuilding the aggregate state of the columns whose
+// turn it is; the first V tile of every wave is already in flight while the softmax runs.
 #pragma once
 #include "common.h"
 

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(KEEP_NT) void decode_keep_kernel(DecodeParams P) {
 
   const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y + P.u0, uio = u - P.io_u0, tid = threadIdx.x;
   const int wave = tid / WAVE, lane = tid % WAVE, head = lane & 15, kq = lane >> 4;
-  const int Cs = P.Cs, R = P.R, n_pad = P.n_pad;
+  const int n_pad = P.n_pad;
 
   float *stg = smem + (size_t)wave * 16 * KEEP_PS;            // [16][KEEP_PS] this wave's weights of one block
   float *scw = smem + (size_t)NW * 16 * KEEP_PS + wave * 16;  // [16] this wave's rescale factors
