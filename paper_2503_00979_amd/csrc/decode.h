@@ -828,6 +828,42 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
 #pragma unroll
     for (int g = 0; g < G; ++g) selfl[g] = shf[1 + g];
   }
+  // ---- the rebuilt aggregates of this step's turn columns (complete in LDS since the barrier above) go out to
+  // their sfx rows: by the waves that have no slots to take in the softmax and record phases below, beside those
+  // phases, if there are such waves; else by everybody after them.  Threads t0, t0 + nthr, .. of the caller's.
+  auto store_turn_columns = [&](int t0, int nthr) {
+    const int rz = wm1, r0 = wm1 == 0 ? R - 1 : wm1 - 1;  // (p-1) mod R, (p-2) mod R
+    // row R-1 of the staging area stands for the zeroed row (p-1) mod R
+    if (((cpt | turn_n | turn0) & 3) == 0) {
+      // whole groups of four columns: 16-byte stores (CsP is a multiple of 32, the staging area starts 16-byte aligned)
+      const int q4 = cpt >> 2, total = R * q4, csh = P.cpt_shift;
+      for (int idx = t0; idx < total; idx += nthr) {
+        const int i = csh >= 2 ? idx >> (csh - 2) : idx / q4, c4 = (idx - i * q4) * 4;
+        if (c4 < turn_n) {
+          int r = r0 - i;
+          if (r < 0) r += R;
+          const bool last = i == R - 1;
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (!last) v = *(const float4 *)(stage + (size_t)i * cpt + c4);
+          *(float4 *)(sfxu + (size_t)(last ? rz : r) * CsP + turn0 + c4) = v;
+        }
+      }
+    } else {
+      const int total = R * cpt, csh = P.cpt_shift;
+      for (int idx = t0; idx < total; idx += nthr) {
+        const int i = csh >= 0 ? idx >> csh : idx / cpt, cc = idx - i * cpt;
+        if (cc < turn_n) {
+          int r = r0 - i;
+          if (r < 0) r += R;
+          const bool last = i == R - 1;
+          sfxu[(size_t)(last ? rz : r) * CsP + turn0 + cc] = last ? 0.f : stage[idx];
+        }
+      }
+    }
+  };
+  const int busy_waves = (nq + WAVE - 1) / WAVE;  // waves that hold slots in the phases below (4 slots a thread)
+  const bool helpers = turn_n > 0 && busy_waves < NW;
+  if (helpers && wave >= busy_waves) store_turn_columns(tid - busy_waves * WAVE, (NW - busy_waves) * WAVE);
   // ---- softmax: exact max, sum, weights (4 slots per thread and head at a time)
   float M[G], inv[G], pself[G];
   {
@@ -947,21 +983,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   }
   wave_argmin(bF, bP, bC);
   if (lane == 0) { bestF[wave] = bF; bestP[wave] = bP; bestC[wave] = bC; }
-  // rebuilt aggregates of this step's turn columns go out to their sfx rows
-  if (turn_n > 0) {
-    const int rz = wm1, r0 = wm1 == 0 ? R - 1 : wm1 - 1;  // (p-1) mod R, (p-2) mod R
-    const int total = R * cpt;  // row R-1 of the staging area stands for the zeroed row (p-1) mod R
-    const int csh = P.cpt_shift;
-    for (int idx = tid; idx < total; idx += NT) {
-      const int i = csh >= 0 ? idx >> csh : idx / cpt, cc = idx - i * cpt;
-      if (cc < turn_n) {
-        int r = r0 - i;
-        if (r < 0) r += R;
-        const bool last = i == R - 1;
-        sfxu[(size_t)(last ? rz : r) * CsP + turn0 + cc] = last ? 0.f : stage[idx];
-      }
-    }
-  }
+  if (turn_n > 0 && !helpers) store_turn_columns(tid, NT);
   lds_barrier();
   if (CLK && P.dbgT && tid == 0) P.dbgT[(size_t)u * 8 + 2] = wall_clock64();
 
