@@ -442,8 +442,11 @@ __device__ __forceinline__ void coarse_select(const StepTail<T> &c) {
 
 // The new token takes its slot: K, V, position (the slot's aggregates are the former occupant's: record4 ignores
 // the new part at the next step and the old part until the column's next turn); the unit's counters move on.
-template <typename T, int D, bool CLK>
-__device__ __forceinline__ void commit_step(const StepTail<T> &c) {
+// PRE: the caller has already loaded this thread's piece of the new token's key (kpre: threads 0 .. D/EPL-1) and of its
+// value (vpre; bf16 caches: the element of channel NT-1-tid in .x; fp32: the piece of threads 64 .. 64+D/EPL-1)
+template <typename T, int D, bool CLK, bool PRE = false>
+__device__ __forceinline__ void commit_step(const StepTail<T> &c, uint4 kpre = uint4{0u, 0u, 0u, 0u},
+                                            uint4 vpre = uint4{0u, 0u, 0u, 0u}) {
   const DecodeParams &P = c.P;
   const int u = c.u, tid = c.tid, NT = c.NT, n_pad = c.n_pad, p = c.p, w = c.w;
   int *sh = c.sh;
@@ -454,13 +457,15 @@ __device__ __forceinline__ void commit_step(const StepTail<T> &c) {
   T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
   constexpr int PCS = D / EPL;  // 16-byte pieces per row
   if (tid < PCS)                // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
-    *(uint4 *)(Kw_ + L::k_off(dest, tid * EPL)) = ((const uint4 *)c.knew)[tid];
+    *(uint4 *)(Kw_ + L::k_off(dest, tid * EPL)) = PRE ? kpre : ((const uint4 *)c.knew)[tid];
   if constexpr (L::tiled) {
     // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
-    for (int ch = NT - 1 - tid; ch < D; ch += NT) ((uint16_t *)Vw_)[L::v_off(dest, ch)] = ((const uint16_t *)c.vnew)[ch];
+    // (workgroups have at least D threads: one element a thread)
+    for (int ch = NT - 1 - tid; ch < D; ch += NT)
+      ((uint16_t *)Vw_)[L::v_off(dest, ch)] = PRE ? (uint16_t)vpre.x : ((const uint16_t *)c.vnew)[ch];
   } else {
     if (tid >= 64 && tid < 64 + PCS)
-      *(uint4 *)(Vw_ + L::v_off(dest, (tid - 64) * EPL)) = ((const uint4 *)c.vnew)[tid - 64];
+      *(uint4 *)(Vw_ + L::v_off(dest, (tid - 64) * EPL)) = PRE ? vpre : ((const uint4 *)c.vnew)[tid - 64];
   }
   if (tid == 0) {
     c.posu[dest] = p;
@@ -613,6 +618,24 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
       hole_top = P.holes[(size_t)u * Tev + n_holes - 1];
       free_slot_bits(hbits, n_pad, P.holes + (size_t)u * Tev, n_holes, tid, NT);
       lds_barrier();
+    }
+  }
+  // ---- what the end of the step needs of the new token: this thread's pieces of its key and value for the commit,
+  // and the value element of the first output element it sums -- asked for now, not behind the V pass
+  constexpr int PCSp = D / EPL;
+  uint4 kpre = {0u, 0u, 0u, 0u}, vpre = kpre;
+  float vn_pre = 0.f;
+  {
+    if (tid < PCSp) kpre = ((const uint4 *)knew)[tid];
+    if constexpr (L::tiled) {
+      if (NT - 1 - tid < D) vpre.x = ((const uint16_t *)vnew)[NT - 1 - tid];
+    } else {
+      if (tid >= 64 && tid < 64 + PCSp) vpre = ((const uint4 *)vnew)[tid - 64];
+    }
+    if (tid < G * D) {
+      const int ch = tid % D;
+      if constexpr (sizeof(T) == 4) vn_pre = ((const float *)vnew)[ch];
+      else vn_pre = __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
     }
   }
   // ---- the waves rebuild the columns whose turn it is, a group of columns each
@@ -1133,9 +1156,11 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
     const int g = idx / D, ch = idx % D;
     float o = 0.f;
     for (int x = 0; x < NW; ++x) o += lg[(size_t)(x * G + g) * D + ch];
-    float vn;
-    if constexpr (sizeof(T) == 4) vn = ((const float *)vnew)[ch];
-    else vn = __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+    float vn = vn_pre;  // (the first element of every thread; the others -- small workgroups -- are fetched here)
+    if (idx != tid) {
+      if constexpr (sizeof(T) == 4) vn = ((const float *)vnew)[ch];
+      else vn = __uint_as_float(((uint32_t)((const uint16_t *)vnew)[ch]) << 16);
+    }
     float psg = 0.f;
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) psg = gg == g ? pself[gg] : psg;
@@ -1146,7 +1171,7 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
   // ---- selection among more than C+1 candidates (coarse schedule), commit: shared with the split kernel
   StepTail<T> tc{P, u, tid, NT, NW, wave, lane, n_pad, n_used, p, w, Tev, sh, Fl, Pl, best2, nwu, posu, knew, vnew};
   if constexpr (COARSE) coarse_select<T, D>(tc);
-  commit_step<T, D, CLK>(tc);
+  commit_step<T, D, CLK, true>(tc, kpre, vpre);
 }
 
 // Register budgets.  The compiler version this is built with places spill stores at the top of the block
