@@ -428,7 +428,7 @@ __device__ __forceinline__ void coarse_select(const StepTail<T> &c) {
       f = INFINITY; bp = -1; bc = -1;
       if (lane < NW) { f = bF[lane]; bp = bPp[lane]; bc = bCc[lane]; }
       wave_argmin(f, bp, bc);
-      if (bc >= 0 && bc % NT == tid) Fl[bc] = INFINITY;
+      if (bc >= 0 && bc % NT == tid) { Fl[bc] = INFINITY; Pl[bc] = -1; }
       if (tid == 0 && bc >= 0) {
         evl[it] = bp;
         posu[bc] = -1;
@@ -453,22 +453,23 @@ __device__ __forceinline__ void commit_step(const StepTail<T> &c, uint4 kpre = u
   using L = Layout<T, D>;
   constexpr int EPL = Elem<T>::EPL;
   const int dest = sh[2];
+  const bool okd = (unsigned)dest < (unsigned)n_pad;  // (always; nothing is ever written outside the unit's slots)
   T *Kw_ = (T *)P.K + (size_t)u * n_pad * D;
   T *Vw_ = (T *)P.V + (size_t)u * n_pad * D;
   constexpr int PCS = D / EPL;  // 16-byte pieces per row
-  if (tid < PCS)                // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
+  if (okd && tid < PCS)         // K: 16-byte pieces exist in both layouts (8 or 4 consecutive channels)
     *(uint4 *)(Kw_ + L::k_off(dest, tid * EPL)) = PRE ? kpre : ((const uint4 *)c.knew)[tid];
   if constexpr (L::tiled) {
     // V: one element per (slot, channel) in tile order; starts with the last threads, the K pieces took the first
     // (workgroups have at least D threads: one element a thread)
-    for (int ch = NT - 1 - tid; ch < D; ch += NT)
+    for (int ch = NT - 1 - tid; okd && ch < D; ch += NT)
       ((uint16_t *)Vw_)[L::v_off(dest, ch)] = PRE ? (uint16_t)vpre.x : ((const uint16_t *)c.vnew)[ch];
   } else {
-    if (tid >= 64 && tid < 64 + PCS)
+    if (okd && tid >= 64 && tid < 64 + PCS)
       *(uint4 *)(Vw_ + L::v_off(dest, (tid - 64) * EPL)) = PRE ? vpre : ((const uint4 *)c.vnew)[tid - 64];
   }
   if (tid == 0) {
-    c.posu[dest] = p;
+    if (okd) c.posu[dest] = p;
     int32_t *m = P.meta + (size_t)u * META;
     m[0] = sh[4];
     m[1] = p + 1;
@@ -968,9 +969,12 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
         if (pj[i] == p - 1) nwo[i] = 0.f;  // born at the last step: what is stored is the former occupant's
         nwo[i] = fuse2(fusion, nwo[i], S[i]);
         const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
-        const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
+        // (a score that is not a number -- the caller's q or k were not -- counts as the largest: a candidate is
+        // then still found, by position, and the cache keeps its structure)
+        const float Fv = fuse2(fusion, so, nwo[i]);
+        const float F = cand && Fv == Fv ? Fv : INFINITY;
         if (cand && P.dbgF) P.dbgF[(size_t)u * n_pad + j] = F;
-        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = pj[i]; }
+        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = cand ? pj[i] : -1; }  // (position -1: never taken)
         if (cand && cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         ++rem;
         if (rem == cps) { rem = 0; ++phi; }
@@ -1029,9 +1033,10 @@ __device__ __forceinline__ void decode_fused_body(const DecodeParams &P) {
         } else if (n_holes > 0) {
           dest = hole_top; nu = n_used; nh = n_holes - 1;
         }
-      } else if (older > Cs) {
+      } else if (older > Cs && bc >= 0) {
         dest = bc; evicted = bp; nu = n_used;
       }
+      if (dest >= n_pad) { dest = -1; nu = n_used; }  // (a full cache with nothing to evict cannot happen: no write then)
       sh[2] = dest;
       sh[3] = evicted;
       sh[4] = nu;

@@ -443,9 +443,10 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
         if (pj[i] == p - 1) nwo[i] = 0.f;  // born at the last step: what is stored is the former occupant's
         nwo[i] = fuse2(fusion, nwo[i], S4[i]);
         const bool cand = j < n_used && pj[i] >= 0 && pj[i] <= p - R;
-        const float F = cand ? fuse2(fusion, so, nwo[i]) : INFINITY;
+        const float Fv = fuse2(fusion, so, nwo[i]);
+        const float F = cand && Fv == Fv ? Fv : INFINITY;  // (not a number: counts as the largest, see decode.h)
         if (cand && P.dbgF) P.dbgF[(size_t)u * n_pad + j] = F;
-        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = pj[i]; }
+        if (sel_step && j < n_used) { Fl[j] = F; Pl[j] = cand ? pj[i] : -1; }
         if (cand && cand_before(bF, bP, F, pj[i])) { bF = F; bP = pj[i]; bC = j; }
         ++rem;
         if (rem == cps) { rem = 0; ++phi; }
@@ -520,9 +521,10 @@ __global__ __launch_bounds__(SPLIT_NT) void decode_split_kernel(DecodeParams P) 
         } else if (n_holes > 0) {
           dest = hole_top; nu = n_used; nh = n_holes - 1;
         }
-      } else if (older > Cs) {
+      } else if (older > Cs && bc >= 0) {
         dest = bc; evicted = bp; nu = n_used;
       }
+      if (dest >= n_pad) { dest = -1; nu = n_used; }
       sh[2] = dest;
       sh[3] = evicted;
       sh[4] = nu;

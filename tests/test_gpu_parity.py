@@ -825,6 +825,35 @@ def test_rerun_is_bit_identical(oracle_lib):
     assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
 
 
+@pytest.mark.parametrize("T", [1, 4])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_queries_that_are_not_numbers_leave_the_cache_in_order(dtype, T):
+    """A query of NaNs (a diverged model) makes every score of that step NaN.  The step must still evict by the
+    rules' last resort -- position -- so that the cache keeps its structure: C older tokens and the R most recent,
+    every position once; and the steps after it run as usual."""
+    from paper_2503_00979_amd import binding
+    wl = inputs.small_workload(17000 + T, L=2, B=2, M=8, Mkv=2, d=128, dtype=dtype, C=24, R=8, fusion="sum",
+                               prompt_lens=(60, 37), steps=40, evict_every=T)
+    g = binding.MorphKV.from_workload(wl, DEV)
+    Qw, K, V = wl.prompt()
+    g.prefill_select(Qw.to(DEV), K.to(DEV), V.to(DEV), wl.prompt_len_tensor().numpy())
+    for t in range(wl.steps):
+        q, k, v = (x.to(DEV) for x in wl.decode_inputs(t))
+        if t in (12, 13, 29):
+            q = torch.full_like(q, float("nan"))
+        g.decode_step(q, k, v)
+        pos, n_old = g.export_positions()
+        pos, n_old = pos.cpu().numpy(), n_old.cpu().numpy()
+        for u in range(pos.shape[0]):
+            b = (u // wl.n_kv_heads) % wl.batch
+            last = wl.prompt_lens[b] + t
+            held = np.sort(pos[u][pos[u] >= 0])
+            assert len(np.unique(held)) == len(held) and held[-1] == last
+            assert np.array_equal(held[held > last - wl.R], np.arange(last - wl.R + 1, last + 1))
+            assert n_old[u] == len(held) - wl.R and wl.C <= n_old[u] <= wl.C + max(T, 1) - 1
+    torch.cuda.synchronize()
+
+
 def test_error_paths(oracle_lib):
     from paper_2503_00979_amd import binding
     with pytest.raises(binding.MorphKVError) as e:
