@@ -160,7 +160,10 @@ int morphkv_prefill_attend_select(morphkv_handle *h, const void *Q, const void *
  *  k_new  device [L][B][M'][d]   its key   (enters the window after the step)
  *  v_new  device [L][B][M'][d]   its value
  *  out    device [L][B][M][d]    fp32 attention output over the resident cache plus the token itself
- * Inputs are only read; cache and scores_ring are updated in place. */
+ * Inputs are only read; cache and scores_ring are updated in place.  Values are not checked: a query or key that
+ * is not a number gives an output that is not one, and scores that are not numbers count as the largest (such a
+ * step evicts by position alone); the cache keeps its structure -- C older tokens and the R most recent, every
+ * position once -- whatever the values are. */
 int morphkv_decode_step(morphkv_handle *h, const void *q, const void *k_new, const void *v_new, float *out,
                         void *stream /* hipStream_t */);
 
